@@ -1,0 +1,180 @@
+"""CPU oracle for the Zeno aggregation step (arXiv 1805.10032).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain, float64 statement of
+what the hot path computes.  Only the tests, the smoke check and the
+``cpu_baseline`` leg of the benchmark may call it; the product path never does.
+It shares no code with the HIP library and imports nothing from the package.
+
+Everything is written one candidate at a time, in the order of the paper's
+definitions, with the perturbed parameter vector ``x - gamma*u`` materialised.
+No blocking, fusion or reordering.
+
+Parameter layout (the interface convention, not part of the paper): a parameter
+vector p of length d is, for l = 1..L, the weight matrix W_l stored row-major as
+[dims[l] x dims[l-1]] (out x in) followed, if the model has biases, by the bias
+b_l[dims[l]].  Candidate gradients use the same layout.
+
+Pins (see tests/test_oracle_*.py): least-squares closed form, b=0 equals Mean,
+b=m-1 equals the arg-max row, Lemma 1 (bounded score), the Assumption 2
+sandwich for convex losses, ln C at zero parameters, library cross-checks for
+logsumexp / mean / median / an MLP forward, brute-force subset enumeration,
+the 1-D example in the Discussion section for Mean / Median / Krum, and the
+(m+1) forward-evaluation count of the Discussion section.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+LOSS_SQUARED = "squared"
+LOSS_SOFTMAX_CE = "softmax_ce"
+
+# Number of calls of f_r since the last reset; the Discussion section prices
+# Zeno at (m+1) loss evaluations of n_r samples each.
+forward_evaluations = 0
+
+
+def num_params(dims, has_bias):
+    """d for a chain of linear layers dims[0] -> ... -> dims[L]."""
+    d = 0
+    for l in range(1, len(dims)):
+        d += dims[l] * dims[l - 1]
+        if has_bias:
+            d += dims[l]
+    return d
+
+
+def unflatten(p, dims, has_bias):
+    """Split a flat parameter vector into [(W_l, b_l)] following the layout above."""
+    p = np.asarray(p, dtype=np.float64)
+    assert p.ndim == 1 and p.shape[0] == num_params(dims, has_bias)
+    layers = []
+    off = 0
+    for l in range(1, len(dims)):
+        n_out, n_in = dims[l], dims[l - 1]
+        W = p[off:off + n_out * n_in].reshape(n_out, n_in)
+        off += n_out * n_in
+        if has_bias:
+            bias = p[off:off + n_out]
+            off += n_out
+        else:
+            bias = np.zeros(n_out, dtype=np.float64)
+        layers.append((W, bias))
+    return layers
+
+
+def forward(p, dims, has_bias, features):
+    """Model output for every sample: linear layers with ReLU between them and
+    none after the last (Section 3: f(x; z) for the model classes of the
+    synthetic workloads)."""
+    h = np.asarray(features, dtype=np.float64)
+    layers = unflatten(p, dims, has_bias)
+    for l, (W, bias) in enumerate(layers):
+        z = h @ W.T + bias
+        h = np.maximum(z, 0.0) if l + 1 < len(layers) else z
+    return h
+
+
+def sample_losses(z, loss, labels=None, targets=None):
+    """Per-sample loss f(x; z_k) from the model output z [n_r x C]."""
+    if loss == LOSS_SQUARED:
+        y = np.asarray(targets, dtype=np.float64)
+        return 0.5 * (z[:, 0] - y) ** 2
+    if loss == LOSS_SOFTMAX_CE:
+        lab = np.asarray(labels, dtype=np.int64)
+        zmax = np.max(z, axis=1)
+        lse = zmax + np.log(np.sum(np.exp(z - zmax[:, None]), axis=1))
+        return lse - z[np.arange(z.shape[0]), lab]
+    raise ValueError(loss)
+
+
+def f_r(p, dims, has_bias, loss, features, labels=None, targets=None):
+    """f_r(p) = (1/n_r) sum_k f(p; z_k)   (Definition 2)."""
+    global forward_evaluations
+    forward_evaluations += 1
+    z = forward(p, dims, has_bias, features)
+    with np.errstate(invalid="ignore", over="ignore"):
+        return float(np.mean(sample_losses(z, loss, labels, targets)))
+
+
+def score(x, u, gamma, rho, f0, dims, has_bias, loss, features, labels=None, targets=None):
+    """Score_{gamma,rho}(u, x) = f_r(x) - f_r(x - gamma u) - rho ||u||^2
+    (Definition 2); f0 = f_r(x) is evaluated once by the caller and shared."""
+    x = np.asarray(x, dtype=np.float64)
+    u = np.asarray(u, dtype=np.float64)
+    with np.errstate(invalid="ignore", over="ignore"):
+        xp = x - gamma * u
+        fi = f_r(xp, dims, has_bias, loss, features, labels, targets)
+        return f0 - fi - rho * float(np.dot(u, u))
+
+
+def scores(x, G, gamma, rho, dims, has_bias, loss, features, labels=None, targets=None,
+           rows=None):
+    """Scores of the candidates G[i] (all rows, or only those listed in rows)."""
+    f0 = f_r(np.asarray(x, dtype=np.float64), dims, has_bias, loss, features, labels, targets)
+    idx = range(G.shape[0]) if rows is None else rows
+    return np.array([score(x, G[i], gamma, rho, f0, dims, has_bias, loss, features,
+                           labels, targets) for i in idx], dtype=np.float64)
+
+
+def select(score_values, b):
+    """Indices of the m-b highest scores (Definition 3), reported ascending.
+
+    Reading where the paper is silent: ties go to the lower index, a NaN score
+    ranks as minus infinity."""
+    s = np.asarray(score_values, dtype=np.float64)
+    m = s.shape[0]
+    assert 0 <= b < m
+    key = np.where(np.isnan(s), -np.inf, s)
+    order = sorted(range(m), key=lambda i: (-key[i], i))
+    return np.array(sorted(order[:m - b]), dtype=np.int64)
+
+
+def zeno_aggregate(G, score_values, b):
+    """Zeno_b: average of the m-b highest-scoring candidates (Definition 3)."""
+    sel = select(score_values, b)
+    acc = np.zeros(G.shape[1], dtype=np.float64)
+    for i in sel:
+        acc += np.asarray(G[i], dtype=np.float64)
+    return acc / float(len(sel)), sel
+
+
+def mean(G):
+    """Mean aggregation rule (Section 6.1.1)."""
+    acc = np.zeros(G.shape[1], dtype=np.float64)
+    for i in range(G.shape[0]):
+        acc += np.asarray(G[i], dtype=np.float64)
+    return acc / float(G.shape[0])
+
+
+def median(G):
+    """Marginal median (Definition 4).  Reading for even m: the midpoint of the
+    two middle values.  NaN sorts above +inf."""
+    G = np.asarray(G, dtype=np.float64)
+    m = G.shape[0]
+    srt = np.sort(G, axis=0)  # NaN last
+    if m % 2 == 1:
+        return srt[m // 2].copy()
+    with np.errstate(invalid="ignore", over="ignore"):
+        return 0.5 * (srt[m // 2 - 1] + srt[m // 2])
+
+
+def krum(G, b):
+    """Krum_b (Definition 5): the candidate with the smallest sum of squared
+    distances to its m-b-2 nearest neighbours; ties go to the lower index."""
+    G = np.asarray(G, dtype=np.float64)
+    m = G.shape[0]
+    assert m - b - 2 >= 1
+    best, best_val = -1, np.inf
+    for i in range(m):
+        dist = sorted(float(np.sum((G[i] - G[j]) ** 2)) for j in range(m) if j != i)
+        val = sum(dist[:m - b - 2])
+        if val < best_val:
+            best, best_val = i, val
+    return G[best].copy(), best
+
+
+def zeno_step(x, G, b, gamma, rho, dims, has_bias, loss, features, labels=None, targets=None):
+    """One whole aggregation: scores, selection, average."""
+    s = scores(x, G, gamma, rho, dims, has_bias, loss, features, labels, targets)
+    out, sel = zeno_aggregate(G, s, b)
+    return s, sel, out
