@@ -1,0 +1,145 @@
+/*
+ * zeno.h -- C ABI of the MI355X (gfx950) Zeno aggregation library.
+ *
+ * The library implements the server-side aggregation step of
+ * "Zeno: Distributed Stochastic Gradient Descent with Suspicion-based
+ * Fault-tolerance" (arXiv 1805.10032):
+ *
+ *   Definition 2 (Stochastic Descendant Score)
+ *       Score_{gamma,rho}(u, x) = f_r(x) - f_r(x - gamma u) - rho ||u||^2,
+ *       f_r = mean loss over the n_r samples the server drew for this iteration.
+ *   Definition 3 (Suspicion-based Aggregation, Zeno_b)
+ *       average of the m-b candidates with the highest scores.
+ *   Section 6.1.1 baselines: Mean, and Definition 4 (marginal Median).
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ * Pointers.  Arguments marked DEVICE point to HIP device memory of the current
+ *   device, owned by the caller, at least 4-byte aligned.  Arguments marked
+ *   HOST are ordinary host pointers and are read before the call returns.
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
+ *   stream).  Every call only enqueues work on that stream and returns; no call
+ *   synchronises with the host, reads device results on the host, or allocates
+ *   or frees device memory.  Scratch memory is the caller's `workspace`.
+ * Parameter layout.  A parameter vector of the model (x, and every row of the
+ *   candidate matrix G) is, for l = 1..L: the weight matrix W_l stored
+ *   row-major as [dims[l] x dims[l-1]] (out x in), followed, if has_bias, by
+ *   the bias b_l[dims[l]].  d = zeno_model_num_params().
+ * Candidate matrix.  G is [m x d] row-major with leading dimension d.  d need
+ *   not be a multiple of 4; rows may therefore be only 4-byte aligned.
+ * Errors.  Every call returns a zeno_status_t; nothing is thrown across the
+ *   ABI.  Argument errors are detected on the host before anything is
+ *   enqueued, so a failed call leaves the outputs untouched.
+ * Non-finite data.  "Arbitrary values" (Section 3, Eq. 1) include NaN/Inf
+ *   rows: they propagate through the forward pass, a NaN score ranks as
+ *   -infinity, ties go to the lower index, and the median sorts NaN above +Inf.
+ */
+#ifndef ZENO_H_
+#define ZENO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ZENO_MAX_LAYERS 8
+#define ZENO_MAX_CANDIDATES 1024
+
+typedef enum {
+  ZENO_OK = 0,
+  ZENO_ERR_INVALID_ARG = 1, /* NULL/misaligned pointer, m<1, m>1024, b<0, b>=m, n_r<1, bad gamma/rho/dims */
+  ZENO_ERR_UNSUPPORTED = 2, /* a size beyond what the kernels cover (see each call) */
+  ZENO_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned (256 B) or smaller than the query says */
+  ZENO_ERR_DEVICE = 4       /* a HIP launch failed */
+} zeno_status_t;
+
+typedef enum {
+  ZENO_LOSS_SQUARED = 0,   /* f(x; (a, y)) = 1/2 (model(a) - y)^2, output width 1 */
+  ZENO_LOSS_SOFTMAX_CE = 1 /* f(x; (a, y)) = logsumexp(model(a)) - model(a)[y], natural log */
+} zeno_loss_t;
+
+typedef enum {
+  ZENO_FWD_FP32 = 0, /* forward-pass products in fp32 (fp32 matrix cores), fp32 accumulate */
+  ZENO_FWD_BF16 = 1  /* matrix operands rounded to bf16, fp32 accumulate */
+} zeno_fwd_dtype_t;
+
+/* Model whose loss the score evaluates: L linear layers, ReLU between them,
+ * none after the last.  HOST struct, copied by zeno_model_create. */
+typedef struct {
+  int32_t n_layers;                  /* L, 1..ZENO_MAX_LAYERS */
+  int32_t dims[ZENO_MAX_LAYERS + 1]; /* dims[0] = input width ... dims[L] = output width, each >= 1 */
+  int32_t has_bias;                  /* 0 or 1 */
+  int32_t loss;                      /* zeno_loss_t; ZENO_LOSS_SQUARED requires dims[L] == 1 */
+  int32_t fwd;                       /* zeno_fwd_dtype_t */
+} zeno_model_desc_t;
+
+typedef struct zeno_model zeno_model_t; /* opaque HOST object owned by the library */
+
+/* The n_r samples the server drew for this iteration (Algorithm 1, server
+ * side: drawn after the candidates arrived; one batch for all m candidates). */
+typedef struct {
+  int32_t n_r;             /* >= 1 */
+  const float* features;   /* DEVICE [n_r x dims[0]] row-major */
+  const int32_t* labels;   /* DEVICE [n_r], softmax-CE only, 0 <= label < dims[L] */
+  const float* targets;    /* DEVICE [n_r], squared loss only */
+} zeno_batch_t;
+
+/* Create / destroy the host-side model object.  `out` receives the handle.
+ * Errors: INVALID_ARG for NULL pointers, n_layers or dims out of range, a
+ * squared loss with output width != 1, unknown enum values. */
+zeno_status_t zeno_model_create(const zeno_model_desc_t* desc, zeno_model_t** out);
+void zeno_model_destroy(zeno_model_t* model);
+
+/* d, the length of a parameter vector in the layout above. */
+int64_t zeno_model_num_params(const zeno_model_t* model);
+
+/* Bytes of DEVICE scratch that zeno_score needs for m candidates and a batch of
+ * n_r samples (activations of the m+1 forward passes, partial norms).  Returns
+ * 0 for invalid arguments. */
+size_t zeno_score_workspace_bytes(const zeno_model_t* model, int32_t m, int32_t n_r);
+
+/* Definition 2 for every row of G:
+ *   scores[i] = f_r(x) - f_r(x - gamma G[i]) - rho ||G[i]||^2,  i = 0..m-1.
+ * f_r(x) is evaluated once and shared (Section 6.7: (m+1) loss evaluations).
+ * The perturbed parameters x - gamma G[i] are never materialised: each row of
+ * G is read from memory once, and what is propagated through the layers is the
+ * change of the activations relative to the forward pass at x, so that the
+ * difference f_r(x) - f_r(x - gamma u) is formed without cancellation.
+ *   x       DEVICE [d]            current parameters
+ *   G       DEVICE [m x d]        candidate gradient estimators, 1 <= m <= 1024
+ *   batch   HOST struct with DEVICE pointers
+ *   gamma   learning rate, finite, >= 0;  rho  finite, >= 0 (rho = 0 is the
+ *           appendix's choice for mu >= 0)
+ *   scores  DEVICE [m] fp32 out
+ *   workspace DEVICE, 256-byte aligned, >= zeno_score_workspace_bytes(model, m, n_r)
+ * Batches of more than 128 samples are processed in passes of 128, each pass
+ * reading G again. */
+zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float* G, int32_t m,
+                         const zeno_batch_t* batch, float gamma, float rho, float* scores,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Definition 3: out = (1/(m-b)) * sum of the m-b rows of G with the highest
+ * scores, 0 <= b < m (b = 0 is the Mean).  The selection runs on the device
+ * from `scores` (no host round trip); rows are summed in ascending index order
+ * in fp64 and rounded once to fp32.
+ *   scores   DEVICE [m] (as written by zeno_score)
+ *   out      DEVICE [d]
+ *   selected DEVICE [m-b] int32 out, ascending indices of the chosen rows; may be NULL */
+zeno_status_t zeno_aggregate(const float* G, const float* scores, int32_t m, int64_t d, int32_t b,
+                             float* out, int32_t* selected, void* stream);
+
+/* Mean baseline (Section 6.1.1): out[j] = (1/m) sum_i G[i][j]. */
+zeno_status_t zeno_mean(const float* G, int32_t m, int64_t d, float* out, void* stream);
+
+/* Marginal median (Definition 4): out[j] = median_i G[i][j]; for even m the
+ * midpoint of the two middle values.  UNSUPPORTED for m > 128. */
+zeno_status_t zeno_median(const float* G, int32_t m, int64_t d, float* out, void* stream);
+
+const char* zeno_status_string(zeno_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZENO_H_ */

@@ -178,3 +178,82 @@ def zeno_step(x, G, b, gamma, rho, dims, has_bias, loss, features, labels=None, 
     s = scores(x, G, gamma, rho, dims, has_bias, loss, features, labels, targets)
     out, sel = zeno_aggregate(G, s, b)
     return s, sel, out
+
+
+# ---------------------------------------------------------------------------
+# bf16-operand variant (workloads whose forward passes use bf16 operands with
+# fp32 accumulation).  The paper fixes no precision; this is the rounding
+# contract of the bf16 forward mode, stated in words and written out plainly:
+#
+#   * every operand of a matrix product is rounded to bfloat16 (round to
+#     nearest, ties to even) first; products are accumulated exactly (float64
+#     here stands for the fp32 accumulator); biases are added unrounded;
+#   * the pass at x computes z0_l = rb(h0_{l-1}) rb(W_l)^T + b_l, h0_l = relu(z0_l),
+#     h0_0 = the batch;
+#   * candidate u is propagated as the CHANGE of the pre-activations,
+#       dz_l = -gamma ( rb(h_{l-1}) rb(U_l)^T + rb(D_{l-1}) rb(W_l)^T + ub_l ),
+#       h_l = relu(z0_l + dz_l),  D_l = (relu(z0_l + dz_l) - relu(z0_l)) (-1/gamma),
+#     with D_0 = 0 and h_0 = the batch.  In exact arithmetic z0_l + dz_l equals the
+#     pre-activation of the model at x - gamma u, so without rounding this is
+#     Definition 2 unchanged;
+#   * loss difference per sample and the final combine as in the exact oracle.
+#
+# Pinned by: exact equality with the float64 oracle when every operand is
+# bf16-representable (tests/test_oracle_bf16.py), and a forward-error bound
+# against the float64 oracle on random inputs.  Beyond that the contract has no
+# external reference ("parity unpinned" applies to the choice of rounding
+# points, not to the arithmetic).
+# ---------------------------------------------------------------------------
+def round_bf16(a):
+    """Nearest bfloat16 (ties to even) of the fp32 rounding of a, as float64."""
+    f = np.ascontiguousarray(np.asarray(a, dtype=np.float32))
+    bits = f.view(np.uint32).astype(np.uint64)
+    rounded = ((bits + 0x7FFF + ((bits >> 16) & 1)) >> 16) << 16
+    out = (rounded & 0xFFFFFFFF).astype(np.uint32).view(np.float32).astype(np.float64)
+    return np.where(np.isnan(f), np.nan, out)
+
+
+def _f32(a):
+    with np.errstate(over="ignore", invalid="ignore"):
+        return np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+
+def scores_bf16(x, G, gamma, rho, dims, has_bias, loss, features, labels=None, targets=None, rows=None):
+    """Scores under the bf16 rounding contract above."""
+    global forward_evaluations
+    rb = round_bf16
+    L = len(dims) - 1
+    layers_x = unflatten(x, dims, has_bias)
+    batch = np.asarray(features, dtype=np.float64)
+    with np.errstate(invalid="ignore", over="ignore"):
+        # pass at x
+        forward_evaluations += 1
+        h0, z0 = [batch], []
+        for l, (W, bias) in enumerate(layers_x):
+            z = _f32(rb(h0[-1]) @ rb(W).T + bias)
+            z0.append(z)
+            if l + 1 < L:
+                h0.append(np.maximum(z, 0.0))
+        base_losses = sample_losses(z0[-1], loss, labels, targets)
+        idx = range(G.shape[0]) if rows is None else rows
+        out = []
+        neg_inv_gamma = _f32(-1.0 / np.float32(gamma)) if gamma > 0 else 0.0
+        for i in idx:
+            forward_evaluations += 1
+            u = np.asarray(G[i], dtype=np.float64)
+            layers_u = unflatten(u, dims, has_bias)
+            h, dprime, dz = batch, None, None
+            for l, ((U, ub), (W, _)) in enumerate(zip(layers_u, layers_x)):
+                acc = rb(h) @ rb(U).T + ub
+                if dprime is not None:
+                    acc = acc + rb(dprime) @ rb(W).T
+                dz = _f32(-np.float64(np.float32(gamma)) * _f32(acc))
+                if l + 1 < L:
+                    zs = _f32(z0[l] + dz)
+                    h_new = np.where(zs <= 0.0, 0.0, zs)
+                    delta = np.where(z0[l] > 0.0, np.where(dz < -z0[l], -z0[l], dz), h_new)
+                    dprime = _f32(delta * neg_inv_gamma)
+                    h = h_new
+            diff = sample_losses(z0[-1] + dz, loss, labels, targets) - base_losses
+            out.append(-float(np.mean(diff)) - rho * float(np.dot(u, u)))
+    return np.array(out, dtype=np.float64)

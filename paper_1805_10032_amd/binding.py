@@ -1,0 +1,215 @@
+"""ctypes binding of the Zeno HIP library (include/zeno.h).
+
+Argument marshalling only: every function takes torch tensors that already
+live on the GPU, passes their device pointers and the current HIP stream to
+the C entry point of the same name, and returns the output tensors.  There is
+no CPU fallback: a missing library or a tensor on the wrong device raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libzeno_hip.so")
+
+ZENO_MAX_LAYERS = 8
+ZENO_MAX_CANDIDATES = 1024
+LOSS = {"squared": 0, "softmax_ce": 1}
+FWD = {"fp32": 0, "bf16": 1}
+STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported size", 3: "workspace", 4: "device"}
+
+EXPORTS = ["zeno_model_create", "zeno_model_destroy", "zeno_model_num_params",
+           "zeno_score_workspace_bytes", "zeno_score", "zeno_aggregate", "zeno_mean",
+           "zeno_median", "zeno_status_string"]
+
+
+class ZenoError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: status {status} ({STATUS.get(int(status), '?')})")
+
+
+class _ModelDesc(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32),
+                ("dims", ctypes.c_int32 * (ZENO_MAX_LAYERS + 1)),
+                ("has_bias", ctypes.c_int32),
+                ("loss", ctypes.c_int32),
+                ("fwd", ctypes.c_int32)]
+
+
+class _Batch(ctypes.Structure):
+    _fields_ = [("n_r", ctypes.c_int32),
+                ("features", ctypes.c_void_p),
+                ("labels", ctypes.c_void_p),
+                ("targets", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
+    """Load the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} is missing: build it with `python -m paper_1805_10032_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    lib.zeno_model_create.argtypes = [ctypes.POINTER(_ModelDesc), ctypes.POINTER(vp)]
+    lib.zeno_model_create.restype = ctypes.c_int
+    lib.zeno_model_destroy.argtypes = [vp]
+    lib.zeno_model_destroy.restype = None
+    lib.zeno_model_num_params.argtypes = [vp]
+    lib.zeno_model_num_params.restype = i64
+    lib.zeno_score_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.zeno_score_workspace_bytes.restype = ctypes.c_size_t
+    lib.zeno_score.argtypes = [vp, vp, vp, i32, ctypes.POINTER(_Batch), f32, f32, vp, vp,
+                               ctypes.c_size_t, vp]
+    lib.zeno_score.restype = ctypes.c_int
+    lib.zeno_aggregate.argtypes = [vp, vp, i32, i64, i32, vp, vp, vp]
+    lib.zeno_aggregate.restype = ctypes.c_int
+    lib.zeno_mean.argtypes = [vp, i32, i64, vp, vp]
+    lib.zeno_mean.restype = ctypes.c_int
+    lib.zeno_median.argtypes = [vp, i32, i64, vp, vp]
+    lib.zeno_median.restype = ctypes.c_int
+    lib.zeno_status_string.argtypes = [ctypes.c_int]
+    lib.zeno_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError(f"{name} must be a CUDA/HIP tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+class ZenoModel:
+    """Host-side model handle (zeno_model_create / zeno_model_destroy)."""
+
+    def __init__(self, dims, has_bias=True, loss="softmax_ce", fwd="fp32"):
+        lib = load_library()
+        desc = _ModelDesc()
+        if not 2 <= len(dims) <= ZENO_MAX_LAYERS + 1:
+            raise ZenoError(1, "ZenoModel")
+        desc.n_layers = len(dims) - 1
+        for i, v in enumerate(dims):
+            desc.dims[i] = int(v)
+        desc.has_bias = int(bool(has_bias))
+        desc.loss = LOSS[loss]
+        desc.fwd = FWD[fwd]
+        handle = ctypes.c_void_p()
+        st = lib.zeno_model_create(ctypes.byref(desc), ctypes.byref(handle))
+        if st != 0:
+            raise ZenoError(st, "zeno_model_create")
+        self._lib = lib
+        self._h = handle
+        self.dims, self.has_bias, self.loss, self.fwd = list(dims), bool(has_bias), loss, fwd
+
+    @property
+    def num_params(self) -> int:
+        return int(self._lib.zeno_model_num_params(self._h))
+
+    def workspace_bytes(self, m: int, n_r: int) -> int:
+        return int(self._lib.zeno_score_workspace_bytes(self._h, int(m), int(n_r)))
+
+    def close(self):
+        if self._h is not None and self._h.value:
+            self._lib.zeno_model_destroy(self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def alloc_workspace(model: ZenoModel, m: int, n_r: int, device=None) -> torch.Tensor:
+    """A byte tensor of the size zeno_score asks for (torch's allocator returns
+    at least 256-byte aligned blocks)."""
+    n = model.workspace_bytes(m, n_r)
+    if n == 0:
+        raise ZenoError(1, "zeno_score_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device or torch.device("cuda", torch.cuda.current_device()))
+
+
+def zeno_score(model: ZenoModel, x, G, features, gamma, rho, *, labels=None, targets=None,
+               scores=None, workspace=None):
+    """scores[i] = f_r(x) - f_r(x - gamma G[i]) - rho ||G[i]||^2  (Definition 2)."""
+    lib = load_library()
+    m, d = int(G.shape[0]), int(G.shape[1])
+    if d != model.num_params or x.numel() != d:
+        raise ValueError("x / G do not match the model's parameter count")
+    n_r = int(features.shape[0])
+    if features.shape[1] != model.dims[0]:
+        raise ValueError("features do not match the model's input width")
+    batch = _Batch()
+    batch.n_r = n_r
+    batch.features = _dev(features, torch.float32, "features")
+    batch.labels = _dev(labels, torch.int32, "labels") if labels is not None else None
+    batch.targets = _dev(targets, torch.float32, "targets") if targets is not None else None
+    if scores is None:
+        scores = torch.empty(m, dtype=torch.float32, device=G.device)
+    if workspace is None:
+        workspace = alloc_workspace(model, m, n_r, G.device)
+    st = lib.zeno_score(model._h, _dev(x, torch.float32, "x"), _dev(G, torch.float32, "G"), m,
+                        ctypes.byref(batch), float(gamma), float(rho),
+                        _dev(scores, torch.float32, "scores"),
+                        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream())
+    if st != 0:
+        raise ZenoError(st, "zeno_score")
+    return scores
+
+
+def zeno_aggregate(G, scores, b, *, out=None, selected=None, want_selected=True):
+    """Zeno_b: mean of the m-b highest-scoring rows (Definition 3).  Returns (out, selected)."""
+    lib = load_library()
+    m, d = int(G.shape[0]), int(G.shape[1])
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=G.device)
+    if selected is None and want_selected and 0 <= b < m:
+        selected = torch.empty(m - b, dtype=torch.int32, device=G.device)
+    st = lib.zeno_aggregate(_dev(G, torch.float32, "G"), _dev(scores, torch.float32, "scores"), m, d, int(b),
+                            _dev(out, torch.float32, "out"),
+                            _dev(selected, torch.int32, "selected") if selected is not None else None,
+                            _stream())
+    if st != 0:
+        raise ZenoError(st, "zeno_aggregate")
+    return out, selected
+
+
+def zeno_mean(G, *, out=None):
+    lib = load_library()
+    m, d = int(G.shape[0]), int(G.shape[1])
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=G.device)
+    st = lib.zeno_mean(_dev(G, torch.float32, "G"), m, d, _dev(out, torch.float32, "out"), _stream())
+    if st != 0:
+        raise ZenoError(st, "zeno_mean")
+    return out
+
+
+def zeno_median(G, *, out=None):
+    lib = load_library()
+    m, d = int(G.shape[0]), int(G.shape[1])
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=G.device)
+    st = lib.zeno_median(_dev(G, torch.float32, "G"), m, d, _dev(out, torch.float32, "out"), _stream())
+    if st != 0:
+        raise ZenoError(st, "zeno_median")
+    return out

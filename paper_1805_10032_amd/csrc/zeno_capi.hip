@@ -1,0 +1,246 @@
+// C ABI of the Zeno library: argument checks, workspace layout and launch
+// sequencing.  Every step of the path runs in the HIP kernels of this library;
+// the host only validates and enqueues.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "zeno_internal.h"
+
+struct zeno_model {
+  zeno_model_desc_t desc;
+  int64_t w_off[ZENO_MAX_LAYERS];  // offset of W_l (l = 0..L-1) inside a parameter vector
+  int64_t b_off[ZENO_MAX_LAYERS];  // offset of b_l, or -1
+  int64_t d;
+};
+
+namespace {
+
+using namespace zeno;
+
+constexpr int kMaxPassRows = 128;  // samples per pass over G (four 32-row accumulator blocks)
+
+inline int pad64(int v) { return (v + 63) / 64 * 64; }
+inline int blocks_for(int rows) { return rows <= 32 ? 1 : (rows <= 64 ? 2 : 4); }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Workspace layout, shared by the size query and the call itself.
+struct Plan {
+  int L, pass_rows, MB, n_pad, esize, P;
+  size_t off_feat, off_hbase[ZENO_MAX_LAYERS], off_z0[ZENO_MAX_LAYERS];
+  size_t off_hc[2], off_dc[2], cand_stride, off_dz, off_norm, off_diff, total;
+};
+
+Plan make_plan(const zeno_model* mdl, int m, int n_r) {
+  Plan p;
+  std::memset(&p, 0, sizeof(p));
+  const zeno_model_desc_t& D = mdl->desc;
+  p.L = D.n_layers;
+  p.pass_rows = n_r < kMaxPassRows ? n_r : kMaxPassRows;
+  p.MB = blocks_for(p.pass_rows);
+  p.n_pad = 32 * p.MB;
+  p.esize = D.fwd == ZENO_FWD_BF16 ? 2 : 4;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  };
+  p.off_feat = take((size_t)p.n_pad * pad64(D.dims[0]) * p.esize);
+  int max_np = 64;
+  for (int l = 0; l < p.L; ++l) {
+    const int N = D.dims[l + 1];
+    p.off_z0[l] = take((size_t)p.pass_rows * N * sizeof(float));
+    if (l + 1 < p.L) {
+      p.off_hbase[l] = take((size_t)p.n_pad * pad64(N) * p.esize);
+      if (pad64(N) > max_np) max_np = pad64(N);
+    }
+    p.P += (pad64(N) + 31) / 32;  // upper bound on the partial-norm slots of this layer
+  }
+  p.cand_stride = align_up((size_t)p.n_pad * max_np * p.esize, 256);
+  if (p.L > 1) {
+    for (int i = 0; i < 2; ++i) p.off_hc[i] = take(p.cand_stride * m);
+    for (int i = 0; i < 2; ++i) p.off_dc[i] = take(p.cand_stride * m);
+  }
+  p.off_dz = take((size_t)m * p.pass_rows * D.dims[p.L] * sizeof(float));
+  p.off_norm = take((size_t)m * p.P * sizeof(double));
+  p.off_diff = take((size_t)m * n_r * sizeof(double));
+  p.total = off;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+zeno_status_t zeno_model_create(const zeno_model_desc_t* desc, zeno_model_t** out) {
+  if (desc == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (desc->n_layers < 1 || desc->n_layers > ZENO_MAX_LAYERS) return ZENO_ERR_INVALID_ARG;
+  for (int l = 0; l <= desc->n_layers; ++l)
+    if (desc->dims[l] < 1) return ZENO_ERR_INVALID_ARG;
+  if (desc->has_bias != 0 && desc->has_bias != 1) return ZENO_ERR_INVALID_ARG;
+  if (desc->loss != ZENO_LOSS_SQUARED && desc->loss != ZENO_LOSS_SOFTMAX_CE) return ZENO_ERR_INVALID_ARG;
+  if (desc->fwd != ZENO_FWD_FP32 && desc->fwd != ZENO_FWD_BF16) return ZENO_ERR_INVALID_ARG;
+  if (desc->loss == ZENO_LOSS_SQUARED && desc->dims[desc->n_layers] != 1) return ZENO_ERR_INVALID_ARG;
+  zeno_model* mdl = new (std::nothrow) zeno_model;
+  if (mdl == nullptr) return ZENO_ERR_DEVICE;
+  mdl->desc = *desc;
+  int64_t off = 0;
+  for (int l = 0; l < desc->n_layers; ++l) {
+    mdl->w_off[l] = off;
+    off += (int64_t)desc->dims[l + 1] * desc->dims[l];
+    mdl->b_off[l] = -1;
+    if (desc->has_bias) {
+      mdl->b_off[l] = off;
+      off += desc->dims[l + 1];
+    }
+  }
+  mdl->d = off;
+  *out = mdl;
+  return ZENO_OK;
+}
+
+void zeno_model_destroy(zeno_model_t* model) { delete model; }
+
+int64_t zeno_model_num_params(const zeno_model_t* model) { return model == nullptr ? 0 : model->d; }
+
+size_t zeno_score_workspace_bytes(const zeno_model_t* model, int32_t m, int32_t n_r) {
+  if (model == nullptr || m < 1 || m > ZENO_MAX_CANDIDATES || n_r < 1) return 0;
+  return make_plan(model, m, n_r).total;
+}
+
+zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float* G, int32_t m,
+                         const zeno_batch_t* batch, float gamma, float rho, float* scores, void* workspace,
+                         size_t workspace_bytes, void* stream_) {
+  if (model == nullptr || x == nullptr || G == nullptr || batch == nullptr || scores == nullptr)
+    return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || batch->n_r < 1) return ZENO_ERR_INVALID_ARG;
+  if (!std::isfinite(gamma) || gamma < 0.f || !std::isfinite(rho) || rho < 0.f) return ZENO_ERR_INVALID_ARG;
+  const zeno_model_desc_t& D = model->desc;
+  if (batch->features == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (D.loss == ZENO_LOSS_SOFTMAX_CE && batch->labels == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (D.loss == ZENO_LOSS_SQUARED && batch->targets == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (!aligned(x, 4) || !aligned(G, 4) || !aligned(scores, 4) || !aligned(batch->features, 4) ||
+      !aligned(batch->labels, 4) || !aligned(batch->targets, 4))
+    return ZENO_ERR_INVALID_ARG;
+  const int n_r = batch->n_r;
+  const Plan p = make_plan(model, m, n_r);
+  if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < p.total) return ZENO_ERR_WORKSPACE;
+
+  hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
+  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+  const bool bf16 = D.fwd == ZENO_FWD_BF16;
+  const int L = p.L;
+  double* norm_partials = reinterpret_cast<double*>(ws + p.off_norm);
+  double* sample_diff = reinterpret_cast<double*>(ws + p.off_diff);
+  float* dZ = reinterpret_cast<float*>(ws + p.off_dz);
+  const int C = D.dims[L];
+
+  // partial-norm slots actually used by the candidate launches
+  int p_off[ZENO_MAX_LAYERS], P = 0;
+  for (int l = 0; l < L; ++l) {
+    p_off[l] = P;
+    P += layer_tiles(D.dims[l + 1], l + 1 == L, L == 1 ? m + 1 : m);
+  }
+
+#define ZENO_TRY(expr)                         \
+  do {                                         \
+    if ((expr) != hipSuccess) return ZENO_ERR_DEVICE; \
+  } while (0)
+
+  for (int begin = 0; begin < n_r; begin += p.pass_rows) {
+    const int rows = (n_r - begin) < p.pass_rows ? (n_r - begin) : p.pass_rows;
+    const bool first_pass = begin == 0;
+    ZENO_TRY(launch_pack_features(batch->features + (size_t)begin * D.dims[0], rows, D.dims[0], pad64(D.dims[0]),
+                                  p.MB, bf16, ws + p.off_feat, stream));
+    for (int l = 0; l < L; ++l) {
+      LayerArgs a;
+      std::memset(&a, 0, sizeof(a));
+      a.G = G;
+      a.x = x;
+      a.d = model->d;
+      a.m = m;
+      a.w_off = model->w_off[l];
+      a.b_off = model->b_off[l];
+      a.N = D.dims[l + 1];
+      a.K = D.dims[l];
+      a.Kp = pad64(a.K);
+      a.Np = pad64(a.N);
+      a.n_r = rows;
+      a.last = (l + 1 == L);
+      a.A_base = l == 0 ? ws + p.off_feat : ws + p.off_hbase[l - 1];
+      a.Z0 = reinterpret_cast<float*>(ws + p.off_z0[l]);
+      a.dZ = dZ;
+      a.H_base = a.last ? nullptr : ws + p.off_hbase[l];
+      a.gamma = gamma;
+      a.neg_inv_gamma = gamma > 0.f ? -1.0f / gamma : 0.f;
+      a.norm_partials = first_pass ? norm_partials : nullptr;
+      a.P = P;
+      a.p_off = p_off[l];
+      if (L > 1) {
+        a.A_cand = l == 0 ? nullptr : ws + p.off_hc[(l - 1) & 1];
+        a.D_cand = l == 0 ? nullptr : ws + p.off_dc[(l - 1) & 1];
+        a.A_stride = (long long)p.cand_stride;
+        a.H_cand = ws + p.off_hc[l & 1];
+        a.Dl_cand = ws + p.off_dc[l & 1];
+        a.H_stride = (long long)p.cand_stride;
+      }
+      if (L == 1) {
+        // single layer: the pass at x and the m candidates share one launch
+        a.src_begin = 0;
+        a.n_src = m + 1;
+        ZENO_TRY(launch_layer(a, bf16, false, p.MB, stream));
+      } else {
+        a.src_begin = m;  // the pass at x first: the candidates' epilogue needs Z0 of this layer
+        a.n_src = 1;
+        ZENO_TRY(launch_layer(a, bf16, false, p.MB, stream));
+        a.src_begin = 0;
+        a.n_src = m;
+        ZENO_TRY(launch_layer(a, bf16, l > 0, p.MB, stream));
+      }
+    }
+    ZENO_TRY(launch_loss(reinterpret_cast<const float*>(ws + p.off_z0[L - 1]), dZ, batch->labels, batch->targets,
+                         D.loss, m, n_r, begin, rows, C, sample_diff, stream));
+  }
+  ZENO_TRY(launch_score_combine(sample_diff, norm_partials, P, m, n_r, rho, scores, stream));
+  return ZENO_OK;
+}
+
+zeno_status_t zeno_aggregate(const float* G, const float* scores, int32_t m, int64_t d, int32_t b, float* out,
+                             int32_t* selected, void* stream) {
+  if (G == nullptr || scores == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || b < 0 || b >= m || d < 1) return ZENO_ERR_INVALID_ARG;
+  if (!aligned(G, 4) || !aligned(scores, 4) || !aligned(out, 4) || !aligned(selected, 4)) return ZENO_ERR_INVALID_ARG;
+  ZENO_TRY(launch_masked_average(G, scores, m, d, b, out, selected, reinterpret_cast<hipStream_t>(stream)));
+  return ZENO_OK;
+}
+
+zeno_status_t zeno_mean(const float* G, int32_t m, int64_t d, float* out, void* stream) {
+  if (G == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1) return ZENO_ERR_INVALID_ARG;
+  if (!aligned(G, 4) || !aligned(out, 4)) return ZENO_ERR_INVALID_ARG;
+  ZENO_TRY(launch_masked_average(G, nullptr, m, d, 0, out, nullptr, reinterpret_cast<hipStream_t>(stream)));
+  return ZENO_OK;
+}
+
+zeno_status_t zeno_median(const float* G, int32_t m, int64_t d, float* out, void* stream) {
+  if (G == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1) return ZENO_ERR_INVALID_ARG;
+  if (!aligned(G, 4) || !aligned(out, 4)) return ZENO_ERR_INVALID_ARG;
+  if (m > 128) return ZENO_ERR_UNSUPPORTED;
+  ZENO_TRY(launch_median(G, m, d, out, reinterpret_cast<hipStream_t>(stream)));
+  return ZENO_OK;
+}
+
+const char* zeno_status_string(zeno_status_t status) {
+  switch (status) {
+    case ZENO_OK: return "ok";
+    case ZENO_ERR_INVALID_ARG: return "invalid argument";
+    case ZENO_ERR_UNSUPPORTED: return "unsupported size";
+    case ZENO_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case ZENO_ERR_DEVICE: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

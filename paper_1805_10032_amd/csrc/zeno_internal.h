@@ -1,0 +1,76 @@
+// Internal declarations shared by the translation units of the Zeno HIP library.
+// Nothing here is part of the C ABI (that is include/zeno.h).
+#ifndef ZENO_INTERNAL_H_
+#define ZENO_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "zeno.h"
+
+namespace zeno {
+
+// Four floats with 4-byte alignment: rows of G and the per-layer blocks inside a
+// row start at arbitrary 4-byte offsets, and gfx950 global loads/stores of 128
+// bits only need dword alignment.
+struct __attribute__((packed, aligned(4))) f4u {
+  float x, y, z, w;
+};
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// One launch of the streaming layer kernel (zeno_layer.hip).  Sources are
+// numbered 0..m-1 for the candidates G[s] and m for the current parameters x.
+struct LayerArgs {
+  const float* G;       // [m x d]
+  const float* x;       // [d]
+  long long d;          // leading dimension of G
+  int m;                // number of candidates
+  int src_begin;        // first source of this launch
+  int n_src;            // number of sources of this launch
+  long long w_off;      // offset of W_l inside a parameter vector
+  long long b_off;      // offset of b_l, or -1
+  int N, K;             // layer width out / in
+  int Kp;               // K rounded up to a multiple of 64 (tiled operand width)
+  int Np;               // N rounded up to a multiple of 64 (tiled width of the next layer's operand)
+  int n_r;              // valid samples (rows) in this pass
+  int last;             // 1: this is the output layer (raw fp32 results)
+  const void* A_base;   // tiled activations of the pass at x, input of this layer
+  const void* A_cand;   // tiled activations of candidate 0 (NULL: all candidates read A_base, first layer)
+  const void* D_cand;   // tiled scaled activation differences of candidate 0 (delta launches only)
+  long long A_stride;   // bytes between consecutive candidates in A_cand / D_cand
+  float* Z0;            // [n_r x N] pre-activations at x: written by source m, read by the others
+  float* dZ;            // [m x n_r x N] change of the output layer's pre-activations (last layer)
+  void* H_base;         // tiled output activations at x (hidden layers)
+  void* H_cand;         // tiled output activations of candidate 0 (hidden layers)
+  void* Dl_cand;        // tiled scaled output differences of candidate 0 (hidden layers)
+  long long H_stride;   // bytes between consecutive candidates in H_cand / Dl_cand
+  float gamma;
+  float neg_inv_gamma;  // -1/gamma, or 0 when gamma == 0
+  double* norm_partials;  // [m x P] partial sums of squares, or NULL in passes after the first
+  int P;                // partial slots per candidate
+  int p_off;            // first slot of this layer
+};
+
+// Launchers.  Each returns the hipError_t of its launches.
+hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, int MB, bool bf16,
+                                void* tiled, hipStream_t stream);
+hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream);
+int layer_tiles(int N, int last, int n_src);  // partial-norm slots a launch over a layer of width N uses
+hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, const float* targets,
+                       int loss, int m, int n_r_total, int chunk_begin, int chunk_rows, int C,
+                       double* sample_diff, hipStream_t stream);
+hipError_t launch_score_combine(const double* sample_diff, const double* norm_partials, int P, int m,
+                                int n_r_total, float rho, float* scores, hipStream_t stream);
+hipError_t launch_masked_average(const float* G, const float* scores, int m, long long d, int b,
+                                 float* out, int32_t* selected, hipStream_t stream);
+hipError_t launch_median(const float* G, int m, long long d, float* out, hipStream_t stream);
+
+}  // namespace zeno
+#endif

@@ -1,0 +1,160 @@
+"""GPU parity of zeno_score (Definition 2) and of the whole step against the
+float64 CPU oracle, called through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import zeno_oracle as O
+from paper_1805_10032_amd import workloads as WL
+from tests._util import (AGG_TOL, SCORE_TOL, check_selection, exact_terms, gpu_scores, npy,
+                         oracle_terms, score_error)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1805_10032_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _check_step(B, w, tol=None):
+    tol = SCORE_TOL[w.fwd] if tol is None else tol
+    s_gpu = gpu_scores(B, w)
+    s_ref, scale = oracle_terms(w)
+    err = score_error(npy(s_gpu), s_ref, scale)
+    assert np.all(err <= tol), (w.name, err.max(), int(err.argmax()))
+    if w.fwd == "bf16":
+        # distance to the float64 definition: bounded by the forward error of bf16 operands
+        s_exact, _ = exact_terms(w)
+        err_exact = score_error(npy(s_gpu), s_exact, scale)
+        print(f"{w.name}: bf16 path vs contract {err.max():.2e}, vs float64 definition {err_exact.max():.2e}")
+        assert np.all(err_exact <= 5e-2), (w.name, err_exact.max())
+    out, sel = B.zeno_aggregate(w.G.cuda(), s_gpu, w.b)
+    torch.cuda.synchronize()
+    finite = np.isfinite(scale)
+    check_selection(npy(sel), s_ref, w.b, tol * float(np.max(scale[finite])) if finite.any() else 0.0)
+    # the aggregate of the rows the GPU chose, against the oracle's average of the same rows
+    ref = np.zeros(w.d)
+    for i in npy(sel):
+        ref += npy(w.G[int(i)]).astype(np.float64)
+    ref /= len(sel)
+    o = npy(out).astype(np.float64)
+    sel_max = max(float(w.G[int(i)].abs().max()) for i in npy(sel))
+    assert np.linalg.norm(o - ref) <= AGG_TOL * np.linalg.norm(ref)
+    assert np.max(np.abs(o - ref)) <= AGG_TOL * sel_max
+    return err
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_numbered_configs_small(B, cfg):
+    w = WL.make_config(cfg)
+    _check_step(B, w)
+    if cfg in (1, 2):   # sign-flipped / huge-noise rows are excluded (Section 6.4 behaviour on tiny cases)
+        s = gpu_scores(B, w)
+        _, sel = B.zeno_aggregate(w.G.cuda(), s, w.b)
+        assert set(npy(sel).tolist()).isdisjoint(set(w.faulty))
+
+
+def test_config1_matches_closed_form(B):
+    """Least squares: score = gamma <grad, u> - gamma^2 ||Au||^2 / (2 n_r) - rho ||u||^2."""
+    w = WL.make_config(1)
+    A, y, x = (npy(t).astype(np.float64) for t in (w.features, w.targets, w.x))
+    grad = A.T @ (A @ x - y) / w.n_r
+    G = npy(w.G).astype(np.float64)
+    ref = w.gamma * G @ grad - w.gamma ** 2 * np.sum((G @ A.T) ** 2, axis=1) / (2 * w.n_r) - w.rho * np.sum(G * G, axis=1)
+    s = npy(gpu_scores(B, w)).astype(np.float64)
+    assert np.max(np.abs(s - ref) / np.abs(ref)) <= 1e-5
+
+
+SMALL = [
+    # dims, m, b, n_r, loss, has_bias
+    ([37, 21, 13, 5], 7, 2, 9, "softmax_ce", True),
+    ([5, 3], 1, 0, 1, "softmax_ce", True),
+    ([65, 1], 3, 1, 33, "squared", False),
+    ([130, 67, 1], 5, 4, 65, "squared", True),
+    ([300, 200, 10], 9, 3, 40, "softmax_ce", True),
+    ([256, 512, 256, 10], 12, 3, 100, "softmax_ce", True),
+    ([64, 128, 64, 32, 16, 8, 4, 3, 2], 6, 2, 17, "softmax_ce", True),   # 8 layers
+    ([100, 1000], 10, 3, 128, "softmax_ce", False),
+    ([257, 129, 1000], 4, 1, 31, "softmax_ce", True),
+]
+
+
+@pytest.mark.parametrize("fwd", ["fp32", "bf16"])
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_small_shapes(B, case, fwd):
+    dims, m, b, n_r, loss, has_bias = SMALL[case]
+    q = min(2, m - 1)
+    w = WL.make_mlp_workload(f"small{case}", 70 + case, dims, m, b, n_r, 0.1, 1e-3, fwd, seed=case,
+                             has_bias=has_bias, loss=loss, n_flip=min(1, q), n_noise=q - min(1, q),
+                             noise_std=5.0)
+    _check_step(B, w)
+
+
+@pytest.mark.parametrize("fwd", ["fp32", "bf16"])
+def test_batches_larger_than_one_pass(B, fwd):
+    """n_r > 128: several passes over G, the ragged last one shorter."""
+    w = WL.make_mlp_workload("multipass", 90, [96, 80, 7], 6, 2, 300, 0.1, 1e-3, fwd, n_flip=1, n_noise=1,
+                             noise_std=3.0)
+    _check_step(B, w)
+
+
+def test_gamma_zero_and_rho_zero(B):
+    w = WL.make_mlp_workload("g0", 91, [40, 30, 6], 5, 1, 12, 0.0, 2e-3, "fp32", n_flip=1)
+    s = npy(gpu_scores(B, w)).astype(np.float64)
+    nrm = np.sum(npy(w.G).astype(np.float64) ** 2, axis=1)
+    np.testing.assert_allclose(s, -w.rho * nrm, rtol=1e-6)
+    w.gamma, w.rho = 0.1, 0.0
+    _check_step(B, w)
+
+
+def test_zero_candidate_scores_zero(B):
+    w = WL.make_mlp_workload("z", 92, [40, 30, 6], 4, 1, 12, 0.1, 1e-3, "bf16", n_flip=1)
+    w.G[2].zero_()
+    s = npy(gpu_scores(B, w))
+    assert s[2] == 0.0
+
+
+@pytest.mark.parametrize("fwd", ["fp32", "bf16"])
+def test_nonfinite_rows_rank_last(B, fwd):
+    """'Arbitrary values' (Section 3): rows holding NaN or Inf must get a NaN or
+    -inf score and be trimmed, never a finite good-looking one."""
+    w = WL.make_mlp_workload("nf", 93, [48, 40, 5], 8, 3, 10, 0.1, 1e-3, fwd)
+    w.G[1, 7] = float("nan")
+    w.G[4, 48 * 40 + 3] = float("inf")          # a bias entry of layer 1
+    w.G[6, -1] = float("-inf")                  # last bias of the output layer
+    s = npy(gpu_scores(B, w)).astype(np.float64)
+    for i in (1, 4, 6):
+        assert np.isnan(s[i]) or s[i] == -np.inf, (i, s[i])
+    ok = [i for i in range(8) if i not in (1, 4, 6)]
+    s_ref, scale = oracle_terms(w, ok)
+    assert np.all(score_error(s[ok], s_ref, scale) <= SCORE_TOL[fwd])
+    _, sel = B.zeno_aggregate(w.G.cuda(), torch.from_numpy(s.astype(np.float32)).cuda(), 3)
+    assert sorted(npy(sel).tolist()) == ok
+
+
+def test_scores_are_deterministic(B):
+    w = WL.make_config(3)
+    a = gpu_scores(B, w)
+    b = gpu_scores(B, w)
+    assert torch.equal(a, b)
+
+
+def test_score_error_codes(B):
+    w = WL.make_config(1)
+    mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
+    x, G, F, t = w.x.cuda(), w.G.cuda(), w.features.cuda(), w.targets.cuda()
+    with pytest.raises(B.ZenoError) as e:
+        B.zeno_score(mdl, x, G, F, float("nan"), 1e-3, targets=t)
+    assert e.value.status == 1
+    with pytest.raises(B.ZenoError) as e:
+        B.zeno_score(mdl, x, G, F, 0.1, -1.0, targets=t)
+    assert e.value.status == 1
+    with pytest.raises(B.ZenoError) as e:
+        B.zeno_score(mdl, x, G, F, 0.1, 1e-3)               # squared loss without targets
+    assert e.value.status == 1
+    with pytest.raises(B.ZenoError) as e:
+        B.zeno_score(mdl, x, G, F, 0.1, 1e-3, targets=t, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 3
