@@ -139,6 +139,37 @@ zeno_status_t zeno_median(const float* G, int32_t m, int64_t d, float* out, void
 
 const char* zeno_status_string(zeno_status_t status);
 
+/* Per-launch timing, a measurement aid (Section 5.3 prices the step by its
+ * O(d m) passes over the candidates; this reports what each pass costs).
+ * While enabled, every kernel launch of the library is bracketed by a pair of
+ * HIP events recorded on the launch's own stream.  zeno_profile_collect waits
+ * for the recorded events, copies up to max_records records (in launch order)
+ * into the HOST array `records`, returns how many it wrote and forgets them
+ * all.  algorithmic_bytes is what the launch must move by definition: the
+ * layer block of every source it streams, or the rows read plus the row
+ * written for the aggregators.  Not thread-safe against concurrent launches
+ * of the same process beyond a mutex around the record list. */
+typedef enum {
+  ZENO_KERNEL_PACK = 0,       /* batch features into matrix-operand order */
+  ZENO_KERNEL_LAYER_BASE = 1, /* one layer of the pass at x */
+  ZENO_KERNEL_LAYER_CAND = 2, /* one layer of the m candidate passes (streams G) */
+  ZENO_KERNEL_LOSS = 3,       /* per-sample loss differences */
+  ZENO_KERNEL_COMBINE = 4,    /* mean, norm and the three-term score */
+  ZENO_KERNEL_AVERAGE = 5,    /* selection + average of the chosen rows */
+  ZENO_KERNEL_MEAN = 6,
+  ZENO_KERNEL_MEDIAN = 7
+} zeno_kernel_t;
+
+typedef struct {
+  int32_t kernel; /* zeno_kernel_t */
+  int32_t layer;  /* 0-based layer index for the layer kernels, else 0 */
+  float ms;       /* elapsed time between the two events */
+  double algorithmic_bytes;
+} zeno_profile_record_t;
+
+zeno_status_t zeno_profile_enable(int32_t enable);
+int32_t zeno_profile_collect(zeno_profile_record_t* records, int32_t max_records);
+
 #ifdef __cplusplus
 }
 #endif

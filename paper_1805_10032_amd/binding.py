@@ -23,7 +23,9 @@ STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported size", 3: "workspace",
 
 EXPORTS = ["zeno_model_create", "zeno_model_destroy", "zeno_model_num_params",
            "zeno_score_workspace_bytes", "zeno_score", "zeno_aggregate", "zeno_mean",
-           "zeno_median", "zeno_status_string"]
+           "zeno_median", "zeno_status_string", "zeno_profile_enable", "zeno_profile_collect"]
+
+KERNEL_NAMES = ["pack", "layer_base", "layer_cand", "loss", "combine", "average", "mean", "median"]
 
 
 class ZenoError(RuntimeError):
@@ -38,6 +40,11 @@ class _ModelDesc(ctypes.Structure):
                 ("has_bias", ctypes.c_int32),
                 ("loss", ctypes.c_int32),
                 ("fwd", ctypes.c_int32)]
+
+
+class _ProfileRecord(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int32), ("layer", ctypes.c_int32), ("ms", ctypes.c_float),
+                ("algorithmic_bytes", ctypes.c_double)]
 
 
 class _Batch(ctypes.Structure):
@@ -78,6 +85,10 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.zeno_mean.restype = ctypes.c_int
     lib.zeno_median.argtypes = [vp, i32, i64, vp, vp]
     lib.zeno_median.restype = ctypes.c_int
+    lib.zeno_profile_enable.argtypes = [i32]
+    lib.zeno_profile_enable.restype = ctypes.c_int
+    lib.zeno_profile_collect.argtypes = [ctypes.POINTER(_ProfileRecord), i32]
+    lib.zeno_profile_collect.restype = i32
     lib.zeno_status_string.argtypes = [ctypes.c_int]
     lib.zeno_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -213,3 +224,15 @@ def zeno_median(G, *, out=None):
     if st != 0:
         raise ZenoError(st, "zeno_median")
     return out
+
+
+def profile_enable(on: bool = True):
+    load_library().zeno_profile_enable(1 if on else 0)
+
+
+def profile_collect(max_records: int = 4096):
+    """[(kernel name, layer, ms, algorithmic bytes)] of the launches since the last collect."""
+    buf = (_ProfileRecord * max_records)()
+    n = load_library().zeno_profile_collect(buf, max_records)
+    return [(KERNEL_NAMES[buf[i].kernel], int(buf[i].layer), float(buf[i].ms), float(buf[i].algorithmic_bytes))
+            for i in range(n)]

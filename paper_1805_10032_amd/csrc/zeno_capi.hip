@@ -3,7 +3,9 @@
 // the host only validates and enqueues.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <vector>
 
 #include "zeno_internal.h"
 
@@ -69,9 +71,74 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
   return p;
 }
 
+#define ZENO_TRY(expr)                                \
+  do {                                                \
+    if ((expr) != hipSuccess) return ZENO_ERR_DEVICE; \
+  } while (0)
+
+// ---- optional per-launch timing (zeno_profile_enable / zeno_profile_collect):
+// while enabled every kernel launch is bracketed by two HIP events recorded on
+// the launch's own stream.
+struct ProfEntry {
+  hipEvent_t start, stop;
+  zeno_profile_record_t rec;
+};
+std::mutex g_prof_mutex;
+bool g_prof_on = false;
+std::vector<ProfEntry> g_prof;
+
+struct ProfScope {
+  hipStream_t stream;
+  int slot = -1;
+  ProfScope(int kernel, int layer, double bytes, hipStream_t s) : stream(s) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (!g_prof_on) return;
+    ProfEntry e;
+    if (hipEventCreate(&e.start) != hipSuccess) return;
+    if (hipEventCreate(&e.stop) != hipSuccess) {
+      (void)hipEventDestroy(e.start);
+      return;
+    }
+    e.rec.kernel = kernel;
+    e.rec.layer = layer;
+    e.rec.ms = 0.f;
+    e.rec.algorithmic_bytes = bytes;
+    (void)hipEventRecord(e.start, stream);
+    g_prof.push_back(e);
+    slot = (int)g_prof.size() - 1;
+  }
+  ~ProfScope() {
+    if (slot < 0) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (slot < (int)g_prof.size()) (void)hipEventRecord(g_prof[slot].stop, stream);
+  }
+};
+
 }  // namespace
 
 extern "C" {
+
+zeno_status_t zeno_profile_enable(int32_t enable) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  g_prof_on = enable != 0;
+  return ZENO_OK;
+}
+
+int32_t zeno_profile_collect(zeno_profile_record_t* records, int32_t max_records) {
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
+  int32_t n = 0;
+  for (ProfEntry& e : g_prof) {
+    float ms = 0.f;
+    if (hipEventSynchronize(e.stop) == hipSuccess && hipEventElapsedTime(&ms, e.start, e.stop) == hipSuccess) {
+      e.rec.ms = ms;
+      if (records != nullptr && n < max_records) records[n++] = e.rec;
+    }
+    (void)hipEventDestroy(e.start);
+    (void)hipEventDestroy(e.stop);
+  }
+  g_prof.clear();
+  return n;
+}
 
 zeno_status_t zeno_model_create(const zeno_model_desc_t* desc, zeno_model_t** out) {
   if (desc == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
@@ -143,16 +210,14 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
     P += layer_tiles(D.dims[l + 1], l + 1 == L, L == 1 ? m + 1 : m);
   }
 
-#define ZENO_TRY(expr)                         \
-  do {                                         \
-    if ((expr) != hipSuccess) return ZENO_ERR_DEVICE; \
-  } while (0)
-
   for (int begin = 0; begin < n_r; begin += p.pass_rows) {
     const int rows = (n_r - begin) < p.pass_rows ? (n_r - begin) : p.pass_rows;
     const bool first_pass = begin == 0;
-    ZENO_TRY(launch_pack_features(batch->features + (size_t)begin * D.dims[0], rows, D.dims[0], pad64(D.dims[0]),
-                                  p.MB, bf16, ws + p.off_feat, stream));
+    {
+      ProfScope ps(ZENO_KERNEL_PACK, 0, 4.0 * rows * D.dims[0], stream);
+      ZENO_TRY(launch_pack_features(batch->features + (size_t)begin * D.dims[0], rows, D.dims[0], pad64(D.dims[0]),
+                                    p.MB, bf16, ws + p.off_feat, stream));
+    }
     for (int l = 0; l < L; ++l) {
       LayerArgs a;
       std::memset(&a, 0, sizeof(a));
@@ -185,23 +250,32 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
         a.Dl_cand = ws + p.off_dc[l & 1];
         a.H_stride = (long long)p.cand_stride;
       }
+      // bytes of this layer's block in one parameter vector (what one source streams)
+      const double layer_bytes = 4.0 * ((double)a.N * a.K + (a.b_off >= 0 ? a.N : 0));
       if (L == 1) {
         // single layer: the pass at x and the m candidates share one launch
         a.src_begin = 0;
         a.n_src = m + 1;
+        ProfScope ps(ZENO_KERNEL_LAYER_CAND, l, layer_bytes * (m + 1), stream);
         ZENO_TRY(launch_layer(a, bf16, false, p.MB, stream));
       } else {
         a.src_begin = m;  // the pass at x first: the candidates' epilogue needs Z0 of this layer
         a.n_src = 1;
-        ZENO_TRY(launch_layer(a, bf16, false, p.MB, stream));
+        {
+          ProfScope ps(ZENO_KERNEL_LAYER_BASE, l, layer_bytes, stream);
+          ZENO_TRY(launch_layer(a, bf16, false, p.MB, stream));
+        }
         a.src_begin = 0;
         a.n_src = m;
+        ProfScope ps(ZENO_KERNEL_LAYER_CAND, l, layer_bytes * m, stream);
         ZENO_TRY(launch_layer(a, bf16, l > 0, p.MB, stream));
       }
     }
+    ProfScope ps(ZENO_KERNEL_LOSS, 0, 4.0 * (m + 1) * rows * C, stream);
     ZENO_TRY(launch_loss(reinterpret_cast<const float*>(ws + p.off_z0[L - 1]), dZ, batch->labels, batch->targets,
                          D.loss, m, n_r, begin, rows, C, sample_diff, stream));
   }
+  ProfScope ps(ZENO_KERNEL_COMBINE, 0, 8.0 * m * (n_r + P), stream);
   ZENO_TRY(launch_score_combine(sample_diff, norm_partials, P, m, n_r, rho, scores, stream));
   return ZENO_OK;
 }
@@ -211,6 +285,7 @@ zeno_status_t zeno_aggregate(const float* G, const float* scores, int32_t m, int
   if (G == nullptr || scores == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
   if (m < 1 || m > ZENO_MAX_CANDIDATES || b < 0 || b >= m || d < 1) return ZENO_ERR_INVALID_ARG;
   if (!aligned(G, 4) || !aligned(scores, 4) || !aligned(out, 4) || !aligned(selected, 4)) return ZENO_ERR_INVALID_ARG;
+  ProfScope ps(ZENO_KERNEL_AVERAGE, 0, 4.0 * (double)d * (m - b + 1), reinterpret_cast<hipStream_t>(stream));
   ZENO_TRY(launch_masked_average(G, scores, m, d, b, out, selected, reinterpret_cast<hipStream_t>(stream)));
   return ZENO_OK;
 }
@@ -219,6 +294,7 @@ zeno_status_t zeno_mean(const float* G, int32_t m, int64_t d, float* out, void* 
   if (G == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
   if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1) return ZENO_ERR_INVALID_ARG;
   if (!aligned(G, 4) || !aligned(out, 4)) return ZENO_ERR_INVALID_ARG;
+  ProfScope ps(ZENO_KERNEL_MEAN, 0, 4.0 * (double)d * (m + 1), reinterpret_cast<hipStream_t>(stream));
   ZENO_TRY(launch_masked_average(G, nullptr, m, d, 0, out, nullptr, reinterpret_cast<hipStream_t>(stream)));
   return ZENO_OK;
 }
@@ -228,6 +304,7 @@ zeno_status_t zeno_median(const float* G, int32_t m, int64_t d, float* out, void
   if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1) return ZENO_ERR_INVALID_ARG;
   if (!aligned(G, 4) || !aligned(out, 4)) return ZENO_ERR_INVALID_ARG;
   if (m > 128) return ZENO_ERR_UNSUPPORTED;
+  ProfScope ps(ZENO_KERNEL_MEDIAN, 0, 4.0 * (double)d * (m + 1), reinterpret_cast<hipStream_t>(stream));
   ZENO_TRY(launch_median(G, m, d, out, reinterpret_cast<hipStream_t>(stream)));
   return ZENO_OK;
 }
