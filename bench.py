@@ -140,14 +140,20 @@ def main():
     torch.cuda.synchronize()
     recs = B.profile_collect()
     B.profile_enable(False)
-    per = {}
+    per, per_layer = {}, {}
     for name, layer, ms, nbytes in recs:
+        if name.startswith("layer"):
+            e = per_layer.setdefault(f"{name}[{layer}]", [0, 0.0, 0.0])
+            e[0] += 1
+            e[1] += ms
+            e[2] += nbytes
         e = per.setdefault(name, [0, 0.0, 0.0])
         e[0] += 1
         e[1] += ms
         e[2] += nbytes
     kernels = {k: {"launches_per_step": v[0] / n_prof, "avg_ms": v[1] / v[0],
                    "algorithmic_GBps": (v[2] / v[0]) / (v[1] / v[0]) / 1e6} for k, v in per.items()}
+    layers = {k: {"avg_ms": v[1] / v[0], "algorithmic_GBps": v[2] / v[1] / 1e6} for k, v in per_layer.items()}
     dom = per["layer_cand"]
     dom_avg_ms = dom[1] / dom[0]
     dom_bytes = dom[2] / dom[0]
@@ -177,6 +183,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(a.config),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms},
         "kernels": kernels,
+        "layers": layers,
     }
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds)

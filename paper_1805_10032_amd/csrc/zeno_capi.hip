@@ -2,6 +2,7 @@
 // sequencing.  Every step of the path runs in the HIP kernels of this library;
 // the host only validates and enqueues.
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -30,6 +31,7 @@ inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_
 struct Plan {
   int L, pass_rows, MB, n_pad, esize, P;
   size_t off_feat, off_hbase[ZENO_MAX_LAYERS], off_z0[ZENO_MAX_LAYERS];
+  size_t off_wt[ZENO_MAX_LAYERS];  // W_l in operand order, layers after the first
   size_t off_hc[2], off_dc[2], cand_stride, off_dz, off_norm, off_diff, total;
 };
 
@@ -56,6 +58,10 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
     if (l + 1 < p.L) {
       p.off_hbase[l] = take((size_t)p.n_pad * pad64(N) * p.esize);
       if (pad64(N) > max_np) max_np = pad64(N);
+    }
+    if (l > 0) {
+      const int cover = (l + 1 < p.L) ? pad64(N) : N;
+      p.off_wt[l] = take((size_t)((cover + 127) / 128 * 128) * pad64(D.dims[l]) * p.esize);
     }
     p.P += (pad64(N) + 31) / 32;  // upper bound on the partial-norm slots of this layer
   }
@@ -234,6 +240,7 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
       a.n_r = rows;
       a.last = (l + 1 == L);
       a.A_base = l == 0 ? ws + p.off_feat : ws + p.off_hbase[l - 1];
+      a.Wt = l > 0 ? ws + p.off_wt[l] : nullptr;
       a.Z0 = reinterpret_cast<float*>(ws + p.off_z0[l]);
       a.dZ = dZ;
       a.H_base = a.last ? nullptr : ws + p.off_hbase[l];
@@ -242,6 +249,9 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
       a.norm_partials = first_pass ? norm_partials : nullptr;
       a.P = P;
       a.p_off = p_off[l];
+#ifdef ZENO_TIMING_EXPERIMENTS
+      a.dbg = std::getenv("ZENO_DEBUG_SKIP") ? std::atoi(std::getenv("ZENO_DEBUG_SKIP")) : 0;
+#endif
       if (L > 1) {
         a.A_cand = l == 0 ? nullptr : ws + p.off_hc[(l - 1) & 1];
         a.D_cand = l == 0 ? nullptr : ws + p.off_dc[(l - 1) & 1];

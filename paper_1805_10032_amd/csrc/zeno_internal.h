@@ -45,6 +45,7 @@ struct LayerArgs {
   const void* A_cand;   // tiled activations of candidate 0 (NULL: all candidates read A_base, first layer)
   const void* D_cand;   // tiled scaled activation differences of candidate 0 (delta launches only)
   long long A_stride;   // bytes between consecutive candidates in A_cand / D_cand
+  void* Wt;             // W_l in matrix-operand order: written by source m, read by delta launches; may be NULL
   float* Z0;            // [n_r x N] pre-activations at x: written by source m, read by the others
   float* dZ;            // [m x n_r x N] change of the output layer's pre-activations (last layer)
   void* H_base;         // tiled output activations at x (hidden layers)
@@ -56,6 +57,7 @@ struct LayerArgs {
   double* norm_partials;  // [m x P] partial sums of squares, or NULL in passes after the first
   int P;                // partial slots per candidate
   int p_off;            // first slot of this layer
+  int dbg;              // timing experiments (only read when built with ZENO_TIMING_EXPERIMENTS)
 };
 
 // Launchers.  Each returns the hipError_t of its launches.

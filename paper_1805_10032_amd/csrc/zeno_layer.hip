@@ -17,17 +17,26 @@
 // accumulated from the same registers that feed the matrix cores.
 //
 // Matrix-core mapping (wave64): each wave owns 32 output features (columns of the
-// 32x32 accumulator blocks) and all MB*32 sample rows.  The weight tile is
-// loaded with fully coalesced 128-bit loads (4 rows x 256 B per instruction),
-// converted, and passed through a wave-private LDS tile to reach the operand
-// layout (lane = feature, 8 consecutive k); the activation operands are stored
-// in global memory already in operand order ("tiled") and are shared by the
-// waves of the workgroup through LDS.
+// 32x32 accumulator blocks) and all MB*32 sample rows.
+//  * U tile (32 features x 64 k, fp32 in HBM): fully coalesced 128-bit loads (4
+//    rows x 256 B per instruction, scalar base + per-lane offset), two chunks in
+//    flight per wave; converted and passed through a wave-private, XOR-swizzled
+//    LDS tile to reach the operand layout (lane = feature, 8 consecutive k).
+//  * Activation operands H_s, D_s: stored in global memory already in operand
+//    order ("tiled"), copied asynchronously global -> LDS (no registers) into a
+//    double buffer and shared by the waves of the workgroup: one barrier per chunk.
+//  * W operand of the second product: written in operand order by the pass at x,
+//    loaded straight into registers.
+#include <type_traits>
+
 #include "zeno_internal.h"
 
 namespace zeno {
 
 namespace {
+
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
 
 template <bool BF16>
 struct Tr;
@@ -35,13 +44,11 @@ template <>
 struct Tr<true> {
   static constexpr int ESIZE = 2;
   static constexpr int CH_BYTES = 32 * 64 * 2;  // one 32-row block of a 64-wide K chunk, tiled operand
-  static constexpr int STAGE_ROW = 64 * 2 + 16; // staged weight row: 64 bf16 + pad (conflict-free b128 reads)
 };
 template <>
 struct Tr<false> {
   static constexpr int ESIZE = 4;
   static constexpr int CH_BYTES = 32 * 64 * 4;
-  static constexpr int STAGE_ROW = 64 * 4 + 16;
 };
 
 // Element index of (row r, column k) inside a tiled activation operand of padded
@@ -91,59 +98,70 @@ __device__ inline f32x4 load4_masked(const float* __restrict__ row, int k, int K
 }
 
 // Load the wave's 32 x 64 weight tile: instruction j covers rows 4j..4j+3, 256
-// contiguous bytes each.
-__device__ inline void load_tile(f32x4 (&u)[8], const float* __restrict__ mat, int row0, int k0, int N, int K,
-                                 int lane) {
-  const int rsub = lane >> 4, k = k0 + ((lane & 15) << 2);
-  if (row0 + 32 <= N && k0 + 64 <= K) {
+// contiguous bytes each.  `tile` is the wave-uniform address of element (row0, k0);
+// `lane_off` = (lane/16)*K + 4*(lane%16) is the lane's element offset inside it.
+// FULL: the whole tile lies inside the matrix (no masking code is generated).
+template <bool FULL>
+__device__ inline void load_tile(f32x4 (&u)[8], const float* __restrict__ tile, unsigned lane_off, int row0, int k0,
+                                 int N, int K, int lane) {
+  if (FULL) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const f4u t = *reinterpret_cast<const f4u*>(mat + (long long)(row0 + 4 * j + rsub) * K + k);
+      const f4u t = *reinterpret_cast<const f4u*>(tile + (long long)(4 * j) * K + lane_off);
       u[j][0] = t.x; u[j][1] = t.y; u[j][2] = t.z; u[j][3] = t.w;
     }
   } else {
+    const int rsub = lane >> 4, kq = (lane & 15) << 2;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int row = row0 + 4 * j + rsub;
-      u[j] = load4_masked(mat + (long long)row * K, k, K, row < N);
+      u[j] = load4_masked(tile + (long long)(4 * j + rsub) * K, kq, K - k0, row < N);
     }
   }
 }
 
+// Wave-private staging tile, unpadded and XOR-swizzled on 16-byte segments so that
+// both the row-wise writes and the operand reads (lane = row) are conflict-free.
 template <bool BF16>
 __device__ inline void stage_tile(const f32x4 (&u)[8], unsigned char* st, int lane) {
-  using T = Tr<BF16>;
   const int rsub = lane >> 4, kq = lane & 15;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    unsigned char* p = st + (4 * j + rsub) * T::STAGE_ROW;
+    const int r = 4 * j + rsub;
     if (BF16) {
       const bf16x4 h = __builtin_convertvector(u[j], bf16x4);
-      *reinterpret_cast<bf16x4*>(p + kq * 8) = h;
+      *reinterpret_cast<bf16x4*>(st + r * 128 + ((((kq >> 1) ^ (r >> 1)) & 7) << 4) + ((kq & 1) << 3)) = h;
     } else {
-      *reinterpret_cast<f32x4*>(p + kq * 16) = u[j];
+      *reinterpret_cast<f32x4*>(st + r * 256 + (((kq ^ r) & 15) << 4)) = u[j];
     }
   }
+}
+
+// s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding: vmcnt in
+// bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+template <int N>
+__device__ inline void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
 template <bool BF16, bool DELTA, int MB, int NW>
 __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   using T = Tr<BF16>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  constexpr int NT = 64 * NW;
   constexpr int BN = 32 * NW;
-  constexpr int A_BYTES = MB * T::CH_BYTES;
-  constexpr int A_PIECES = A_BYTES / 16;
-  constexpr int APT = (A_PIECES + NT - 1) / NT;
-  constexpr int PIECES_PER_BLOCK = T::CH_BYTES / 16;
-  constexpr int STAGE_BYTES = 32 * T::STAGE_ROW;
-  constexpr int N_STAGE = DELTA ? 2 : 1;
+  constexpr int A_BYTES = MB * T::CH_BYTES;            // one operand, one chunk
+  constexpr int AD_BYTES = A_BYTES * (DELTA ? 2 : 1);  // H (and D), one chunk
+  constexpr int AD_KB = AD_BYTES / 1024;               // 1 KB async copies per chunk
+  constexpr int A_KB = A_BYTES / 1024;
+  constexpr int BLOCK_KB = T::CH_BYTES / 1024;
+  constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
+  constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
+  constexpr int COPIES = (AD_KB + NW - 1) / NW;        // async copies issued per wave per chunk
+  constexpr int WREGS = BF16 ? 4 : 8;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  unsigned char* ldsA = lds;
-  unsigned char* ldsD = lds + A_BYTES;
-  unsigned char* stU = lds + A_BYTES * N_STAGE + wave * (STAGE_BYTES * N_STAGE);
-  unsigned char* stW = stU + STAGE_BYTES;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  unsigned char* stU = lds + AD_BYTES * (DBUF ? 2 : 1) + wave * STAGE_BYTES;
 
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2):
   // consecutive slots of one XCD walk through the feature tiles of one source,
@@ -156,15 +174,25 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   const int s = a.src_begin + src_local;
   const bool is_base = (s == a.m);
   const float* __restrict__ P = is_base ? a.x : a.G + (long long)s * a.d;
-  const float* __restrict__ Umat = P + a.w_off;
-  const float* __restrict__ Wmat = a.x + a.w_off;
   const int row0 = nt * BN + wave * 32;
   const int N = a.N, K = a.K;
   const int n_chunks = a.Kp >> 6;
+  const float* __restrict__ Urow0 = P + a.w_off + (long long)row0 * K;  // wave-uniform
+  const unsigned lane_off = (unsigned)(lane >> 4) * (unsigned)K + ((lane & 15) << 2);
+  const bool full_rows = row0 + 32 <= N;
 
   const unsigned char* Ag = reinterpret_cast<const unsigned char*>(a.A_base);
   if (!is_base && a.A_cand != nullptr) Ag = reinterpret_cast<const unsigned char*>(a.A_cand) + (long long)s * a.A_stride;
   const unsigned char* Dg = DELTA ? reinterpret_cast<const unsigned char*>(a.D_cand) + (long long)s * a.A_stride : nullptr;
+
+  const bool pack = is_base && a.Wt != nullptr;
+  unsigned char* Wt_wave = reinterpret_cast<unsigned char*>(a.Wt) +
+                           ((long long)(row0 >> 5) * n_chunks * WREGS * 64 + lane) * 16;
+  // The main loop exists in up to four versions chosen per wave: FULL (every
+  // weight tile lies inside the matrix: straight-line loads, and the in-order
+  // completion of loads lets a chunk wait for exactly its own activation copies)
+  // or masked, and PACK (the pass at x also writes W in operand order) or not.
+  const bool all_full = full_rows && (K & 63) == 0;
 
   f32x16 acc[MB];
 #pragma unroll
@@ -175,87 +203,138 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   const bool do_norm = (a.norm_partials != nullptr) && !is_base;
   double nrm = 0.0;
 
-  f32x4 u[8], w[8];
-  f32x4 pa[APT], pd[APT];
+  f32x4 u0[8], u1[8];
+  f32x4 w0[WREGS], w1[WREGS];
+#ifdef ZENO_TIMING_EXPERIMENTS
+  // Timing experiments only (results are wrong): bit 0 skips the matrix products
+  // and their LDS reads, bit 1 the activation copies, bit 2 the staging writes.
+  const int dbg = a.dbg;
+#else
+  constexpr int dbg = 0;
+#endif
 
-  auto load_A = [&](int c) {
+  // Asynchronous copy of chunk c of the tiled activation operands into LDS buffer
+  // `buf`: AD_KB pieces of 1 KB (64 lanes x 16 B land at consecutive LDS addresses),
+  // dealt round-robin to the waves.
+  auto copy_AD = [&](int c, int buf) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < APT; ++i) {
-      const int p = tid + i * NT;
-      if (A_PIECES % NT == 0 || p < A_PIECES) {
-        const int mb = p / PIECES_PER_BLOCK, within = p % PIECES_PER_BLOCK;
-        const long long off = ((long long)mb * n_chunks + c) * T::CH_BYTES + within * 16;
-        pa[i] = *reinterpret_cast<const f32x4*>(Ag + off);
-        if (DELTA) pd[i] = *reinterpret_cast<const f32x4*>(Dg + off);
+    for (int i = 0; i < COPIES; ++i) {
+      const int q = wave + i * NW;
+      if (AD_KB % NW == 0 || q < AD_KB) {
+        const int op = q / A_KB, piece = q % A_KB;
+        const int mb = piece / BLOCK_KB, within = piece % BLOCK_KB;
+        const unsigned char* src = (op ? Dg : Ag) + ((long long)mb * n_chunks + c) * T::CH_BYTES + within * 1024 + lane * 16;
+        unsigned char* dst = lds + buf * AD_BYTES + q * 1024;
+        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
       }
     }
   };
-
-  load_tile(u, Umat, row0, 0, N, K, lane);
-  if (DELTA) load_tile(w, Wmat, row0, 0, N, K, lane);
-  load_A(0);
-
-  for (int c = 0; c < n_chunks; ++c) {
-    __syncthreads();  // every wave has finished reading the previous chunk from LDS
+  auto load_W = [&](f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < APT; ++i) {
-      const int p = tid + i * NT;
-      if (A_PIECES % NT == 0 || p < A_PIECES) {
-        *reinterpret_cast<f32x4*>(ldsA + p * 16) = pa[i];
-        if (DELTA) *reinterpret_cast<f32x4*>(ldsD + p * 16) = pd[i];
-      }
-    }
+    for (int r = 0; r < WREGS; ++r)
+      w[r] = *reinterpret_cast<const f32x4*>(Wt_wave + ((long long)c * WREGS + r) * 1024);
+  };
+
+  // One K chunk.  Its weight tile sits in registers u (loaded two chunks ago); its
+  // activation operands were copied into LDS buffer c&1 during the previous chunk.
+  // Issue order per chunk: copies(c+1), U(c+2), [matrix products of c], W(c+2).
+  auto chunk = [&](auto full_c, auto pack_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_c)::value;
+    constexpr bool PACK = decltype(pack_c)::value;
+    const int buf = DBUF ? (c & 1) : 0;
     if (do_norm) {
       float q = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) q += (u[j][0] * u[j][0] + u[j][1] * u[j][1]) + (u[j][2] * u[j][2] + u[j][3] * u[j][3]);
       nrm += (double)q;
     }
-    stage_tile<BF16>(u, stU, lane);
-    if (DELTA) stage_tile<BF16>(w, stW, lane);
-    if (c + 1 < n_chunks) {
-      load_tile(u, Umat, row0, (c + 1) << 6, N, K, lane);
-      if (DELTA) load_tile(w, Wmat, row0, (c + 1) << 6, N, K, lane);
-      load_A(c + 1);
-    }
-    __syncthreads();  // activations of this chunk are visible to all waves
-
-    const int n = lane & 31, h = lane >> 5;
-    if (BF16) {
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const bf16x8 bu = *reinterpret_cast<const bf16x8*>(stU + n * T::STAGE_ROW + t * 32 + h * 16);
-        bf16x8 bw;
-        if (DELTA) bw = *reinterpret_cast<const bf16x8*>(stW + n * T::STAGE_ROW + t * 32 + h * 16);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          const bf16x8 ah = *reinterpret_cast<const bf16x8*>(ldsA + ((mb * 4 + t) * 64 + lane) * 16);
-          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bu, acc[mb], 0, 0, 0);
-          if (DELTA) {
-            const bf16x8 ad = *reinterpret_cast<const bf16x8*>(ldsD + ((mb * 4 + t) * 64 + lane) * 16);
-            acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, bw, acc[mb], 0, 0, 0);
-          }
-        }
+    if (!(dbg & 4)) stage_tile<BF16>(u, stU, lane);
+    if (DBUF) {
+      // copies(c) were issued before U(c+1) [8 loads] and W(c+1) [WREGS loads]
+      if (FULL && !PACK) {
+        wait_vmcnt<8 + (DELTA ? WREGS : 0)>();
+      } else {
+        wait_vmcnt<0>();
       }
+      __syncthreads();  // copies of every wave have landed; everyone is done with buffer buf^1
+      if (c + 1 < n_chunks && !(dbg & 2)) copy_AD(c + 1, buf ^ 1);
     } else {
+      __syncthreads();  // single buffer: everyone is done with the previous chunk
+      copy_AD(c, 0);
+      wait_vmcnt<0>();
+      __syncthreads();
+    }
+    if (c + 2 < n_chunks) load_tile<FULL>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
+
+    // Matrix products of this chunk in groups of MB products that share one B
+    // operand (k-step t, operand H or D).  The scheduler is fenced so that the LDS
+    // reads of group g+1 are issued right behind the products of group g.
+    const unsigned char* bufA = lds + buf * AD_BYTES;
+    const unsigned char* bufD = bufA + A_BYTES;
+    const int n = lane & 31, h = lane >> 5;
+    constexpr int OPS = DELTA ? 2 : 1;
+    constexpr int KS = BF16 ? 4 : 8;   // operand k-steps per chunk (16 k / 8 k each)
+    constexpr int NG = KS * OPS;
+    auto read_group = [&](f32x4 (&fr)[MB], int g) __attribute__((always_inline)) {
+      const int t = g / OPS, op = g % OPS;
 #pragma unroll
-      for (int g = 0; g < 8; ++g) {
-        const f32x4 bu = *reinterpret_cast<const f32x4*>(stU + n * T::STAGE_ROW + (8 * g + 4 * h) * 4);
-        f32x4 bw;
-        if (DELTA) bw = *reinterpret_cast<const f32x4*>(stW + n * T::STAGE_ROW + (8 * g + 4 * h) * 4);
+      for (int mb = 0; mb < MB; ++mb)
+        fr[mb] = *reinterpret_cast<const f32x4*>((op ? bufD : bufA) + ((mb * KS + t) * 64 + lane) * 16);
+    };
+    auto read_b = [&](int t) __attribute__((always_inline)) {
+      if (BF16) return *reinterpret_cast<const f32x4*>(stU + n * 128 + ((((2 * t + h) ^ (n >> 1)) & 7) << 4));
+      return *reinterpret_cast<const f32x4*>(stU + n * 256 + ((((2 * t + h) ^ n) & 15) << 4));
+    };
+    f32x4 fr[NG][MB];
+    f32x4 bq[KS];
+    if (dbg & 1) return;
+    bq[0] = read_b(0);
+    read_group(fr[0], 0);
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          const f32x4 ah = *reinterpret_cast<const f32x4*>(ldsA + ((mb * 8 + g) * 64 + lane) * 16);
+    for (int g = 0; g < NG; ++g) {
+      const int t = g / OPS, op = g % OPS;
+      __builtin_amdgcn_sched_barrier(0);
+      const f32x4 bv = op ? w[t] : bq[t];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ah[e], bu[e], acc[mb], 0, 0, 0);
-          if (DELTA) {
-            const f32x4 ad = *reinterpret_cast<const f32x4*>(ldsD + ((mb * 8 + g) * 64 + lane) * 16);
+      for (int mb = 0; mb < MB; ++mb) {
+        if (BF16) {
+          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[g][mb]),
+                                                            __builtin_bit_cast(bf16x8, bv), acc[mb], 0, 0, 0);
+        } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(ad[e], bw[e], acc[mb], 0, 0, 0);
-          }
+          for (int e = 0; e < 4; ++e) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(fr[g][mb][e], bv[e], acc[mb], 0, 0, 0);
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
+      // the reads of the next group are issued behind this group's products and
+      // complete while the matrix pipeline works through them
+      if (g + 1 < NG) {
+        read_group(fr[g + 1], g + 1);
+        if ((g + 1) % OPS == 0) bq[(g + 1) / OPS] = read_b((g + 1) / OPS);
+      }
+      if (PACK && op == 0) *reinterpret_cast<f32x4*>(Wt_wave + ((long long)c * WREGS + t) * 1024) = bq[t];
     }
+    if (DELTA && c + 2 < n_chunks) load_W(w, c + 2);
+  };
+
+  auto run = [&](auto full_c, auto pack_c) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_c)::value;
+    if (DBUF) copy_AD(0, 0);
+    load_tile<FULL>(u0, Urow0, lane_off, row0, 0, N, K, lane);
+    if (n_chunks > 1) load_tile<FULL>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
+    if (DELTA) {
+      load_W(w0, 0);
+      if (n_chunks > 1) load_W(w1, 1);
+    }
+    for (int c = 0; c < n_chunks; c += 2) {
+      chunk(full_c, pack_c, u0, w0, c);
+      if (c + 1 < n_chunks) chunk(full_c, pack_c, u1, w1, c + 1);
+    }
+  };
+  if (!DELTA && pack) {
+    if (all_full) run(std::true_type{}, std::true_type{}); else run(std::false_type{}, std::true_type{});
+  } else {
+    if (all_full) run(std::true_type{}, std::false_type{}); else run(std::false_type{}, std::false_type{});
   }
 
   // ---- epilogue.  Accumulator element j of block mb in lane (n, h) is sample row
@@ -329,7 +408,10 @@ template <bool BF16, bool DELTA, int MB, int NW>
 hipError_t launch_inst(const LayerArgs& a, hipStream_t stream) {
   using T = Tr<BF16>;
   constexpr int BN = 32 * NW;
-  constexpr int lds_bytes = MB * T::CH_BYTES * (DELTA ? 2 : 1) + NW * 32 * T::STAGE_ROW * (DELTA ? 2 : 1);
+  constexpr int AD_BYTES = MB * T::CH_BYTES * (DELTA ? 2 : 1);
+  constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
+  constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
+  constexpr int lds_bytes = AD_BYTES * (DBUF ? 2 : 1) + NW * STAGE_BYTES;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW>),
