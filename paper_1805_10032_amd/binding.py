@@ -13,7 +13,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "lib", "libzeno_hip.so")
+LIB_PATH = os.environ.get("ZENO_HIP_LIB") or os.path.join(_HERE, "lib", "libzeno_hip.so")
 
 ZENO_MAX_LAYERS = 8
 ZENO_MAX_CANDIDATES = 1024

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
-LIB_PATH = os.path.join(LIB_DIR, "libzeno_hip.so")
+LIB_PATH = os.environ.get("ZENO_BUILD_OUT") or os.path.join(LIB_DIR, "libzeno_hip.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["zeno_capi.hip", "zeno_layer.hip", "zeno_loss.hip", "zeno_aggregate.hip", "zeno_median.hip"]

@@ -63,27 +63,27 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
     double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     int s = 0;
     for (; s + kRowBatch <= n_sel; s += kRowBatch) {
-      f4u v[kRowBatch];
+      f32x4 v[kRowBatch];
 #pragma unroll
       for (int t = 0; t < kRowBatch; ++t) {
         const long long row = ALL ? (s + t) : sel_list[s + t];
-        v[t] = *reinterpret_cast<const f4u*>(col + row * d);
+        v[t] = load_stream4(col + row * d);
       }
 #pragma unroll
       for (int t = 0; t < kRowBatch; ++t) {
-        a0 += (double)v[t].x;
-        a1 += (double)v[t].y;
-        a2 += (double)v[t].z;
-        a3 += (double)v[t].w;
+        a0 += (double)v[t][0];
+        a1 += (double)v[t][1];
+        a2 += (double)v[t][2];
+        a3 += (double)v[t][3];
       }
     }
     for (; s < n_sel; ++s) {
       const long long row = ALL ? s : sel_list[s];
-      const f4u v = *reinterpret_cast<const f4u*>(col + row * d);
-      a0 += (double)v.x;
-      a1 += (double)v.y;
-      a2 += (double)v.z;
-      a3 += (double)v.w;
+      const f32x4 v = load_stream4(col + row * d);
+      a0 += (double)v[0];
+      a1 += (double)v[1];
+      a2 += (double)v[2];
+      a3 += (double)v[3];
     }
     f4u r;
     r.x = (float)(a0 / n);

@@ -18,6 +18,13 @@ struct __attribute__((packed, aligned(4))) f4u {
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef f32x4 f32x4_a4 __attribute__((aligned(4)));  // same, for 4-byte aligned addresses
+
+// Streaming (non-temporal) 128-bit load from a 4-byte aligned address: rows of G
+// are read exactly once, so they should not displace reusable lines in the caches.
+__device__ inline f32x4 load_stream4(const float* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const f32x4_a4*>(p));
+}
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));

@@ -38,6 +38,8 @@ namespace {
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
+constexpr int kSrcChunk = 32;  // sources per scheduling unit (one feature tile each)
+
 template <bool BF16>
 struct Tr;
 template <>
@@ -107,8 +109,11 @@ __device__ inline void load_tile(f32x4 (&u)[8], const float* __restrict__ tile, 
   if (FULL) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const f4u t = *reinterpret_cast<const f4u*>(tile + (long long)(4 * j) * K + lane_off);
-      u[j][0] = t.x; u[j][1] = t.y; u[j][2] = t.z; u[j][3] = t.w;
+#ifdef ZENO_LAYER_NT
+      u[j] = load_stream4(tile + (long long)(4 * j) * K + lane_off);
+#else
+      u[j] = *reinterpret_cast<const f32x4_a4*>(tile + (long long)(4 * j) * K + lane_off);
+#endif
     }
   } else {
     const int rsub = lane >> 4, kq = (lane & 15) << 2;
@@ -163,13 +168,21 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   unsigned char* stU = lds + AD_BYTES * (DBUF ? 2 : 1) + wave * STAGE_BYTES;
 
-  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2):
-  // consecutive slots of one XCD walk through the feature tiles of one source,
-  // so that a source's activations are fetched into a single L2.
+  // Workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8), each with its
+  // own L2.  The work is cut into units of one feature tile x a chunk of up to
+  // kSrcChunk sources; units go round-robin to the XCDs and the workgroups of a
+  // unit occupy consecutive slots of their XCD.  The workgroups that run together
+  // on an XCD therefore stream the SAME rows of W (second product) at about the
+  // same time and share them through that L2, while everything that is private to
+  // a source (its activations) is reused inside the workgroup through LDS.
   const int n_tiles = (cover_rows(a.N, a.last) + BN - 1) / BN;
+  const int cc = a.n_src < kSrcChunk ? a.n_src : kSrcChunk;
+  const int n_cchunks = (a.n_src + cc - 1) / cc;
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int src_local = (slot / n_tiles) * 8 + xcd;
-  const int nt = slot % n_tiles;
+  const int unit = (slot / cc) * 8 + xcd;
+  if (unit >= n_tiles * n_cchunks) return;
+  const int nt = unit / n_cchunks;
+  const int src_local = (unit % n_cchunks) * cc + slot % cc;
   if (src_local >= a.n_src) return;
   const int s = a.src_begin + src_local;
   const bool is_base = (s == a.m);
@@ -420,13 +433,16 @@ hipError_t launch_inst(const LayerArgs& a, hipStream_t stream) {
     attr_set = true;
   }
   const int n_tiles = (cover_rows(a.N, a.last) + BN - 1) / BN;
-  const int grid = ((a.n_src + 7) / 8) * 8 * n_tiles;
+  const int cc = a.n_src < kSrcChunk ? a.n_src : kSrcChunk;
+  const int units = n_tiles * ((a.n_src + cc - 1) / cc);
+  const int grid = ((units + 7) / 8) * 8 * cc;
   hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW>), dim3(grid), dim3(64 * NW), lds_bytes, stream, a);
   return hipGetLastError();
 }
 
 template <bool BF16, bool DELTA, int MB>
 hipError_t launch_nw(const LayerArgs& a, int NW, hipStream_t stream) {
+  if (NW == 8) return launch_inst<BF16, DELTA, MB, 8>(a, stream);
   if (NW == 4) return launch_inst<BF16, DELTA, MB, 4>(a, stream);
   return launch_inst<BF16, DELTA, MB, 1>(a, stream);
 }
@@ -438,12 +454,14 @@ hipError_t launch_mb(const LayerArgs& a, int MB, int NW, hipStream_t stream) {
   return launch_nw<BF16, DELTA, 4>(a, NW, stream);
 }
 
-// Waves per workgroup: 4 (128 features per workgroup) when that still gives at
-// least two workgroups per compute unit, else 1 (32 features) to spread a narrow
-// layer over more compute units.
+// Waves per workgroup (32 output features each): the widest workgroup that still
+// gives every compute unit work, since a wider workgroup re-reads less of the
+// activations per byte of weights; narrow layers fall back to one wave to spread
+// over more compute units.
 int pick_nw(int rows, int n_src) {
-  const long long wg4 = (long long)((rows + 127) / 128) * n_src;
-  return wg4 >= 512 ? 4 : 1;
+  if ((long long)((rows + 255) / 256) * n_src >= 256) return 8;
+  if ((long long)((rows + 127) / 128) * n_src >= 256) return 4;
+  return 1;
 }
 
 }  // namespace
