@@ -30,6 +30,9 @@ def parse_args():
     ap.add_argument("--buffers", type=int, default=0,
                     help="distinct copies of G to rotate over (0 = automatic: enough to defeat the 256 MB cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain elementwise copy-like kernel (torch.ceil, 4 GiB in, 4 GiB out) so that rocprofv3 "
+                         "byte counters collected over this command can be scaled")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU oracle sample")
     return ap.parse_args()
 
@@ -120,6 +123,14 @@ def main():
         B.zeno_score(mdl, w.x, G, w.features, w.gamma, w.rho, labels=w.labels, targets=w.targets,
                      scores=scores, workspace=ws)
         B.zeno_aggregate(G, scores, b, out=out, selected=sel)
+
+    if a.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.ceil(src, out=dst)   # a plain elementwise kernel: reads 4 GiB, writes 4 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(a.warmup):
         step(i)
