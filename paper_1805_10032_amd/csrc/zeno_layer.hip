@@ -38,7 +38,7 @@ namespace {
 typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-constexpr int kSrcChunk = 32;  // sources per scheduling unit (one feature tile each)
+constexpr int kSrcChunk = 16;  // sources per scheduling unit (one feature tile each)
 
 template <bool BF16>
 struct Tr;
@@ -116,11 +116,24 @@ __device__ inline void load_tile(f32x4 (&u)[8], const float* __restrict__ tile, 
 #endif
     }
   } else {
+    // Ragged tile.  Rows beyond the matrix read row N-1 instead (always in bounds)
+    // and are zeroed afterwards; only the last K chunk of a width that is not a
+    // multiple of 64 takes the element-wise path.
     const int rsub = lane >> 4, kq = (lane & 15) << 2;
+    const bool k_full = k0 + 64 <= K;  // wave-uniform
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int row = row0 + 4 * j + rsub;
-      u[j] = load4_masked(tile + (long long)(4 * j + rsub) * K, kq, K - k0, row < N);
+      const int back = row < N ? 0 : row - (N - 1);
+      const float* p = tile + (long long)(4 * j + rsub - back) * K;
+      f32x4 v;
+      if (k_full) {
+        v = *reinterpret_cast<const f32x4_a4*>(p + kq);
+      } else {
+        v = load4_masked(p, kq, K - k0, true);
+      }
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      u[j] = row < N ? v : zero;
     }
   }
 }
@@ -271,6 +284,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
       }
       __syncthreads();  // copies of every wave have landed; everyone is done with buffer buf^1
       if (c + 1 < n_chunks && !(dbg & 2)) copy_AD(c + 1, buf ^ 1);
+      __builtin_amdgcn_sched_barrier(0);  // the wait above counts on the copies being issued before the next loads
     } else {
       __syncthreads();  // single buffer: everyone is done with the previous chunk
       copy_AD(c, 0);
@@ -333,6 +347,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   auto run = [&](auto full_c, auto pack_c) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_c)::value;
     if (DBUF) copy_AD(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     load_tile<FULL>(u0, Urow0, lane_off, row0, 0, N, K, lane);
     if (n_chunks > 1) load_tile<FULL>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
     if (DELTA) {
