@@ -209,11 +209,46 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
   float* dZ = reinterpret_cast<float*>(ws + p.off_dz);
   const int C = D.dims[L];
 
+  auto make_job = [&](int l) {
+    LayerJob j;
+    std::memset(&j, 0, sizeof(j));
+    j.w_off = model->w_off[l];
+    j.b_off = model->b_off[l];
+    j.N = D.dims[l + 1];
+    j.K = D.dims[l];
+    j.Kp = pad64(j.K);
+    j.Np = pad64(j.N);
+    j.last = (l + 1 == L);
+    j.A_base = l == 0 ? ws + p.off_feat : ws + p.off_hbase[l - 1];
+    j.Wt = l > 0 ? ws + p.off_wt[l] : nullptr;
+    j.Z0 = reinterpret_cast<float*>(ws + p.off_z0[l]);
+    j.H_base = j.last ? nullptr : ws + p.off_hbase[l];
+    return j;
+  };
+  // bytes of layer l's block in one parameter vector (what one source streams)
+  auto layer_bytes = [&](int l) {
+    return 4.0 * ((double)D.dims[l + 1] * D.dims[l] + (model->b_off[l] >= 0 ? D.dims[l + 1] : 0));
+  };
+  LayerArgs common;
+  std::memset(&common, 0, sizeof(common));
+  common.G = G;
+  common.x = x;
+  common.d = model->d;
+  common.dZ = dZ;
+  common.gamma = gamma;
+  common.neg_inv_gamma = gamma > 0.f ? -1.0f / gamma : 0.f;
+#ifdef ZENO_TIMING_EXPERIMENTS
+  common.dbg = std::getenv("ZENO_DEBUG_SKIP") ? std::atoi(std::getenv("ZENO_DEBUG_SKIP")) : 0;
+#endif
+
   // partial-norm slots actually used by the candidate launches
   int p_off[ZENO_MAX_LAYERS], P = 0;
   for (int l = 0; l < L; ++l) {
+    LayerArgs t = common;
+    t.n_cand = m;
+    t.cj = make_job(l);
     p_off[l] = P;
-    P += layer_tiles(D.dims[l + 1], l + 1 == L, L == 1 ? m + 1 : m);
+    P += layer_tiles(t);
   }
 
   for (int begin = 0; begin < n_r; begin += p.pass_rows) {
@@ -224,62 +259,56 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
       ZENO_TRY(launch_pack_features(batch->features + (size_t)begin * D.dims[0], rows, D.dims[0], pad64(D.dims[0]),
                                     p.MB, bf16, ws + p.off_feat, stream));
     }
-    for (int l = 0; l < L; ++l) {
-      LayerArgs a;
-      std::memset(&a, 0, sizeof(a));
-      a.G = G;
-      a.x = x;
-      a.d = model->d;
-      a.m = m;
-      a.w_off = model->w_off[l];
-      a.b_off = model->b_off[l];
-      a.N = D.dims[l + 1];
-      a.K = D.dims[l];
-      a.Kp = pad64(a.K);
-      a.Np = pad64(a.N);
+    // Launch order: [pass at x, layer 0] then for every layer l the candidates'
+    // layer l together with the pass at x through layer l+1 (whose input the
+    // previous launch completed).  A single-layer model needs one launch.
+    if (L > 1) {
+      LayerArgs a = common;
       a.n_r = rows;
-      a.last = (l + 1 == L);
-      a.A_base = l == 0 ? ws + p.off_feat : ws + p.off_hbase[l - 1];
-      a.Wt = l > 0 ? ws + p.off_wt[l] : nullptr;
-      a.Z0 = reinterpret_cast<float*>(ws + p.off_z0[l]);
-      a.dZ = dZ;
-      a.H_base = a.last ? nullptr : ws + p.off_hbase[l];
-      a.gamma = gamma;
-      a.neg_inv_gamma = gamma > 0.f ? -1.0f / gamma : 0.f;
+      a.has_base = 1;
+      a.bj = make_job(0);
+      ProfScope ps(ZENO_KERNEL_LAYER_BASE, 0, layer_bytes(0), stream);
+      ZENO_TRY(launch_layer(a, bf16, false, p.MB, stream));
+    }
+    for (int l = 0; l < L; ++l) {
+      LayerArgs a = common;
+      a.n_r = rows;
+      a.n_cand = m;
+      a.cj = make_job(l);
       a.norm_partials = first_pass ? norm_partials : nullptr;
       a.P = P;
       a.p_off = p_off[l];
-#ifdef ZENO_TIMING_EXPERIMENTS
-      a.dbg = std::getenv("ZENO_DEBUG_SKIP") ? std::atoi(std::getenv("ZENO_DEBUG_SKIP")) : 0;
-#endif
-      if (L > 1) {
+      double bytes = layer_bytes(l) * m;
+      if (L == 1) {
+        a.has_base = 1;
+        a.bj = make_job(0);
+        bytes += layer_bytes(0);
+      } else {
         a.A_cand = l == 0 ? nullptr : ws + p.off_hc[(l - 1) & 1];
         a.D_cand = l == 0 ? nullptr : ws + p.off_dc[(l - 1) & 1];
         a.A_stride = (long long)p.cand_stride;
         a.H_cand = ws + p.off_hc[l & 1];
         a.Dl_cand = ws + p.off_dc[l & 1];
         a.H_stride = (long long)p.cand_stride;
-      }
-      // bytes of this layer's block in one parameter vector (what one source streams)
-      const double layer_bytes = 4.0 * ((double)a.N * a.K + (a.b_off >= 0 ? a.N : 0));
-      if (L == 1) {
-        // single layer: the pass at x and the m candidates share one launch
-        a.src_begin = 0;
-        a.n_src = m + 1;
-        ProfScope ps(ZENO_KERNEL_LAYER_CAND, l, layer_bytes * (m + 1), stream);
-        ZENO_TRY(launch_layer(a, bf16, false, p.MB, stream));
-      } else {
-        a.src_begin = m;  // the pass at x first: the candidates' epilogue needs Z0 of this layer
-        a.n_src = 1;
-        {
-          ProfScope ps(ZENO_KERNEL_LAYER_BASE, l, layer_bytes, stream);
-          ZENO_TRY(launch_layer(a, bf16, false, p.MB, stream));
+        if (l + 1 < L) {
+          a.has_base = 1;
+          a.bj = make_job(l + 1);
+          if (layer_merge_pays(a, bf16, l > 0, p.MB)) {
+            bytes += layer_bytes(l + 1);
+          } else {
+            // the extra workgroups would cost a whole extra round: run the pass at x on its own first
+            LayerArgs b = common;
+            b.n_r = rows;
+            b.has_base = 1;
+            b.bj = a.bj;
+            a.has_base = 0;
+            ProfScope ps(ZENO_KERNEL_LAYER_BASE, l + 1, layer_bytes(l + 1), stream);
+            ZENO_TRY(launch_layer(b, bf16, false, p.MB, stream));
+          }
         }
-        a.src_begin = 0;
-        a.n_src = m;
-        ProfScope ps(ZENO_KERNEL_LAYER_CAND, l, layer_bytes * m, stream);
-        ZENO_TRY(launch_layer(a, bf16, l > 0, p.MB, stream));
       }
+      ProfScope ps(ZENO_KERNEL_LAYER_CAND, l, bytes, stream);
+      ZENO_TRY(launch_layer(a, bf16, l > 0, p.MB, stream));
     }
     ProfScope ps(ZENO_KERNEL_LOSS, 0, 4.0 * (m + 1) * rows * C, stream);
     ZENO_TRY(launch_loss(reinterpret_cast<const float*>(ws + p.off_z0[L - 1]), dZ, batch->labels, batch->targets,

@@ -32,30 +32,38 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// One launch of the streaming layer kernel (zeno_layer.hip).  Sources are
-// numbered 0..m-1 for the candidates G[s] and m for the current parameters x.
+// One linear layer as a launch of the streaming layer kernel sees it.
+struct LayerJob {
+  long long w_off;     // offset of W_l inside a parameter vector
+  long long b_off;     // offset of b_l, or -1
+  int N, K;            // layer width out / in
+  int Kp;              // K rounded up to a multiple of 64 (tiled operand width)
+  int Np;              // N rounded up to a multiple of 64 (tiled width of the next layer's operand)
+  int last;            // 1: output layer (raw fp32 results instead of tiled activations)
+  const void* A_base;  // tiled activations of the pass at x that feed this layer
+  void* Wt;            // W_l in matrix-operand order (written by the pass at x, read by the candidates); may be NULL
+  float* Z0;           // [n_r x N] pre-activations at x (written by the pass at x, read by the candidates)
+  void* H_base;        // tiled output activations of the pass at x (hidden layers)
+};
+
+// One launch of the streaming layer kernel (zeno_layer.hip): the candidates'
+// pass through layer `cj` (n_cand workgroup columns, may be 0) and, in the same
+// launch, the pass at x through layer `bj` (has_base; normally the NEXT layer,
+// whose input the previous launch finished), so that the short pass at x hides
+// behind the long candidate stream.
 struct LayerArgs {
   const float* G;       // [m x d]
   const float* x;       // [d]
   long long d;          // leading dimension of G
-  int m;                // number of candidates
-  int src_begin;        // first source of this launch
-  int n_src;            // number of sources of this launch
-  long long w_off;      // offset of W_l inside a parameter vector
-  long long b_off;      // offset of b_l, or -1
-  int N, K;             // layer width out / in
-  int Kp;               // K rounded up to a multiple of 64 (tiled operand width)
-  int Np;               // N rounded up to a multiple of 64 (tiled width of the next layer's operand)
+  int n_cand;           // candidates in this launch (0 or m)
+  int has_base;         // 1: the launch also runs the pass at x through bj
+  int base_blocks;      // leading block indices reserved for the pass at x (multiple of 8)
   int n_r;              // valid samples (rows) in this pass
-  int last;             // 1: this is the output layer (raw fp32 results)
-  const void* A_base;   // tiled activations of the pass at x, input of this layer
-  const void* A_cand;   // tiled activations of candidate 0 (NULL: all candidates read A_base, first layer)
+  LayerJob cj, bj;
+  const void* A_cand;   // tiled activations of candidate 0 (NULL: all candidates read cj.A_base, first layer)
   const void* D_cand;   // tiled scaled activation differences of candidate 0 (delta launches only)
   long long A_stride;   // bytes between consecutive candidates in A_cand / D_cand
-  void* Wt;             // W_l in matrix-operand order: written by source m, read by delta launches; may be NULL
-  float* Z0;            // [n_r x N] pre-activations at x: written by source m, read by the others
   float* dZ;            // [m x n_r x N] change of the output layer's pre-activations (last layer)
-  void* H_base;         // tiled output activations at x (hidden layers)
   void* H_cand;         // tiled output activations of candidate 0 (hidden layers)
   void* Dl_cand;        // tiled scaled output differences of candidate 0 (hidden layers)
   long long H_stride;   // bytes between consecutive candidates in H_cand / Dl_cand
@@ -71,7 +79,8 @@ struct LayerArgs {
 hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, int MB, bool bf16,
                                 void* tiled, hipStream_t stream);
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream);
-int layer_tiles(int N, int last, int n_src);  // partial-norm slots a launch over a layer of width N uses
+bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB);  // run a.bj inside the candidates' launch?
+int layer_tiles(const LayerArgs& a);  // partial-norm slots (feature tiles) of the candidate job of this launch
 hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, const float* targets,
                        int loss, int m, int n_r_total, int chunk_begin, int chunk_rows, int C,
                        double* sample_diff, hipStream_t stream);

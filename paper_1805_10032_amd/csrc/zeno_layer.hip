@@ -181,43 +181,56 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   unsigned char* stU = lds + AD_BYTES * (DBUF ? 2 : 1) + wave * STAGE_BYTES;
 
-  // Workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8), each with its
-  // own L2.  The work is cut into units of one feature tile x a chunk of up to
-  // kSrcChunk sources; units go round-robin to the XCDs and the workgroups of a
-  // unit occupy consecutive slots of their XCD.  The workgroups that run together
+  // Which job: the leading base_blocks block indices run the pass at x (one
+  // feature tile each), the rest the candidates.
+  // Candidates: workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8), each
+  // with its own L2.  The work is cut into units of one feature tile x a chunk of up
+  // to kSrcChunk candidates; units go round-robin to the XCDs and the workgroups of
+  // a unit occupy consecutive slots of their XCD.  The workgroups that run together
   // on an XCD therefore stream the SAME rows of W (second product) at about the
   // same time and share them through that L2, while everything that is private to
-  // a source (its activations) is reused inside the workgroup through LDS.
-  const int n_tiles = (cover_rows(a.N, a.last) + BN - 1) / BN;
-  const int cc = a.n_src < kSrcChunk ? a.n_src : kSrcChunk;
-  const int n_cchunks = (a.n_src + cc - 1) / cc;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int unit = (slot / cc) * 8 + xcd;
-  if (unit >= n_tiles * n_cchunks) return;
-  const int nt = unit / n_cchunks;
-  const int src_local = (unit % n_cchunks) * cc + slot % cc;
-  if (src_local >= a.n_src) return;
-  const int s = a.src_begin + src_local;
-  const bool is_base = (s == a.m);
+  // a candidate (its activations) is reused inside the workgroup through LDS.
+  const bool is_base = (int)blockIdx.x < a.base_blocks;
+  const LayerJob& J = is_base ? a.bj : a.cj;
+  const int N = J.N, K = J.K, last = J.last, Np = J.Np;
+  const int n_chunks = J.Kp >> 6;
+  const int n_tiles = (cover_rows(N, last) + BN - 1) / BN;
+  int nt, s = 0;
+  if (is_base) {
+    nt = blockIdx.x;
+    if (nt >= n_tiles) return;
+  } else {
+    const int bid = blockIdx.x - a.base_blocks;
+    const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
+    const int n_cchunks = (a.n_cand + cc - 1) / cc;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int unit = (slot / cc) * 8 + xcd;
+    if (unit >= n_tiles * n_cchunks) return;
+    nt = unit / n_cchunks;
+    s = (unit % n_cchunks) * cc + slot % cc;
+    if (s >= a.n_cand) return;
+  }
   const float* __restrict__ P = is_base ? a.x : a.G + (long long)s * a.d;
   const int row0 = nt * BN + wave * 32;
-  const int N = a.N, K = a.K;
-  const int n_chunks = a.Kp >> 6;
-  const float* __restrict__ Urow0 = P + a.w_off + (long long)row0 * K;  // wave-uniform
+  const float* __restrict__ Urow0 = P + J.w_off + (long long)row0 * K;  // wave-uniform
   const unsigned lane_off = (unsigned)(lane >> 4) * (unsigned)K + ((lane & 15) << 2);
   const bool full_rows = row0 + 32 <= N;
 
-  const unsigned char* Ag = reinterpret_cast<const unsigned char*>(a.A_base);
+  const unsigned char* Ag = reinterpret_cast<const unsigned char*>(J.A_base);
   if (!is_base && a.A_cand != nullptr) Ag = reinterpret_cast<const unsigned char*>(a.A_cand) + (long long)s * a.A_stride;
-  const unsigned char* Dg = DELTA ? reinterpret_cast<const unsigned char*>(a.D_cand) + (long long)s * a.A_stride : nullptr;
+  // The pass at x has no second product: its D operand is a harmless alias of H
+  // and its products are skipped.
+  const bool has_delta = DELTA && !is_base;
+  const unsigned char* Dg = has_delta ? reinterpret_cast<const unsigned char*>(a.D_cand) + (long long)s * a.A_stride : Ag;
 
-  const bool pack = is_base && a.Wt != nullptr;
-  unsigned char* Wt_wave = reinterpret_cast<unsigned char*>(a.Wt) +
+  const bool pack = is_base && J.Wt != nullptr;
+  unsigned char* Wt_wave = reinterpret_cast<unsigned char*>(J.Wt) +
                            ((long long)(row0 >> 5) * n_chunks * WREGS * 64 + lane) * 16;
-  // The main loop exists in up to four versions chosen per wave: FULL (every
-  // weight tile lies inside the matrix: straight-line loads, and the in-order
-  // completion of loads lets a chunk wait for exactly its own activation copies)
-  // or masked, and PACK (the pass at x also writes W in operand order) or not.
+  // The main loop exists in four versions chosen per wave: FULL (every weight tile
+  // lies inside the matrix: straight-line loads, and the in-order completion of
+  // loads lets a candidate chunk wait for exactly its own activation copies) or
+  // ragged, and BASE (pass at x: no second product, writes W in operand order) or
+  // candidate.
   const bool all_full = full_rows && (K & 63) == 0;
 
   f32x16 acc[MB];
@@ -264,9 +277,10 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   // One K chunk.  Its weight tile sits in registers u (loaded two chunks ago); its
   // activation operands were copied into LDS buffer c&1 during the previous chunk.
   // Issue order per chunk: copies(c+1), U(c+2), [matrix products of c], W(c+2).
-  auto chunk = [&](auto full_c, auto pack_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
+  auto chunk = [&](auto full_c, auto base_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_c)::value;
-    constexpr bool PACK = decltype(pack_c)::value;
+    constexpr bool BASE = decltype(base_c)::value;   // this workgroup runs the pass at x
+    constexpr bool SECOND = DELTA && !BASE;           // second product D W^T present
     const int buf = DBUF ? (c & 1) : 0;
     if (do_norm) {
       float q = 0.f;
@@ -277,8 +291,8 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
     if (!(dbg & 4)) stage_tile<BF16>(u, stU, lane);
     if (DBUF) {
       // copies(c) were issued before U(c+1) [8 loads] and W(c+1) [WREGS loads]
-      if (FULL && !PACK) {
-        wait_vmcnt<8 + (DELTA ? WREGS : 0)>();
+      if (FULL && !BASE) {
+        wait_vmcnt<8 + (SECOND ? WREGS : 0)>();
       } else {
         wait_vmcnt<0>();
       }
@@ -324,6 +338,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
       const f32x4 bv = op ? w[t] : bq[t];
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
+        if (op == 1 && !SECOND) break;  // the pass at x has no second product
         if (BF16) {
           acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[g][mb]),
                                                             __builtin_bit_cast(bf16x8, bv), acc[mb], 0, 0, 0);
@@ -339,27 +354,28 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
         read_group(fr[g + 1], g + 1);
         if ((g + 1) % OPS == 0) bq[(g + 1) / OPS] = read_b((g + 1) / OPS);
       }
-      if (PACK && op == 0) *reinterpret_cast<f32x4*>(Wt_wave + ((long long)c * WREGS + t) * 1024) = bq[t];
+      if (BASE && pack && op == 0) *reinterpret_cast<f32x4*>(Wt_wave + ((long long)c * WREGS + t) * 1024) = bq[t];
     }
-    if (DELTA && c + 2 < n_chunks) load_W(w, c + 2);
+    if (SECOND && c + 2 < n_chunks) load_W(w, c + 2);
   };
 
-  auto run = [&](auto full_c, auto pack_c) __attribute__((always_inline)) {
+  auto run = [&](auto full_c, auto base_c) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_c)::value;
+    constexpr bool SECOND = DELTA && !decltype(base_c)::value;
     if (DBUF) copy_AD(0, 0);
     __builtin_amdgcn_sched_barrier(0);
     load_tile<FULL>(u0, Urow0, lane_off, row0, 0, N, K, lane);
     if (n_chunks > 1) load_tile<FULL>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
-    if (DELTA) {
+    if (SECOND) {
       load_W(w0, 0);
       if (n_chunks > 1) load_W(w1, 1);
     }
     for (int c = 0; c < n_chunks; c += 2) {
-      chunk(full_c, pack_c, u0, w0, c);
-      if (c + 1 < n_chunks) chunk(full_c, pack_c, u1, w1, c + 1);
+      chunk(full_c, base_c, u0, w0, c);
+      if (c + 1 < n_chunks) chunk(full_c, base_c, u1, w1, c + 1);
     }
   };
-  if (!DELTA && pack) {
+  if (is_base) {
     if (all_full) run(std::true_type{}, std::true_type{}); else run(std::false_type{}, std::true_type{});
   } else {
     if (all_full) run(std::true_type{}, std::false_type{}); else run(std::false_type{}, std::false_type{});
@@ -371,7 +387,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   const int feat = row0 + n;
   const bool feat_ok = feat < N;
   float bias = 0.f;
-  if (a.b_off >= 0 && feat_ok) bias = P[a.b_off + feat];
+  if (J.b_off >= 0 && feat_ok) bias = P[J.b_off + feat];
   if (do_norm && h == 0) nrm += (double)(bias * bias);
 
 #pragma unroll
@@ -382,24 +398,24 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
       const bool ok = feat_ok && r < a.n_r;
       const float val = acc[mb][j] + bias;
       if (is_base) {
-        if (ok) a.Z0[(long long)r * N + feat] = val;
-        if (!a.last && feat < a.Np) store_tiled<BF16>(a.H_base, r, feat, a.Np, ok ? relu_nan(val) : 0.f);
+        if (ok) J.Z0[(long long)r * N + feat] = val;
+        if (!last && feat < Np) store_tiled<BF16>(J.H_base, r, feat, Np, ok ? relu_nan(val) : 0.f);
       } else {
         const float dz = -a.gamma * val;
-        if (a.last) {
+        if (last) {
           if (ok) a.dZ[((long long)s * a.n_r + r) * N + feat] = dz;
-        } else if (feat < a.Np) {
+        } else if (feat < Np) {
           float hv = 0.f, dv = 0.f;
           if (ok) {
-            const float z0 = a.Z0[(long long)r * N + feat];
+            const float z0 = J.Z0[(long long)r * N + feat];
             const float zs = z0 + dz;
             hv = relu_nan(zs);
             // relu(z0 + dz) - relu(z0) without cancellation
             dv = (z0 > 0.f) ? ((dz < -z0) ? -z0 : dz) : hv;
             dv *= a.neg_inv_gamma;
           }
-          store_tiled<BF16>(reinterpret_cast<unsigned char*>(a.H_cand) + (long long)s * a.H_stride, r, feat, a.Np, hv);
-          store_tiled<BF16>(reinterpret_cast<unsigned char*>(a.Dl_cand) + (long long)s * a.H_stride, r, feat, a.Np, dv);
+          store_tiled<BF16>(reinterpret_cast<unsigned char*>(a.H_cand) + (long long)s * a.H_stride, r, feat, Np, hv);
+          store_tiled<BF16>(reinterpret_cast<unsigned char*>(a.Dl_cand) + (long long)s * a.H_stride, r, feat, Np, dv);
         }
       }
     }
@@ -432,8 +448,10 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
   }
 }
 
+int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
+
 template <bool BF16, bool DELTA, int MB, int NW>
-hipError_t launch_inst(const LayerArgs& a, hipStream_t stream) {
+hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
   using T = Tr<BF16>;
   constexpr int BN = 32 * NW;
   constexpr int AD_BYTES = MB * T::CH_BYTES * (DELTA ? 2 : 1);
@@ -447,12 +465,49 @@ hipError_t launch_inst(const LayerArgs& a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int n_tiles = (cover_rows(a.N, a.last) + BN - 1) / BN;
-  const int cc = a.n_src < kSrcChunk ? a.n_src : kSrcChunk;
-  const int units = n_tiles * ((a.n_src + cc - 1) / cc);
-  const int grid = ((units + 7) / 8) * 8 * cc;
-  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW>), dim3(grid), dim3(64 * NW), lds_bytes, stream, a);
+  a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) + 7) / 8 * 8 : 0;
+  int cand_blocks = 0;
+  if (a.n_cand > 0) {
+    const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
+    const int units = job_tiles(a.cj, BN) * ((a.n_cand + cc - 1) / cc);
+    cand_blocks = ((units + 7) / 8) * 8 * cc;
+  }
+  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW), lds_bytes,
+                     stream, a);
   return hipGetLastError();
+}
+
+// Workgroups of this instantiation that fit on one compute unit (cached).
+template <bool BF16, bool DELTA, int MB, int NW>
+int wgs_per_cu_inst() {
+  static int cached = 0;
+  if (cached == 0) {
+    using T = Tr<BF16>;
+    constexpr int AD_BYTES = MB * T::CH_BYTES * (DELTA ? 2 : 1);
+    constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
+    constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
+    constexpr int lds_bytes = AD_BYTES * (DBUF ? 2 : 1) + NW * STAGE_BYTES;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW>),
+                                                     64 * NW, lds_bytes) != hipSuccess || n < 1)
+      n = 1;
+    cached = n;
+  }
+  return cached;
+}
+
+template <bool BF16, bool DELTA, int MB>
+int wgs_per_cu_nw(int NW) {
+  if (NW == 8) return wgs_per_cu_inst<BF16, DELTA, MB, 8>();
+  if (NW == 4) return wgs_per_cu_inst<BF16, DELTA, MB, 4>();
+  return wgs_per_cu_inst<BF16, DELTA, MB, 1>();
+}
+
+template <bool BF16, bool DELTA>
+int wgs_per_cu_mb(int MB, int NW) {
+  if (MB == 1) return wgs_per_cu_nw<BF16, DELTA, 1>(NW);
+  if (MB == 2) return wgs_per_cu_nw<BF16, DELTA, 2>(NW);
+  return wgs_per_cu_nw<BF16, DELTA, 4>(NW);
 }
 
 template <bool BF16, bool DELTA, int MB>
@@ -479,12 +534,37 @@ int pick_nw(int rows, int n_src) {
   return 1;
 }
 
+// Waves per workgroup of a launch, from the job that dominates it.
+int launch_nw_for(const LayerArgs& a) {
+  if (a.n_cand > 0) return pick_nw(cover_rows(a.cj.N, a.cj.last), a.n_cand);
+  return pick_nw(cover_rows(a.bj.N, a.bj.last), 1);
+}
+
 }  // namespace
 
-int layer_tiles(int N, int last, int n_src) {
-  const int rows = cover_rows(N, last);
-  const int NW = pick_nw(rows, n_src);
-  return (rows + 32 * NW - 1) / (32 * NW);
+int layer_tiles(const LayerArgs& a) { return job_tiles(a.cj, 32 * launch_nw_for(a)); }
+
+// Should the pass at x (a.bj) ride in the candidates' launch?  Workgroups run in
+// rounds of (compute units x resident workgroups); the extra workgroups are free
+// when they fit into the last round and cost a whole extra round when the
+// candidates fill their rounds exactly, unless there are many rounds anyway.
+bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB) {
+  if (a.n_cand <= 0) return true;
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+      v = 256;
+    n_cu = v;
+  }
+  const int NW = launch_nw_for(a);
+  const int per_cu = bf16 ? (delta ? wgs_per_cu_mb<true, true>(MB, NW) : wgs_per_cu_mb<true, false>(MB, NW))
+                          : (delta ? wgs_per_cu_mb<false, true>(MB, NW) : wgs_per_cu_mb<false, false>(MB, NW));
+  const long long slots = (long long)n_cu * per_cu;
+  const long long cand = (long long)job_tiles(a.cj, 32 * NW) * a.n_cand;
+  const long long base = job_tiles(a.bj, 32 * NW);
+  const long long rounds_without = (cand + slots - 1) / slots, rounds_with = (cand + base + slots - 1) / slots;
+  return rounds_with == rounds_without || rounds_without >= 8;
 }
 
 hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, int MB, bool bf16, void* tiled,
@@ -501,7 +581,7 @@ hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, i
 }
 
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream) {
-  const int NW = pick_nw(cover_rows(a.N, a.last), a.n_src);
+  const int NW = launch_nw_for(a);
   if (bf16) {
     return delta ? launch_mb<true, true>(a, MB, NW, stream) : launch_mb<true, false>(a, MB, NW, stream);
   }
