@@ -162,7 +162,19 @@ def main():
         e[0] += 1
         e[1] += ms
         e[2] += nbytes
-    kernels = {k: {"launches_per_step": v[0] / n_prof, "avg_ms": v[1] / v[0],
+    # the two baseline aggregators on the same G (Section 6.1.1, Definition 4)
+    B.profile_enable(True)
+    for i in range(3):
+        B.zeno_mean(Gs[i % n_buf], out=out)
+        B.zeno_median(Gs[i % n_buf], out=out)
+    torch.cuda.synchronize()
+    for name, layer, ms, nbytes in B.profile_collect():
+        e = per.setdefault(name, [0, 0.0, 0.0])
+        e[0] += 1
+        e[1] += ms
+        e[2] += nbytes
+    B.profile_enable(False)
+    kernels = {k: {"launches_per_step": v[0] / (3 if k in ("mean", "median") else n_prof), "avg_ms": v[1] / v[0],
                    "algorithmic_GBps": (v[2] / v[0]) / (v[1] / v[0]) / 1e6} for k, v in per.items()}
     layers = {k: {"avg_ms": v[1] / v[0], "algorithmic_GBps": v[2] / v[1] / 1e6} for k, v in per_layer.items()}
     dom = per["layer_cand"]

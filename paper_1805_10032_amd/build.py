@@ -33,22 +33,44 @@ def _hipcc():
     return "hipcc"
 
 
-def _compile(src):
+PER_FILE_FLAGS = {}
+
+
+def _fresh(obj, src, stamp):
+    """True if obj was built from the current source, headers and flags."""
+    try:
+        if open(obj + ".flags").read() != stamp:
+            return False
+        t = os.path.getmtime(obj)
+        deps = [os.path.join(CSRC, src), os.path.join(CSRC, "zeno_internal.h"), os.path.join(ROOT, "include", "zeno.h")]
+        return all(os.path.getmtime(d) < t for d in deps)
+    except OSError:
+        return False
+
+
+def _compile(src, force=True):
     obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
     extra = os.environ.get("ZENO_EXTRA_HIPCC_FLAGS", "").split()
-    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    stamp = " ".join([*HIPCC_FLAGS, *PER_FILE_FLAGS.get(src, []), *extra])
+    if not force and _fresh(obj, src, stamp):
+        return obj, ""
+    cmd = [_hipcc(), *HIPCC_FLAGS, *PER_FILE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in res.stderr.splitlines() if "not a recognized feature" not in l)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+    with open(obj + ".flags", "w") as fh:
+        fh.write(stamp)
     return obj, err
 
 
-def build(verbose=True):
+def build(verbose=True, force=True):
+    """Compile and link.  force=False reuses objects whose source, headers and
+    flags are unchanged (the 128-wide median network alone takes minutes)."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     os.makedirs(LIB_DIR, exist_ok=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        results = list(ex.map(_compile, SOURCES))
+        results = list(ex.map(lambda s: _compile(s, force), SOURCES))
     for obj, err in results:
         if verbose and err.strip():
             print(err, file=sys.stderr)
@@ -62,4 +84,4 @@ def build(verbose=True):
 
 
 if __name__ == "__main__":
-    build()
+    build(force="--force" in sys.argv)
