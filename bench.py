@@ -33,6 +33,9 @@ def parse_args():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise copy-like kernel (torch.ceil, 4 GiB in, 4 GiB out) so that rocprofv3 "
                          "byte counters collected over this command can be scaled")
+    ap.add_argument("--row-align", type=int, default=32,
+                    help="alignment of the rows of G in floats (32 = 128-byte lines, the layout the library "
+                         "recommends; 1 = densely packed rows)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU oracle sample")
     return ap.parse_args()
 
@@ -102,7 +105,7 @@ def main():
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
 
-    w = WL.make_config(a.config, device=dev)
+    w = WL.make_config(a.config, device=dev, row_align=a.row_align)
     m, d, b = w.m, w.d, w.b
     g_bytes = 4 * m * d
     if a.buffers > 0:
@@ -111,7 +114,10 @@ def main():
         n_buf = 1               # far larger than the 256 MB last-level cache
     else:
         n_buf = min(8, (1 << 30) // g_bytes + 1)
-    Gs = [w.G] + [w.G.clone() for _ in range(n_buf - 1)]
+    Gs = [w.G]
+    for _ in range(n_buf - 1):
+        Gs.append(WL._alloc_rows(m, d, a.row_align, dev))
+        Gs[-1].copy_(w.G)
     mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
     ws = B.alloc_workspace(mdl, m, w.n_r, dev)
     scores = torch.empty(m, dtype=torch.float32, device=dev)
@@ -198,7 +204,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config {a.config}: " + "->".join(str(v) for v in w.dims) +
                                f" {w.loss}, d={d}, m={m}, b={b}, n_r={w.n_r}, gamma={w.gamma}, rho={w.rho}",
-                   "G_bytes": g_bytes, "G_buffers_rotated": n_buf},
+                   "G_bytes": g_bytes, "G_row_pitch_floats": int(w.G.stride(0)), "G_buffers_rotated": n_buf},
         "step_algorithmic_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "layer_kernel (candidate layers, streams G)",

@@ -25,8 +25,13 @@
  *   candidate matrix G) is, for l = 1..L: the weight matrix W_l stored
  *   row-major as [dims[l] x dims[l-1]] (out x in), followed, if has_bias, by
  *   the bias b_l[dims[l]].  d = zeno_model_num_params().
- * Candidate matrix.  G is [m x d] row-major with leading dimension d.  d need
- *   not be a multiple of 4; rows may therefore be only 4-byte aligned.
+ * Candidate matrix.  G is [m x d] row-major; consecutive rows are ldg >= d
+ *   floats apart (ldg = d: densely packed).  Neither d nor ldg need be a
+ *   multiple of 4, so rows may be only 4-byte aligned and every kernel accepts
+ *   that.  The server decides where the workers' vectors land, and the layout
+ *   the kernels are fastest on is G 128-byte aligned with ldg a multiple of 32
+ *   floats: then every 128-byte memory line of a row belongs to one load
+ *   instruction and the rows are streamed with loads that bypass cache retention.
  * Errors.  Every call returns a zeno_status_t; nothing is thrown across the
  *   ABI.  Argument errors are detected on the host before anything is
  *   enqueued, so a failed call leaves the outputs untouched.
@@ -49,7 +54,7 @@ extern "C" {
 
 typedef enum {
   ZENO_OK = 0,
-  ZENO_ERR_INVALID_ARG = 1, /* NULL/misaligned pointer, m<1, m>1024, b<0, b>=m, n_r<1, bad gamma/rho/dims */
+  ZENO_ERR_INVALID_ARG = 1, /* NULL/misaligned pointer, m<1, m>1024, b<0, b>=m, n_r<1, ldg<d, bad gamma/rho/dims */
   ZENO_ERR_UNSUPPORTED = 2, /* a size beyond what the kernels cover (see each call) */
   ZENO_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned (256 B) or smaller than the query says */
   ZENO_ERR_DEVICE = 4       /* a HIP launch failed */
@@ -108,7 +113,7 @@ size_t zeno_score_workspace_bytes(const zeno_model_t* model, int32_t m, int32_t 
  * change of the activations relative to the forward pass at x, so that the
  * difference f_r(x) - f_r(x - gamma u) is formed without cancellation.
  *   x       DEVICE [d]            current parameters
- *   G       DEVICE [m x d]        candidate gradient estimators, 1 <= m <= 1024
+ *   G, ldg  DEVICE [m x d], rows ldg >= d floats apart: candidate gradient estimators, 1 <= m <= 1024
  *   batch   HOST struct with DEVICE pointers
  *   gamma   learning rate, finite, >= 0;  rho  finite, >= 0 (rho = 0 is the
  *           appendix's choice for mu >= 0)
@@ -116,7 +121,7 @@ size_t zeno_score_workspace_bytes(const zeno_model_t* model, int32_t m, int32_t 
  *   workspace DEVICE, 256-byte aligned, >= zeno_score_workspace_bytes(model, m, n_r)
  * Batches of more than 128 samples are processed in passes of 128, each pass
  * reading G again. */
-zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float* G, int32_t m,
+zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float* G, int64_t ldg, int32_t m,
                          const zeno_batch_t* batch, float gamma, float rho, float* scores,
                          void* workspace, size_t workspace_bytes, void* stream);
 
@@ -127,15 +132,15 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
  *   scores   DEVICE [m] (as written by zeno_score)
  *   out      DEVICE [d]
  *   selected DEVICE [m-b] int32 out, ascending indices of the chosen rows; may be NULL */
-zeno_status_t zeno_aggregate(const float* G, const float* scores, int32_t m, int64_t d, int32_t b,
+zeno_status_t zeno_aggregate(const float* G, int64_t ldg, const float* scores, int32_t m, int64_t d, int32_t b,
                              float* out, int32_t* selected, void* stream);
 
 /* Mean baseline (Section 6.1.1): out[j] = (1/m) sum_i G[i][j]. */
-zeno_status_t zeno_mean(const float* G, int32_t m, int64_t d, float* out, void* stream);
+zeno_status_t zeno_mean(const float* G, int64_t ldg, int32_t m, int64_t d, float* out, void* stream);
 
 /* Marginal median (Definition 4): out[j] = median_i G[i][j]; for even m the
  * midpoint of the two middle values.  UNSUPPORTED for m > 128. */
-zeno_status_t zeno_median(const float* G, int32_t m, int64_t d, float* out, void* stream);
+zeno_status_t zeno_median(const float* G, int64_t ldg, int32_t m, int64_t d, float* out, void* stream);
 
 const char* zeno_status_string(zeno_status_t status);
 

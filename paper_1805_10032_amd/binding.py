@@ -76,14 +76,14 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.zeno_model_num_params.restype = i64
     lib.zeno_score_workspace_bytes.argtypes = [vp, i32, i32]
     lib.zeno_score_workspace_bytes.restype = ctypes.c_size_t
-    lib.zeno_score.argtypes = [vp, vp, vp, i32, ctypes.POINTER(_Batch), f32, f32, vp, vp,
+    lib.zeno_score.argtypes = [vp, vp, vp, i64, i32, ctypes.POINTER(_Batch), f32, f32, vp, vp,
                                ctypes.c_size_t, vp]
     lib.zeno_score.restype = ctypes.c_int
-    lib.zeno_aggregate.argtypes = [vp, vp, i32, i64, i32, vp, vp, vp]
+    lib.zeno_aggregate.argtypes = [vp, i64, vp, i32, i64, i32, vp, vp, vp]
     lib.zeno_aggregate.restype = ctypes.c_int
-    lib.zeno_mean.argtypes = [vp, i32, i64, vp, vp]
+    lib.zeno_mean.argtypes = [vp, i64, i32, i64, vp, vp]
     lib.zeno_mean.restype = ctypes.c_int
-    lib.zeno_median.argtypes = [vp, i32, i64, vp, vp]
+    lib.zeno_median.argtypes = [vp, i64, i32, i64, vp, vp]
     lib.zeno_median.restype = ctypes.c_int
     lib.zeno_profile_enable.argtypes = [i32]
     lib.zeno_profile_enable.restype = ctypes.c_int
@@ -107,6 +107,29 @@ def _dev(t: torch.Tensor, dtype, name: str) -> int:
     if not t.is_contiguous():
         raise ValueError(f"{name} must be contiguous")
     return t.data_ptr()
+
+
+def _rows(G: torch.Tensor):
+    """(pointer, ldg) of a candidate matrix: rows contiguous, ldg >= d floats apart
+    (a column slice of a wider allocation is accepted as it is, nothing is copied)."""
+    if not isinstance(G, torch.Tensor) or not G.is_cuda or G.dtype != torch.float32 or G.dim() != 2:
+        raise ValueError("G must be a 2-D float32 CUDA/HIP tensor")
+    m, d = G.shape
+    if d > 1 and G.stride(1) != 1:
+        raise ValueError("the rows of G must be contiguous")
+    ldg = int(G.stride(0)) if m > 1 else int(d)
+    if ldg < d:
+        raise ValueError("the rows of G overlap")
+    return G.data_ptr(), ldg
+
+
+def alloc_candidates(m: int, d: int, device=None, align: int = 32) -> torch.Tensor:
+    """An [m x d] float32 view whose rows start `align`-float (128-byte) aligned: the
+    layout the streaming kernels are fastest on."""
+    ldg = (int(d) + align - 1) // align * align
+    buf = torch.empty((int(m), ldg), dtype=torch.float32,
+                      device=device or torch.device("cuda", torch.cuda.current_device()))
+    return buf[:, :int(d)]
 
 
 class ZenoModel:
@@ -178,7 +201,8 @@ def zeno_score(model: ZenoModel, x, G, features, gamma, rho, *, labels=None, tar
         scores = torch.empty(m, dtype=torch.float32, device=G.device)
     if workspace is None:
         workspace = alloc_workspace(model, m, n_r, G.device)
-    st = lib.zeno_score(model._h, _dev(x, torch.float32, "x"), _dev(G, torch.float32, "G"), m,
+    g_ptr, ldg = _rows(G)
+    st = lib.zeno_score(model._h, _dev(x, torch.float32, "x"), g_ptr, ldg, m,
                         ctypes.byref(batch), float(gamma), float(rho),
                         _dev(scores, torch.float32, "scores"),
                         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream())
@@ -195,7 +219,8 @@ def zeno_aggregate(G, scores, b, *, out=None, selected=None, want_selected=True)
         out = torch.empty(d, dtype=torch.float32, device=G.device)
     if selected is None and want_selected and 0 <= b < m:
         selected = torch.empty(m - b, dtype=torch.int32, device=G.device)
-    st = lib.zeno_aggregate(_dev(G, torch.float32, "G"), _dev(scores, torch.float32, "scores"), m, d, int(b),
+    g_ptr, ldg = _rows(G)
+    st = lib.zeno_aggregate(g_ptr, ldg, _dev(scores, torch.float32, "scores"), m, d, int(b),
                             _dev(out, torch.float32, "out"),
                             _dev(selected, torch.int32, "selected") if selected is not None else None,
                             _stream())
@@ -209,7 +234,8 @@ def zeno_mean(G, *, out=None):
     m, d = int(G.shape[0]), int(G.shape[1])
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=G.device)
-    st = lib.zeno_mean(_dev(G, torch.float32, "G"), m, d, _dev(out, torch.float32, "out"), _stream())
+    g_ptr, ldg = _rows(G)
+    st = lib.zeno_mean(g_ptr, ldg, m, d, _dev(out, torch.float32, "out"), _stream())
     if st != 0:
         raise ZenoError(st, "zeno_mean")
     return out
@@ -220,7 +246,8 @@ def zeno_median(G, *, out=None):
     m, d = int(G.shape[0]), int(G.shape[1])
     if out is None:
         out = torch.empty(d, dtype=torch.float32, device=G.device)
-    st = lib.zeno_median(_dev(G, torch.float32, "G"), m, d, _dev(out, torch.float32, "out"), _stream())
+    g_ptr, ldg = _rows(G)
+    st = lib.zeno_median(g_ptr, ldg, m, d, _dev(out, torch.float32, "out"), _stream())
     if st != 0:
         raise ZenoError(st, "zeno_median")
     return out

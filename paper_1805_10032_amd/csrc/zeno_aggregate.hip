@@ -47,7 +47,8 @@ __device__ void select_rows(const float* __restrict__ scores, int m, int n_sel, 
 template <bool ALL>
 __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* __restrict__ G,
                                                                   const float* __restrict__ scores, int m,
-                                                                  long long d, int b, float* __restrict__ out,
+                                                                  long long d, long long ldg, int b,
+                                                                  float* __restrict__ out,
                                                                   int32_t* __restrict__ selected) {
   __shared__ float key[ZENO_MAX_CANDIDATES];
   __shared__ int flag[ZENO_MAX_CANDIDATES];
@@ -67,7 +68,7 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
 #pragma unroll
       for (int t = 0; t < kRowBatch; ++t) {
         const long long row = ALL ? (s + t) : sel_list[s + t];
-        v[t] = load_stream4(col + row * d);
+        v[t] = load_stream4(col + row * ldg);
       }
 #pragma unroll
       for (int t = 0; t < kRowBatch; ++t) {
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
     }
     for (; s < n_sel; ++s) {
       const long long row = ALL ? s : sel_list[s];
-      const f32x4 v = load_stream4(col + row * d);
+      const f32x4 v = load_stream4(col + row * ldg);
       a0 += (double)v[0];
       a1 += (double)v[1];
       a2 += (double)v[2];
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
       double a = 0.0;
       for (int s = 0; s < n_sel; ++s) {
         const long long row = ALL ? s : sel_list[s];
-        a += (double)G[row * d + j];
+        a += (double)G[row * ldg + j];
       }
       out[j] = (float)(a / n);
     }
@@ -107,17 +108,17 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
 
 }  // namespace
 
-hipError_t launch_masked_average(const float* G, const float* scores, int m, long long d, int b, float* out,
-                                 int32_t* selected, hipStream_t stream) {
+hipError_t launch_masked_average(const float* G, long long ldg, const float* scores, int m, long long d, int b,
+                                 float* out, int32_t* selected, hipStream_t stream) {
   long long n_vec = d / 4;
   long long want = (n_vec + kThreads - 1) / kThreads;
   int grid = (int)(want < 1 ? 1 : (want > 256 * 16 ? 256 * 16 : want));
   if (scores == nullptr) {
-    hipLaunchKernelGGL(masked_average_kernel<true>, dim3(grid), dim3(kThreads), 0, stream, G, scores, m, d, 0,
-                       out, selected);
+    hipLaunchKernelGGL(masked_average_kernel<true>, dim3(grid), dim3(kThreads), 0, stream, G, scores, m, d, ldg,
+                       0, out, selected);
   } else {
-    hipLaunchKernelGGL(masked_average_kernel<false>, dim3(grid), dim3(kThreads), 0, stream, G, scores, m, d, b,
-                       out, selected);
+    hipLaunchKernelGGL(masked_average_kernel<false>, dim3(grid), dim3(kThreads), 0, stream, G, scores, m, d, ldg,
+                       b, out, selected);
   }
   return hipGetLastError();
 }

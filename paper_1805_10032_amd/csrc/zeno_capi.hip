@@ -182,12 +182,12 @@ size_t zeno_score_workspace_bytes(const zeno_model_t* model, int32_t m, int32_t 
   return make_plan(model, m, n_r).total;
 }
 
-zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float* G, int32_t m,
+zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float* G, int64_t ldg, int32_t m,
                          const zeno_batch_t* batch, float gamma, float rho, float* scores, void* workspace,
                          size_t workspace_bytes, void* stream_) {
   if (model == nullptr || x == nullptr || G == nullptr || batch == nullptr || scores == nullptr)
     return ZENO_ERR_INVALID_ARG;
-  if (m < 1 || m > ZENO_MAX_CANDIDATES || batch->n_r < 1) return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || batch->n_r < 1 || ldg < model->d) return ZENO_ERR_INVALID_ARG;
   if (!std::isfinite(gamma) || gamma < 0.f || !std::isfinite(rho) || rho < 0.f) return ZENO_ERR_INVALID_ARG;
   const zeno_model_desc_t& D = model->desc;
   if (batch->features == nullptr) return ZENO_ERR_INVALID_ARG;
@@ -233,7 +233,7 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
   std::memset(&common, 0, sizeof(common));
   common.G = G;
   common.x = x;
-  common.d = model->d;
+  common.ldg = ldg;
   common.dZ = dZ;
   common.gamma = gamma;
   common.neg_inv_gamma = gamma > 0.f ? -1.0f / gamma : 0.f;
@@ -319,32 +319,32 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
   return ZENO_OK;
 }
 
-zeno_status_t zeno_aggregate(const float* G, const float* scores, int32_t m, int64_t d, int32_t b, float* out,
-                             int32_t* selected, void* stream) {
+zeno_status_t zeno_aggregate(const float* G, int64_t ldg, const float* scores, int32_t m, int64_t d, int32_t b,
+                             float* out, int32_t* selected, void* stream) {
   if (G == nullptr || scores == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
-  if (m < 1 || m > ZENO_MAX_CANDIDATES || b < 0 || b >= m || d < 1) return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || b < 0 || b >= m || d < 1 || ldg < d) return ZENO_ERR_INVALID_ARG;
   if (!aligned(G, 4) || !aligned(scores, 4) || !aligned(out, 4) || !aligned(selected, 4)) return ZENO_ERR_INVALID_ARG;
   ProfScope ps(ZENO_KERNEL_AVERAGE, 0, 4.0 * (double)d * (m - b + 1), reinterpret_cast<hipStream_t>(stream));
-  ZENO_TRY(launch_masked_average(G, scores, m, d, b, out, selected, reinterpret_cast<hipStream_t>(stream)));
+  ZENO_TRY(launch_masked_average(G, ldg, scores, m, d, b, out, selected, reinterpret_cast<hipStream_t>(stream)));
   return ZENO_OK;
 }
 
-zeno_status_t zeno_mean(const float* G, int32_t m, int64_t d, float* out, void* stream) {
+zeno_status_t zeno_mean(const float* G, int64_t ldg, int32_t m, int64_t d, float* out, void* stream) {
   if (G == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
-  if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1) return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1 || ldg < d) return ZENO_ERR_INVALID_ARG;
   if (!aligned(G, 4) || !aligned(out, 4)) return ZENO_ERR_INVALID_ARG;
   ProfScope ps(ZENO_KERNEL_MEAN, 0, 4.0 * (double)d * (m + 1), reinterpret_cast<hipStream_t>(stream));
-  ZENO_TRY(launch_masked_average(G, nullptr, m, d, 0, out, nullptr, reinterpret_cast<hipStream_t>(stream)));
+  ZENO_TRY(launch_masked_average(G, ldg, nullptr, m, d, 0, out, nullptr, reinterpret_cast<hipStream_t>(stream)));
   return ZENO_OK;
 }
 
-zeno_status_t zeno_median(const float* G, int32_t m, int64_t d, float* out, void* stream) {
+zeno_status_t zeno_median(const float* G, int64_t ldg, int32_t m, int64_t d, float* out, void* stream) {
   if (G == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
-  if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1) return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1 || ldg < d) return ZENO_ERR_INVALID_ARG;
   if (!aligned(G, 4) || !aligned(out, 4)) return ZENO_ERR_INVALID_ARG;
   if (m > 128) return ZENO_ERR_UNSUPPORTED;
   ProfScope ps(ZENO_KERNEL_MEDIAN, 0, 4.0 * (double)d * (m + 1), reinterpret_cast<hipStream_t>(stream));
-  ZENO_TRY(launch_median(G, m, d, out, reinterpret_cast<hipStream_t>(stream)));
+  ZENO_TRY(launch_median(G, ldg, m, d, out, reinterpret_cast<hipStream_t>(stream)));
   return ZENO_OK;
 }
 

@@ -54,7 +54,7 @@ struct LayerJob {
 struct LayerArgs {
   const float* G;       // [m x d]
   const float* x;       // [d]
-  long long d;          // leading dimension of G
+  long long ldg;        // floats between consecutive rows of G
   int n_cand;           // candidates in this launch (0 or m)
   int has_base;         // 1: the launch also runs the pass at x through bj
   int base_blocks;      // leading block indices reserved for the pass at x (multiple of 8)
@@ -86,9 +86,9 @@ hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, 
                        double* sample_diff, hipStream_t stream);
 hipError_t launch_score_combine(const double* sample_diff, const double* norm_partials, int P, int m,
                                 int n_r_total, float rho, float* scores, hipStream_t stream);
-hipError_t launch_masked_average(const float* G, const float* scores, int m, long long d, int b,
+hipError_t launch_masked_average(const float* G, long long ldg, const float* scores, int m, long long d, int b,
                                  float* out, int32_t* selected, hipStream_t stream);
-hipError_t launch_median(const float* G, int m, long long d, float* out, hipStream_t stream);
+hipError_t launch_median(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream);
 
 }  // namespace zeno
 #endif

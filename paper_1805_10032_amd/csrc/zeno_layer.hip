@@ -103,17 +103,20 @@ __device__ inline f32x4 load4_masked(const float* __restrict__ row, int k, int K
 // contiguous bytes each.  `tile` is the wave-uniform address of element (row0, k0);
 // `lane_off` = (lane/16)*K + 4*(lane%16) is the lane's element offset inside it.
 // FULL: the whole tile lies inside the matrix (no masking code is generated).
-template <bool FULL>
+// NT: streaming loads that do not keep the lines in the caches.  Only chosen when
+// every 256-byte row segment starts on a 128-byte line: a line that two load
+// instructions share would otherwise be fetched from memory twice.
+template <bool FULL, bool NT>
 __device__ inline void load_tile(f32x4 (&u)[8], const float* __restrict__ tile, unsigned lane_off, int row0, int k0,
                                  int N, int K, int lane) {
   if (FULL) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-#ifdef ZENO_LAYER_NT
-      u[j] = load_stream4(tile + (long long)(4 * j) * K + lane_off);
-#else
-      u[j] = *reinterpret_cast<const f32x4_a4*>(tile + (long long)(4 * j) * K + lane_off);
-#endif
+      if (NT) {
+        u[j] = load_stream4(tile + (long long)(4 * j) * K + lane_off);
+      } else {
+        u[j] = *reinterpret_cast<const f32x4_a4*>(tile + (long long)(4 * j) * K + lane_off);
+      }
     }
   } else {
     // Ragged tile.  Rows beyond the matrix read row N-1 instead (always in bounds)
@@ -162,7 +165,7 @@ __device__ inline void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <bool BF16, bool DELTA, int MB, int NW>
+template <bool BF16, bool DELTA, int MB, int NW, bool NT>
 __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   using T = Tr<BF16>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -210,7 +213,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
     s = (unit % n_cchunks) * cc + slot % cc;
     if (s >= a.n_cand) return;
   }
-  const float* __restrict__ P = is_base ? a.x : a.G + (long long)s * a.d;
+  const float* __restrict__ P = is_base ? a.x : a.G + (long long)s * a.ldg;
   const int row0 = nt * BN + wave * 32;
   const float* __restrict__ Urow0 = P + J.w_off + (long long)row0 * K;  // wave-uniform
   const unsigned lane_off = (unsigned)(lane >> 4) * (unsigned)K + ((lane & 15) << 2);
@@ -305,7 +308,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
       wait_vmcnt<0>();
       __syncthreads();
     }
-    if (c + 2 < n_chunks) load_tile<FULL>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
+    if (c + 2 < n_chunks) load_tile<FULL, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
 
     // Matrix products of this chunk in groups of MB products that share one B
     // operand (k-step t, operand H or D).  The scheduler is fenced so that the LDS
@@ -364,8 +367,8 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
     constexpr bool SECOND = DELTA && !decltype(base_c)::value;
     if (DBUF) copy_AD(0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    load_tile<FULL>(u0, Urow0, lane_off, row0, 0, N, K, lane);
-    if (n_chunks > 1) load_tile<FULL>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
+    load_tile<FULL, NT>(u0, Urow0, lane_off, row0, 0, N, K, lane);
+    if (n_chunks > 1) load_tile<FULL, NT>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
     if (SECOND) {
       load_W(w0, 0);
       if (n_chunks > 1) load_W(w1, 1);
@@ -450,7 +453,7 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
 
 int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
 
-template <bool BF16, bool DELTA, int MB, int NW>
+template <bool BF16, bool DELTA, int MB, int NW, bool NT>
 hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
   using T = Tr<BF16>;
   constexpr int BN = 32 * NW;
@@ -460,7 +463,7 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
   constexpr int lds_bytes = AD_BYTES * (DBUF ? 2 : 1) + NW * STAGE_BYTES;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -472,7 +475,7 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
     const int units = job_tiles(a.cj, BN) * ((a.n_cand + cc - 1) / cc);
     cand_blocks = ((units + 7) / 8) * 8 * cc;
   }
-  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW), lds_bytes,
+  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW, NT>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW), lds_bytes,
                      stream, a);
   return hipGetLastError();
 }
@@ -488,7 +491,7 @@ int wgs_per_cu_inst() {
     constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
     constexpr int lds_bytes = AD_BYTES * (DBUF ? 2 : 1) + NW * STAGE_BYTES;
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW>),
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, false>),
                                                      64 * NW, lds_bytes) != hipSuccess || n < 1)
       n = 1;
     cached = n;
@@ -510,11 +513,28 @@ int wgs_per_cu_mb(int MB, int NW) {
   return wgs_per_cu_nw<BF16, DELTA, 4>(NW);
 }
 
+// Streaming loads are used when every row segment a load instruction covers
+// starts on a 128-byte line: base pointers, row pitch, block offset and row
+// length of every job in the launch are multiples of 128 bytes.
+bool job_lines_aligned(const LayerJob& j) { return j.w_off % 32 == 0 && j.K % 32 == 0; }
+bool launch_lines_aligned(const LayerArgs& a) {
+  bool ok = true;
+  if (a.n_cand > 0) ok = ok && reinterpret_cast<uintptr_t>(a.G) % 128 == 0 && a.ldg % 32 == 0 && job_lines_aligned(a.cj);
+  if (a.has_base) ok = ok && reinterpret_cast<uintptr_t>(a.x) % 128 == 0 && job_lines_aligned(a.bj);
+  return ok;
+}
+
+template <bool BF16, bool DELTA, int MB, int NW>
+hipError_t launch_nt(const LayerArgs& a, hipStream_t stream) {
+  if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream);
+  return launch_inst<BF16, DELTA, MB, NW, false>(a, stream);
+}
+
 template <bool BF16, bool DELTA, int MB>
 hipError_t launch_nw(const LayerArgs& a, int NW, hipStream_t stream) {
-  if (NW == 8) return launch_inst<BF16, DELTA, MB, 8>(a, stream);
-  if (NW == 4) return launch_inst<BF16, DELTA, MB, 4>(a, stream);
-  return launch_inst<BF16, DELTA, MB, 1>(a, stream);
+  if (NW == 8) return launch_nt<BF16, DELTA, MB, 8>(a, stream);
+  if (NW == 4) return launch_nt<BF16, DELTA, MB, 4>(a, stream);
+  return launch_nt<BF16, DELTA, MB, 1>(a, stream);
 }
 
 template <bool BF16, bool DELTA>

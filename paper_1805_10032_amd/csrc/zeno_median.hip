@@ -54,7 +54,7 @@ __device__ inline void sort_regs(int (&v)[H]) {
 
 template <int P>
 __global__ __launch_bounds__(kThreads) void median_kernel(const float* __restrict__ G, int m, long long d,
-                                                          float* __restrict__ out) {
+                                                          long long ldg, float* __restrict__ out) {
   constexpr int H = P / 2;
   const long long stride = (long long)gridDim.x * kThreads;
   const int f = (P - m) / 2;  // -inf keys in front; the rest of the padding is +inf keys behind
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kThreads) void median_kernel(const float* __restric
 #pragma unroll
     for (int i = 0; i < P; ++i) {
       val[i] = *p;
-      p += (i + 1 < m) ? d : 0;
+      p += (i + 1 < m) ? ldg : 0;
       asm volatile("" : "+v"(p));
     }
 #pragma unroll
@@ -95,23 +95,23 @@ __global__ __launch_bounds__(kThreads) void median_kernel(const float* __restric
 }
 
 template <int P>
-hipError_t launch_p(const float* G, int m, long long d, float* out, hipStream_t stream) {
+hipError_t launch_p(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream) {
   long long want = (d + kThreads - 1) / kThreads;
   int grid = (int)(want < 1 ? 1 : (want > 256 * 32 ? 256 * 32 : want));
-  hipLaunchKernelGGL(median_kernel<P>, dim3(grid), dim3(kThreads), 0, stream, G, m, d, out);
+  hipLaunchKernelGGL(median_kernel<P>, dim3(grid), dim3(kThreads), 0, stream, G, m, d, ldg, out);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_median(const float* G, int m, long long d, float* out, hipStream_t stream) {
-  if (m <= 2) return launch_p<2>(G, m, d, out, stream);
-  if (m <= 4) return launch_p<4>(G, m, d, out, stream);
-  if (m <= 8) return launch_p<8>(G, m, d, out, stream);
-  if (m <= 16) return launch_p<16>(G, m, d, out, stream);
-  if (m <= 32) return launch_p<32>(G, m, d, out, stream);
-  if (m <= 64) return launch_p<64>(G, m, d, out, stream);
-  return launch_p<128>(G, m, d, out, stream);
+hipError_t launch_median(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream) {
+  if (m <= 2) return launch_p<2>(G, ldg, m, d, out, stream);
+  if (m <= 4) return launch_p<4>(G, ldg, m, d, out, stream);
+  if (m <= 8) return launch_p<8>(G, ldg, m, d, out, stream);
+  if (m <= 16) return launch_p<16>(G, ldg, m, d, out, stream);
+  if (m <= 32) return launch_p<32>(G, ldg, m, d, out, stream);
+  if (m <= 64) return launch_p<64>(G, ldg, m, d, out, stream);
+  return launch_p<128>(G, ldg, m, d, out, stream);
 }
 
 }  // namespace zeno

@@ -126,15 +126,22 @@ def _draw_batch(dims, loss, n, gen, device, feat="normal"):
     return features, labels, targets
 
 
+def _alloc_rows(m, d, row_align, device):
+    """[m x d] float32 whose rows are row_align floats aligned (a view of a wider buffer)."""
+    ldg = (d + row_align - 1) // row_align * row_align
+    return torch.empty((m, ldg), dtype=torch.float32, device=device)[:, :d]
+
+
 def make_mlp_workload(name, cfg, dims, m, b, n_r, gamma, rho, fwd, *, seed=0, device="cpu",
                       has_bias=True, loss="softmax_ce", n_flip=0, flip_scale=-4.0,
                       n_noise=0, noise_std=100.0, feat="normal", init="he",
-                      worker_batch=None, faulty_first=False):
+                      worker_batch=None, faulty_first=False, row_align=1):
     """m candidates for an MLP/softmax model: honest rows are exact minibatch
     gradients at x on each worker's own i.i.d. batch; n_flip rows are identical
     copies of flip_scale x (mean of the honest rows); n_noise rows are
     independent N(0, noise_std^2) per coordinate.  Faulty rows sit at a seeded
-    random subset of the m positions."""
+    random subset of the m positions.  Rows of G are row_align-float aligned
+    (1 = densely packed; the values do not depend on it)."""
     device = torch.device(device)
     x = init_params(dims, has_bias, _gen(seed, cfg, 1, device), device, init)
     features, labels, targets = _draw_batch(dims, loss, n_r, _gen(seed, cfg, 2, device), device, feat)
@@ -146,7 +153,7 @@ def make_mlp_workload(name, cfg, dims, m, b, n_r, gamma, rho, fwd, *, seed=0, de
         perm = list(range(m))
     flip_rows, noise_rows = sorted(perm[:n_flip]), sorted(perm[n_flip:q])
     faulty = sorted(perm[:q])
-    G = torch.empty((m, d), dtype=torch.float32, device=device)
+    G = _alloc_rows(m, d, row_align, device)
     honest_sum = torch.zeros(d, dtype=torch.float64, device=device)
     wb = worker_batch or n_r
     n_honest = 0
@@ -168,7 +175,7 @@ def make_mlp_workload(name, cfg, dims, m, b, n_r, gamma, rho, fwd, *, seed=0, de
 
 
 def make_least_squares(name="cfg1", cfg=1, d=64, n_r=16, m=8, b=2, q=2, gamma=0.1, rho=5e-4,
-                       *, seed=0, device="cpu", noise=0.1, flip_scale=-4.0):
+                       *, seed=0, device="cpu", noise=0.1, flip_scale=-4.0, row_align=1):
     """Linear model, squared loss, no bias: A ~ N(0,1), y = A w* + N(0, 0.01^2),
     x ~ N(0,1); honest rows = gradient of f_r itself plus N(0, noise^2); faulty
     rows = flip_scale x that gradient."""
@@ -181,7 +188,7 @@ def make_least_squares(name="cfg1", cfg=1, d=64, n_r=16, m=8, b=2, q=2, gamma=0.
     grad = (A.double().T @ (A.double() @ x.double() - y.double()) / n_r).float()
     perm = torch.randperm(m, generator=_gen(seed, cfg, 3, "cpu")).tolist()
     faulty = sorted(perm[:q])
-    G = torch.empty((m, d), dtype=torch.float32, device=device)
+    G = _alloc_rows(m, d, row_align, device)
     for i in range(m):
         if i in faulty:
             G[i] = flip_scale * grad
@@ -191,24 +198,25 @@ def make_least_squares(name="cfg1", cfg=1, d=64, n_r=16, m=8, b=2, q=2, gamma=0.
                     x, G, A, None, y, faulty)
 
 
-def make_config(cfg: int, *, seed=0, device="cpu") -> Workload:
+def make_config(cfg: int, *, seed=0, device="cpu", row_align=1) -> Workload:
     """The five numbered workloads (1 = smallest ... 5 = 14 GB of candidates)."""
     if cfg == 1:
-        return make_least_squares(seed=seed, device=device)
+        return make_least_squares(seed=seed, device=device, row_align=row_align)
     if cfg == 2:
         return make_mlp_workload("cfg2", 2, [784, 10], 20, 8, 32, 0.1, 5e-4, "fp32",
                                  seed=seed, device=device, n_noise=8, noise_std=200.0,
-                                 feat="uniform", init="small", worker_batch=32)
+                                 feat="uniform", init="small", worker_batch=32, row_align=row_align)
     if cfg == 3:
         return make_mlp_workload("cfg3", 3, [3072, 512, 10], 20, 8, 32, 0.05, 1e-3, "fp32",
-                                 seed=seed, device=device, n_flip=8, flip_scale=-4.0)
+                                 seed=seed, device=device, n_flip=8, flip_scale=-4.0, row_align=row_align)
     if cfg == 4:
         return make_mlp_workload("cfg4", 4, [3072, 2048, 2048, 2048, 10], 100, 40, 64, 0.05, 1e-3,
                                  "bf16", seed=seed, device=device, n_flip=20, flip_scale=-4.0,
-                                 n_noise=20, noise_std=100.0)
+                                 n_noise=20, noise_std=100.0, row_align=row_align)
     if cfg == 5:
         return make_mlp_workload("cfg5", 5, [4096, 4096, 4096, 4096, 1000], 64, 16, 128, 0.02, 1e-4,
-                                 "bf16", seed=seed, device=device, n_flip=16, flip_scale=-10.0)
+                                 "bf16", seed=seed, device=device, n_flip=16, flip_scale=-10.0,
+                                 row_align=row_align)
     raise ValueError(f"no such config: {cfg}")
 
 

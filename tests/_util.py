@@ -48,12 +48,22 @@ def exact_terms(w, rows=None):
     return s, scale
 
 
-def gpu_scores(B, w, device="cuda"):
+def rows_to_gpu(B, G, row_align=1, device="cuda"):
+    """Copy of the candidate matrix on the GPU whose rows are row_align floats aligned
+    (1: densely packed, whatever alignment that gives)."""
+    if row_align <= 1:
+        return G.contiguous().to(device)
+    out = B.alloc_candidates(G.shape[0], G.shape[1], torch.device(device), row_align)
+    out.copy_(G)
+    return out
+
+
+def gpu_scores(B, w, device="cuda", row_align=1):
     mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
     dev = torch.device(device)
     lab = None if w.labels is None else w.labels.to(dev)
     tgt = None if w.targets is None else w.targets.to(dev)
-    s = B.zeno_score(mdl, w.x.to(dev), w.G.to(dev), w.features.to(dev), w.gamma, w.rho,
+    s = B.zeno_score(mdl, w.x.to(dev), rows_to_gpu(B, w.G, row_align, dev), w.features.to(dev), w.gamma, w.rho,
                      labels=lab, targets=tgt)
     torch.cuda.synchronize()
     return s

@@ -59,10 +59,10 @@ def test_workspace_query(B):
 
 def test_null_pointers_are_rejected_on_the_host(B):
     lib = B.load_library()
-    assert lib.zeno_aggregate(None, None, 4, 8, 1, None, None, None) == 1
-    assert lib.zeno_mean(None, 4, 8, None, None) == 1
-    assert lib.zeno_median(None, 4, 8, None, None) == 1
-    assert lib.zeno_score(None, None, None, 4, None, 0.1, 0.1, None, None, 0, None) == 1
+    assert lib.zeno_aggregate(None, 8, None, 4, 8, 1, None, None, None) == 1
+    assert lib.zeno_mean(None, 8, 4, 8, None, None) == 1
+    assert lib.zeno_median(None, 8, 4, 8, None, None) == 1
+    assert lib.zeno_score(None, None, None, 8, 4, None, 0.1, 0.1, None, None, 0, None) == 1
     assert lib.zeno_status_string(0) == b"ok"
     assert lib.zeno_profile_collect(None, 0) == 0
 
