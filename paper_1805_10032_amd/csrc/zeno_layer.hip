@@ -16,8 +16,10 @@
 // obtained without subtracting two nearly equal losses.  ||u_s||^2 is
 // accumulated from the same registers that feed the matrix cores.
 //
-// Matrix-core mapping (wave64): each wave owns 32 output features (columns of the
-// 32x32 accumulator blocks) and all MB*32 sample rows.
+// Matrix-core mapping (wave64): each wave owns 32 output features (the rows of its
+// 32x32 accumulator blocks, i.e. the weight tile is the FIRST operand) and all
+// MB*32 sample rows (the columns = lanes), so that the results leave the
+// accumulators already in the order the next layer's operand is stored in.
 //  * U tile (32 features x 64 k, fp32 in HBM): fully coalesced 128-bit loads (4
 //    rows x 256 B per instruction, scalar base + per-lane offset), two chunks in
 //    flight per wave; converted and passed through a wave-private, XOR-swizzled
@@ -35,7 +37,6 @@ namespace zeno {
 
 namespace {
 
-typedef __attribute__((address_space(1))) const void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 constexpr int kSrcChunk = 16;  // sources per scheduling unit (one feature tile each)
@@ -77,6 +78,20 @@ __device__ inline void store_tiled(void* base, int r, int k, int Kp, float v) {
   }
 }
 
+// Four consecutive columns k0..k0+3 (k0 a multiple of 4) of row r of a tiled
+// operand: they are adjacent in memory (8 bytes as bf16, 16 bytes as fp32).
+template <bool BF16>
+__device__ inline void store_tiled4(void* base, int r, int k0, int Kp, const f32x4& v) {
+  const long long idx = tiled_index<BF16>(r, k0, Kp);
+  if (BF16) {
+    bf16x4 t;
+    t[0] = (__bf16)v[0]; t[1] = (__bf16)v[1]; t[2] = (__bf16)v[2]; t[3] = (__bf16)v[3];
+    *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(base) + idx) = t;
+  } else {
+    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(base) + idx) = v;
+  }
+}
+
 // Output features a launch must cover: a hidden layer also writes the zero
 // padding of the next layer's tiled operand (width rounded up to 64).
 __host__ __device__ inline int cover_rows(int N, int last) { return last ? N : (N + 63) / 64 * 64; }
@@ -97,6 +112,19 @@ __device__ inline f32x4 load4_masked(const float* __restrict__ row, int k, int K
     }
   }
   return v;
+}
+
+// Store v[0..3] to row[k..k+3], dropping the elements at or beyond K (4-byte aligned row).
+__device__ inline void store4_masked(float* __restrict__ row, int k, int K, const f32x4& v) {
+  if (k + 4 <= K) {
+    f4u t;
+    t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
+    *reinterpret_cast<f4u*>(row + k) = t;
+  } else {
+    if (k < K) row[k] = v[0];
+    if (k + 1 < K) row[k + 1] = v[1];
+    if (k + 2 < K) row[k + 2] = v[2];
+  }
 }
 
 // Load the wave's 32 x 64 weight tile: instruction j covers rows 4j..4j+3, 256
@@ -165,24 +193,60 @@ __device__ inline void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// Asynchronous 16-byte-per-lane copy from global memory straight into LDS: lane i's
+// 16 bytes at `src` (a per-lane address) land at dst + 16 i, dst wave-uniform.  The
+// instruction is issued through inline assembly on purpose.  The compiler's own
+// wait-count bookkeeping treats such a copy as a possible writer of every LDS
+// address and then drains ALL outstanding loads (vmcnt(0)) before the next LDS
+// read, which would also drain the weight tiles that are meant to stay in flight
+// across chunks.  Issued this way the copy is invisible to that bookkeeping; the
+// kernel waits for it explicitly (wait_vmcnt, loads complete in order) before the
+// workgroup barrier that publishes the buffer.  Hidden loads only make the
+// compiler's own counts for its ordinary loads stricter than needed, never laxer.
+// m0 (the LDS base of the copy) is written inside the statement and is not on the
+// clobber list: the compiler reserves it and uses it for nothing else in this file.
+__device__ inline void lds_dma16(const unsigned char* src, unsigned char* dst) {
+  const unsigned lds_off = (unsigned)(uintptr_t)(lptr_t)dst;  // byte offset inside the workgroup's LDS
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(src), "s"(lds_off)
+               : "memory");
+}
+
+// LDS layout of a workgroup: [activation chunk buffers (one or two)] [one staging
+// tile per wave] [32 bias values per wave].
+template <bool BF16, bool DELTA, int MB, int NW>
+struct Lds {
+  using T = Tr<BF16>;
+  static constexpr int A_BYTES = MB * T::CH_BYTES;            // one operand, one chunk
+  static constexpr int AD_BYTES = A_BYTES * (DELTA ? 2 : 1);  // H (and D), one chunk
+  static constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
+  static constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
+  static constexpr int STAGE_OFF = AD_BYTES * (DBUF ? 2 : 1);
+  static constexpr int BIAS_OFF = STAGE_OFF + NW * STAGE_BYTES;
+  static constexpr int TOTAL = BIAS_OFF + NW * 32 * 4;
+};
+
 template <bool BF16, bool DELTA, int MB, int NW, bool NT>
 __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   using T = Tr<BF16>;
+  using LD = Lds<BF16, DELTA, MB, NW>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   constexpr int BN = 32 * NW;
-  constexpr int A_BYTES = MB * T::CH_BYTES;            // one operand, one chunk
-  constexpr int AD_BYTES = A_BYTES * (DELTA ? 2 : 1);  // H (and D), one chunk
+  constexpr int A_BYTES = LD::A_BYTES;
+  constexpr int AD_BYTES = LD::AD_BYTES;
   constexpr int AD_KB = AD_BYTES / 1024;               // 1 KB async copies per chunk
   constexpr int A_KB = A_BYTES / 1024;
   constexpr int BLOCK_KB = T::CH_BYTES / 1024;
-  constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
-  constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
+  constexpr int STAGE_BYTES = LD::STAGE_BYTES;
+  constexpr bool DBUF = LD::DBUF;
   constexpr int COPIES = (AD_KB + NW - 1) / NW;        // async copies issued per wave per chunk
   constexpr int WREGS = BF16 ? 4 : 8;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  unsigned char* stU = lds + AD_BYTES * (DBUF ? 2 : 1) + wave * STAGE_BYTES;
+  unsigned char* stU = lds + LD::STAGE_OFF + wave * STAGE_BYTES;
+  float* biasL = reinterpret_cast<float*>(lds + LD::BIAS_OFF) + wave * 32;
 
   // Which job: the leading base_blocks block indices run the pass at x (one
   // feature tile each), the rest the candidates.
@@ -242,18 +306,19 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[mb][j] = 0.f;
 
-  const bool do_norm = (a.norm_partials != nullptr) && !is_base;
-  double nrm = 0.0;
-
-  f32x4 u0[8], u1[8];
-  f32x4 w0[WREGS], w1[WREGS];
 #ifdef ZENO_TIMING_EXPERIMENTS
   // Timing experiments only (results are wrong): bit 0 skips the matrix products
-  // and their LDS reads, bit 1 the activation copies, bit 2 the staging writes.
+  // and their LDS reads, bit 1 the activation copies, bit 2 the staging writes,
+  // bit 3 the epilogue, bit 4 the norm.
   const int dbg = a.dbg;
 #else
   constexpr int dbg = 0;
 #endif
+  const bool do_norm = (a.norm_partials != nullptr) && !is_base && !(dbg & 16);
+  double nrm = 0.0;
+
+  f32x4 u0[8], u1[8];
+  f32x4 w0[WREGS], w1[WREGS];
 
   // Asynchronous copy of chunk c of the tiled activation operands into LDS buffer
   // `buf`: AD_KB pieces of 1 KB (64 lanes x 16 B land at consecutive LDS addresses),
@@ -267,7 +332,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
         const int mb = piece / BLOCK_KB, within = piece % BLOCK_KB;
         const unsigned char* src = (op ? Dg : Ag) + ((long long)mb * n_chunks + c) * T::CH_BYTES + within * 1024 + lane * 16;
         unsigned char* dst = lds + buf * AD_BYTES + q * 1024;
-        __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)dst, 16, 0, 0);
+        lds_dma16(src, dst);
       }
     }
   };
@@ -280,9 +345,16 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   // One K chunk.  Its weight tile sits in registers u (loaded two chunks ago); its
   // activation operands were copied into LDS buffer c&1 during the previous chunk.
   // Issue order per chunk: copies(c+1), U(c+2), [matrix products of c], W(c+2).
-  auto chunk = [&](auto full_c, auto base_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
+  // STEADY: the caller guarantees c + 2 < n_chunks, so every load of the chunk is
+  // unconditional.  That matters for more than the saved branches: the compiler
+  // derives its wait counts from the worst path through the loop, and a path on
+  // which the later tile was NOT requested makes it wait for all loads at the top
+  // of every chunk, i.e. no tile would stay in flight across a chunk.
+  auto chunk = [&](auto full_c, auto base_c, auto steady_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c)
+                   __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_c)::value;
     constexpr bool BASE = decltype(base_c)::value;   // this workgroup runs the pass at x
+    constexpr bool STEADY = decltype(steady_c)::value;
     constexpr bool SECOND = DELTA && !BASE;           // second product D W^T present
     const int buf = DBUF ? (c & 1) : 0;
     if (do_norm) {
@@ -293,14 +365,15 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
     }
     if (!(dbg & 4)) stage_tile<BF16>(u, stU, lane);
     if (DBUF) {
-      // copies(c) were issued before U(c+1) [8 loads] and W(c+1) [WREGS loads]
-      if (FULL && !BASE) {
+      // copies(c) were issued before U(c+1) [8 loads] and W(c+1) [WREGS loads]; the
+      // last chunk has no such loads behind its copies and waits for everything
+      if (FULL && !BASE && (STEADY || c + 1 < n_chunks)) {
         wait_vmcnt<8 + (SECOND ? WREGS : 0)>();
       } else {
         wait_vmcnt<0>();
       }
       __syncthreads();  // copies of every wave have landed; everyone is done with buffer buf^1
-      if (c + 1 < n_chunks && !(dbg & 2)) copy_AD(c + 1, buf ^ 1);
+      if ((STEADY || c + 1 < n_chunks) && !(dbg & 2)) copy_AD(c + 1, buf ^ 1);
       __builtin_amdgcn_sched_barrier(0);  // the wait above counts on the copies being issued before the next loads
     } else {
       __syncthreads();  // single buffer: everyone is done with the previous chunk
@@ -308,7 +381,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
       wait_vmcnt<0>();
       __syncthreads();
     }
-    if (c + 2 < n_chunks) load_tile<FULL, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
+    if (STEADY || c + 2 < n_chunks) load_tile<FULL, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
 
     // Matrix products of this chunk in groups of MB products that share one B
     // operand (k-step t, operand H or D).  The scheduler is fenced so that the LDS
@@ -343,11 +416,11 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
       for (int mb = 0; mb < MB; ++mb) {
         if (op == 1 && !SECOND) break;  // the pass at x has no second product
         if (BF16) {
-          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr[g][mb]),
-                                                            __builtin_bit_cast(bf16x8, bv), acc[mb], 0, 0, 0);
+          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bv),
+                                                            __builtin_bit_cast(bf16x8, fr[g][mb]), acc[mb], 0, 0, 0);
         } else {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(fr[g][mb][e], bv[e], acc[mb], 0, 0, 0);
+          for (int e = 0; e < 4; ++e) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[e], fr[g][mb][e], acc[mb], 0, 0, 0);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -359,23 +432,46 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
       }
       if (BASE && pack && op == 0) *reinterpret_cast<f32x4*>(Wt_wave + ((long long)c * WREGS + t) * 1024) = bq[t];
     }
-    if (SECOND && c + 2 < n_chunks) load_W(w, c + 2);
+    if (SECOND && (STEADY || c + 2 < n_chunks)) load_W(w, c + 2);
   };
 
   auto run = [&](auto full_c, auto base_c) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_c)::value;
     constexpr bool SECOND = DELTA && !decltype(base_c)::value;
+    // The wave's 32 bias values are requested first of all and parked in LDS, so
+    // that the epilogue does not start with a round trip to memory.
+    float bias_lane = 0.f;
+    if (J.b_off >= 0 && lane < 32 && row0 + lane < N) bias_lane = P[J.b_off + row0 + lane];
+    __builtin_amdgcn_sched_barrier(0);
     if (DBUF) copy_AD(0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    load_tile<FULL, NT>(u0, Urow0, lane_off, row0, 0, N, K, lane);
-    if (n_chunks > 1) load_tile<FULL, NT>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
-    if (SECOND) {
-      load_W(w0, 0);
-      if (n_chunks > 1) load_W(w1, 1);
+    int c = 0;
+    if (FULL && DBUF && n_chunks >= 4) {
+      // steady state: pairs of chunks whose loads (two chunks ahead) all exist
+      load_tile<FULL, NT>(u0, Urow0, lane_off, row0, 0, N, K, lane);
+      load_tile<FULL, NT>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
+      if (SECOND) {
+        load_W(w0, 0);
+        load_W(w1, 1);
+      }
+      if (lane < 32) biasL[lane] = bias_lane;
+      for (; c + 3 < n_chunks; c += 2) {
+        chunk(full_c, base_c, std::true_type{}, u0, w0, c);
+        chunk(full_c, base_c, std::true_type{}, u1, w1, c + 1);
+      }
+    } else {
+      load_tile<FULL, NT>(u0, Urow0, lane_off, row0, 0, N, K, lane);
+      if (n_chunks > 1) load_tile<FULL, NT>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
+      if (SECOND) {
+        load_W(w0, 0);
+        if (n_chunks > 1) load_W(w1, 1);
+      }
+      if (lane < 32) biasL[lane] = bias_lane;
     }
-    for (int c = 0; c < n_chunks; c += 2) {
-      chunk(full_c, base_c, u0, w0, c);
-      if (c + 1 < n_chunks) chunk(full_c, base_c, u1, w1, c + 1);
+    // the last two or three chunks (all of them for a short K): every load is conditional
+    for (; c < n_chunks; c += 2) {
+      chunk(full_c, base_c, std::false_type{}, u0, w0, c);
+      if (c + 1 < n_chunks) chunk(full_c, base_c, std::false_type{}, u1, w1, c + 1);
     }
   };
   if (is_base) {
@@ -384,41 +480,124 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
     if (all_full) run(std::true_type{}, std::false_type{}); else run(std::false_type{}, std::false_type{});
   }
 
-  // ---- epilogue.  Accumulator element j of block mb in lane (n, h) is sample row
-  // 32 mb + 8 (j/4) + 4 h + j%4 and output feature row0 + n.
+  // ---- epilogue.  The weight tile is the first operand of the products, so the
+  // accumulators hold features along the registers and samples along the lanes:
+  // element j of block mb in lane (n, h) is sample row 32 mb + n and output feature
+  // row0 + 8 (j/4) + 4 h + j%4.  Four consecutive features of one sample are
+  // adjacent in the tiled operand of the next layer, so a lane stores them as one
+  // piece and a wave's store instruction covers one contiguous 512 B / 1 KB run.
+  if (dbg & 8) {
+    if (acc[0][0] == 12345.f) a.dZ[0] = 1.f;
+    return;
+  }
   const int n = lane & 31, h = lane >> 5;
-  const int feat = row0 + n;
-  const bool feat_ok = feat < N;
-  float bias = 0.f;
-  if (J.b_off >= 0 && feat_ok) bias = P[J.b_off + feat];
-  if (do_norm && h == 0) nrm += (double)(bias * bias);
+  f32x4 bias[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    bias[q] = *reinterpret_cast<const f32x4*>(biasL + 8 * q + 4 * h);   // written by this wave before the main loop
+    // every feature of the tile sits in exactly one of the two lanes with n == 0
+    if (do_norm && n == 0)
+      nrm += (double)((bias[q][0] * bias[q][0] + bias[q][1] * bias[q][1]) + (bias[q][2] * bias[q][2] + bias[q][3] * bias[q][3]));
+  }
 
+  if (full_rows) {
+    // All 32 features of the wave exist: no per-element guards.  Rows beyond the
+    // batch read row n_r-1 instead (in bounds) and are masked afterwards, so every
+    // load is unconditional and all of them are in flight together.
+    const bool hidden_cand = !is_base && !last;
+    f32x4 z0v[MB][4];
+    if (hidden_cand) {
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
+      for (int mb = 0; mb < MB; ++mb) {
+        const int r = 32 * mb + n;
+        const int rc = r < a.n_r ? r : a.n_r - 1;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int r = 32 * mb + 8 * (j >> 2) + 4 * h + (j & 3);
-      const bool ok = feat_ok && r < a.n_r;
-      const float val = acc[mb][j] + bias;
-      if (is_base) {
-        if (ok) J.Z0[(long long)r * N + feat] = val;
-        if (!last && feat < Np) store_tiled<BF16>(J.H_base, r, feat, Np, ok ? relu_nan(val) : 0.f);
-      } else {
-        const float dz = -a.gamma * val;
-        if (last) {
-          if (ok) a.dZ[((long long)s * a.n_r + r) * N + feat] = dz;
-        } else if (feat < Np) {
-          float hv = 0.f, dv = 0.f;
-          if (ok) {
-            const float z0 = J.Z0[(long long)r * N + feat];
-            const float zs = z0 + dz;
-            hv = relu_nan(zs);
-            // relu(z0 + dz) - relu(z0) without cancellation
-            dv = (z0 > 0.f) ? ((dz < -z0) ? -z0 : dz) : hv;
-            dv *= a.neg_inv_gamma;
+        for (int q = 0; q < 4; ++q)
+          z0v[mb][q] = *reinterpret_cast<const f32x4_a4*>(J.Z0 + (long long)rc * N + row0 + 8 * q + 4 * h);
+      }
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int r = 32 * mb + n;
+      const bool row_ok = r < a.n_r;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int f0 = row0 + 8 * q + 4 * h;
+        f32x4 val;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) val[i] = acc[mb][4 * q + i] + bias[q][i];
+        if (is_base) {
+          if (row_ok) *reinterpret_cast<f32x4_a4*>(J.Z0 + (long long)r * N + f0) = val;
+          if (!last) {
+            f32x4 hv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hv[i] = row_ok ? relu_nan(val[i]) : 0.f;
+            store_tiled4<BF16>(J.H_base, r, f0, Np, hv);
           }
-          store_tiled<BF16>(reinterpret_cast<unsigned char*>(a.H_cand) + (long long)s * a.H_stride, r, feat, Np, hv);
-          store_tiled<BF16>(reinterpret_cast<unsigned char*>(a.Dl_cand) + (long long)s * a.H_stride, r, feat, Np, dv);
+        } else {
+          f32x4 dz;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dz[i] = -a.gamma * val[i];
+          if (last) {
+            if (row_ok) *reinterpret_cast<f32x4_a4*>(a.dZ + ((long long)s * a.n_r + r) * N + f0) = dz;
+          } else {
+            f32x4 hv, dv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float z0 = z0v[mb][q][i];
+              const float hr = relu_nan(z0 + dz[i]);
+              // relu(z0 + dz) - relu(z0) without cancellation
+              const float dd = (z0 > 0.f) ? ((dz[i] < -z0) ? -z0 : dz[i]) : hr;
+              hv[i] = row_ok ? hr : 0.f;
+              dv[i] = row_ok ? dd * a.neg_inv_gamma : 0.f;
+            }
+            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.H_cand) + (long long)s * a.H_stride, r, f0, Np, hv);
+            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.Dl_cand) + (long long)s * a.H_stride, r, f0, Np, dv);
+          }
+        }
+      }
+    }
+  } else {
+    // ragged tile: per-element guards
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int r = 32 * mb + n;
+      const bool row_ok = r < a.n_r;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int f0 = row0 + 8 * q + 4 * h;
+        f32x4 val;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) val[i] = acc[mb][4 * q + i] + bias[q][i];
+        if (is_base) {
+          if (row_ok) store4_masked(J.Z0 + (long long)r * N, f0, N, val);
+          if (!last && f0 < Np) {
+            f32x4 hv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hv[i] = (row_ok && f0 + i < N) ? relu_nan(val[i]) : 0.f;
+            store_tiled4<BF16>(J.H_base, r, f0, Np, hv);
+          }
+        } else {
+          f32x4 dz;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dz[i] = -a.gamma * val[i];
+          if (last) {
+            if (row_ok) store4_masked(a.dZ + ((long long)s * a.n_r + r) * N, f0, N, dz);
+          } else if (f0 < Np) {
+            const f32x4 z0 = load4_masked(J.Z0 + (long long)r * N, f0, N, row_ok);
+            f32x4 hv, dv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const bool ok = row_ok && f0 + i < N;
+              const float hr = relu_nan(z0[i] + dz[i]);
+              // relu(z0 + dz) - relu(z0) without cancellation
+              const float dd = (z0[i] > 0.f) ? ((dz[i] < -z0[i]) ? -z0[i] : dz[i]) : hr;
+              hv[i] = ok ? hr : 0.f;
+              dv[i] = ok ? dd * a.neg_inv_gamma : 0.f;
+            }
+            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.H_cand) + (long long)s * a.H_stride, r, f0, Np, hv);
+            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.Dl_cand) + (long long)s * a.H_stride, r, f0, Np, dv);
+          }
         }
       }
     }
@@ -455,12 +634,8 @@ int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN 
 
 template <bool BF16, bool DELTA, int MB, int NW, bool NT>
 hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
-  using T = Tr<BF16>;
   constexpr int BN = 32 * NW;
-  constexpr int AD_BYTES = MB * T::CH_BYTES * (DELTA ? 2 : 1);
-  constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
-  constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
-  constexpr int lds_bytes = AD_BYTES * (DBUF ? 2 : 1) + NW * STAGE_BYTES;
+  constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT>),
@@ -485,11 +660,7 @@ template <bool BF16, bool DELTA, int MB, int NW>
 int wgs_per_cu_inst() {
   static int cached = 0;
   if (cached == 0) {
-    using T = Tr<BF16>;
-    constexpr int AD_BYTES = MB * T::CH_BYTES * (DELTA ? 2 : 1);
-    constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
-    constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
-    constexpr int lds_bytes = AD_BYTES * (DBUF ? 2 : 1) + NW * STAGE_BYTES;
+    constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL;
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, false>),
                                                      64 * NW, lds_bytes) != hipSuccess || n < 1)
