@@ -8,7 +8,6 @@ namespace zeno {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowBatch = 8;  // rows whose loads are in flight together per thread
 
 // Every workgroup redoes the selection from the m scores (m <= 1024, a few
 // thousand compares) instead of waiting for a separate launch: rank_i = number
@@ -44,54 +43,121 @@ __device__ void select_rows(const float* __restrict__ scores, int m, int n_sel, 
   __syncthreads();
 }
 
+// Results leave the workgroup in large contiguous bursts: a workgroup averages
+// n_blocks consecutive column blocks of kBlockVec float4 columns each, parks the
+// results in LDS and then writes the whole run (up to 144 KB) at once.  Measured
+// on MI355X, output stores that trickle out between the row loads cost about a
+// fifth of the read bandwidth although they are 1/(n_sel+1) of the bytes; written
+// in bursts (and marked write-through, so they do not linger as dirty lines) they
+// cost a few percent.
+constexpr int kVec = 4;                      // float4 columns per thread and block
+constexpr int kBlockVec = kThreads * kVec;   // float4 columns per block (16 KB of output)
+// rows whose loads are in flight together (x kVec loads each); the variant that
+// looks its rows up in the selected list keeps more in flight to cover the lookup
+constexpr int kRowsAll = 2, kRowsSel = 4;
+constexpr int kMaxBlocks = 9;                // blocks per burst: 9 x 16 KB of LDS
+
+__device__ inline void store_burst(float* p, const f32x4& v) {
+  // 16-byte store, write-through to memory (system-coherent scope bit): the line is
+  // not kept dirty in the L2, which the streaming row loads would have to displace
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+
 template <bool ALL>
 __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* __restrict__ G,
                                                                   const float* __restrict__ scores, int m,
-                                                                  long long d, long long ldg, int b,
+                                                                  long long d, long long ldg, int b, int n_blocks,
                                                                   float* __restrict__ out,
                                                                   int32_t* __restrict__ selected) {
-  __shared__ float key[ZENO_MAX_CANDIDATES];
-  __shared__ int flag[ZENO_MAX_CANDIDATES];
-  __shared__ int sel_list[ZENO_MAX_CANDIDATES];
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  // [selected row list][burst buffer]; the selection's scratch (keys, flags) lies
+  // in the burst buffer, which is not used before the selection is over
+  int* sel_list = reinterpret_cast<int*>(lds_raw);
+  f32x4* burst = reinterpret_cast<f32x4*>(lds_raw + ZENO_MAX_CANDIDATES * sizeof(int));
   const int n_sel = ALL ? m : m - b;
-  if (!ALL) select_rows(scores, m, n_sel, key, flag, sel_list, blockIdx.x == 0 ? selected : nullptr);
+  if (!ALL) {
+    float* key = reinterpret_cast<float*>(burst);
+    int* flag = reinterpret_cast<int*>(key + ZENO_MAX_CANDIDATES);
+    select_rows(scores, m, n_sel, key, flag, sel_list, blockIdx.x == 0 ? selected : nullptr);
+  }
 
   const double n = (double)n_sel;
   const long long n_vec = d / 4;
-  const long long stride = (long long)gridDim.x * kThreads;
-  for (long long c = (long long)blockIdx.x * kThreads + threadIdx.x; c < n_vec; c += stride) {
-    const float* col = G + c * 4;
-    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-    int s = 0;
-    for (; s + kRowBatch <= n_sel; s += kRowBatch) {
-      f32x4 v[kRowBatch];
+  // balanced contiguous share of the column blocks, worked through in bursts of n_blocks
+  const long long blocks_total = (n_vec + kBlockVec - 1) / kBlockVec;
+  const long long blk_begin = blocks_total * blockIdx.x / gridDim.x;
+  const long long blk_end = blocks_total * (blockIdx.x + 1) / gridDim.x;
+  for (long long g = blk_begin; g < blk_end; g += n_blocks) {
+    const int nb = (int)(blk_end - g < n_blocks ? blk_end - g : n_blocks);
+    for (int i = 0; i < nb; ++i) {
+      const long long c0 = (g + i) * kBlockVec + threadIdx.x;
+      double acc[kVec][4];
 #pragma unroll
-      for (int t = 0; t < kRowBatch; ++t) {
-        const long long row = ALL ? (s + t) : sel_list[s + t];
-        v[t] = load_stream4(col + row * ldg);
+      for (int v = 0; v < kVec; ++v)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[v][e] = 0.0;
+      // columns beyond the end re-read the last full column (in bounds) and are not written
+      long long col[kVec];
+#pragma unroll
+      for (int v = 0; v < kVec; ++v) {
+        const long long c = c0 + v * kThreads;
+        col[v] = (c < n_vec ? c : n_vec - 1) * 4;
+      }
+      constexpr int RB = ALL ? kRowsAll : kRowsSel;
+      int s = 0;
+      // the list entries of the NEXT batch are fetched while this batch's loads are
+      // in flight (entries past the end repeat the last one and are never used)
+      int rows[RB];
+#pragma unroll
+      for (int t = 0; t < RB; ++t) rows[t] = ALL ? t : sel_list[t < n_sel ? t : n_sel - 1];
+      for (; s + RB <= n_sel; s += RB) {
+        f32x4 x[RB][kVec];
+#pragma unroll
+        for (int t = 0; t < RB; ++t) {
+          const float* rp = G + (long long)rows[t] * ldg;
+#pragma unroll
+          for (int v = 0; v < kVec; ++v) x[t][v] = load_stream4(rp + col[v]);
+        }
+        // keep the whole batch of loads in flight: without the fences the scheduler
+        // interleaves loads and additions to save registers and waits after every few loads
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < RB; ++t) {
+          const int nx = s + RB + t;
+          rows[t] = ALL ? nx : sel_list[nx < n_sel ? nx : n_sel - 1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < RB; ++t)
+#pragma unroll
+          for (int v = 0; v < kVec; ++v)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[v][e] += (double)x[t][v][e];
+      }
+      for (; s < n_sel; ++s) {
+        const long long row = ALL ? s : sel_list[s];
+        f32x4 x[kVec];
+#pragma unroll
+        for (int v = 0; v < kVec; ++v) x[v] = load_stream4(G + row * ldg + col[v]);
+#pragma unroll
+        for (int v = 0; v < kVec; ++v)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[v][e] += (double)x[v][e];
       }
 #pragma unroll
-      for (int t = 0; t < kRowBatch; ++t) {
-        a0 += (double)v[t][0];
-        a1 += (double)v[t][1];
-        a2 += (double)v[t][2];
-        a3 += (double)v[t][3];
+      for (int v = 0; v < kVec; ++v) {
+        f32x4 r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = (float)(acc[v][e] / n);
+        burst[i * kBlockVec + v * kThreads + threadIdx.x] = r;
       }
     }
-    for (; s < n_sel; ++s) {
-      const long long row = ALL ? s : sel_list[s];
-      const f32x4 v = load_stream4(col + row * ldg);
-      a0 += (double)v[0];
-      a1 += (double)v[1];
-      a2 += (double)v[2];
-      a3 += (double)v[3];
-    }
-    f4u r;
-    r.x = (float)(a0 / n);
-    r.y = (float)(a1 / n);
-    r.z = (float)(a2 / n);
-    r.w = (float)(a3 / n);
-    *reinterpret_cast<f4u*>(out + c * 4) = r;
+    __syncthreads();
+    const long long g0 = g * kBlockVec;
+    const long long left = n_vec - g0;
+    const int n_out = (int)(left < (long long)nb * kBlockVec ? left : (long long)nb * kBlockVec);
+    for (int j = threadIdx.x; j < n_out; j += kThreads) store_burst(out + (g0 + j) * 4, burst[j]);
+    __syncthreads();
   }
   // d mod 4 trailing columns
   if (blockIdx.x == 0) {
@@ -110,15 +176,41 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
 
 hipError_t launch_masked_average(const float* G, long long ldg, const float* scores, int m, long long d, int b,
                                  float* out, int32_t* selected, hipStream_t stream) {
-  long long n_vec = d / 4;
-  long long want = (n_vec + kThreads - 1) / kThreads;
-  int grid = (int)(want < 1 ? 1 : (want > 256 * 16 ? 256 * 16 : want));
+  const long long n_vec = d / 4;
+  // burst length: as long as LDS allows while at least ~512 workgroups' worth of groups remain
+  long long nb = n_vec / ((long long)kBlockVec * 512);
+  const int n_blocks = (int)(nb < 1 ? 1 : (nb > kMaxBlocks ? kMaxBlocks : nb));
+  const size_t lds = ZENO_MAX_CANDIDATES * sizeof(int) + (size_t)n_blocks * kBlockVec * 16;
+  // as many workgroups as the chip holds at once (LDS-limited), each with a balanced share of the blocks
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+      v = 256;
+    n_cu = v;
+  }
+  int per_cu = (int)((160 * 1024) / (lds + 512));
+  per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
+  const long long blocks_total = (n_vec + kBlockVec - 1) / kBlockVec;
+  const long long resident = (long long)n_cu * per_cu;
+  const int grid = (int)(blocks_total < 1 ? 1 : (blocks_total > resident ? resident : blocks_total));
+  static bool attr_set = false;
+  if (!attr_set) {
+    const size_t lds_max = ZENO_MAX_CANDIDATES * sizeof(int) + (size_t)kMaxBlocks * kBlockVec * 16;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&masked_average_kernel<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&masked_average_kernel<false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
   if (scores == nullptr) {
-    hipLaunchKernelGGL(masked_average_kernel<true>, dim3(grid), dim3(kThreads), 0, stream, G, scores, m, d, ldg,
-                       0, out, selected);
+    hipLaunchKernelGGL(masked_average_kernel<true>, dim3(grid), dim3(kThreads), lds, stream, G, scores, m, d, ldg,
+                       0, n_blocks, out, selected);
   } else {
-    hipLaunchKernelGGL(masked_average_kernel<false>, dim3(grid), dim3(kThreads), 0, stream, G, scores, m, d, ldg,
-                       b, out, selected);
+    hipLaunchKernelGGL(masked_average_kernel<false>, dim3(grid), dim3(kThreads), lds, stream, G, scores, m, d, ldg,
+                       b, n_blocks, out, selected);
   }
   return hipGetLastError();
 }
