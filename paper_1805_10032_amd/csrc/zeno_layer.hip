@@ -83,12 +83,14 @@ __device__ inline void store_tiled(void* base, int r, int k, int Kp, float v) {
 template <bool BF16>
 __device__ inline void store_tiled4(void* base, int r, int k0, int Kp, const f32x4& v) {
   const long long idx = tiled_index<BF16>(r, k0, Kp);
+  // write-through stores (system-scope bit): the results are not kept as dirty lines
+  // in the L2, where the streaming weight loads would have to displace them
   if (BF16) {
     bf16x4 t;
     t[0] = (__bf16)v[0]; t[1] = (__bf16)v[1]; t[2] = (__bf16)v[2]; t[3] = (__bf16)v[3];
-    *reinterpret_cast<bf16x4*>(reinterpret_cast<__bf16*>(base) + idx) = t;
+    asm volatile("global_store_dwordx2 %0, %1, off sc1" ::"v"(reinterpret_cast<__bf16*>(base) + idx), "v"(t) : "memory");
   } else {
-    *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(base) + idx) = v;
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(reinterpret_cast<float*>(base) + idx), "v"(v) : "memory");
   }
 }
 
