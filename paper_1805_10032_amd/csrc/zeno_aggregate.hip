@@ -60,7 +60,9 @@ constexpr int kMaxBlocks = 9;                // blocks per burst: 9 x 16 KB of L
 __device__ inline void store_burst(float* p, const f32x4& v) {
   // 16-byte store, write-through to memory (system-coherent scope bit): the line is
   // not kept dirty in the L2, which the streaming row loads would have to displace
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+  // (s_nop: a store wider than 64 bits reads its data registers for two more cycles,
+  // and the compiler does not add the wait states it gives its own stores to assembly)
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 
 template <bool ALL>

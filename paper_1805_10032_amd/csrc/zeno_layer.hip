@@ -84,13 +84,16 @@ template <bool BF16>
 __device__ inline void store_tiled4(void* base, int r, int k0, int Kp, const f32x4& v) {
   const long long idx = tiled_index<BF16>(r, k0, Kp);
   // write-through stores (system-scope bit): the results are not kept as dirty lines
-  // in the L2, where the streaming weight loads would have to displace them
+  // in the L2, where the streaming weight loads would have to displace them.  The
+  // s_nop after the 128-bit store is required: the hardware still reads the data
+  // registers of a store wider than 64 bits for two more cycles, and the compiler,
+  // which adds these wait states to its own stores, does not look inside assembly.
   if (BF16) {
     bf16x4 t;
     t[0] = (__bf16)v[0]; t[1] = (__bf16)v[1]; t[2] = (__bf16)v[2]; t[3] = (__bf16)v[3];
     asm volatile("global_store_dwordx2 %0, %1, off sc1" ::"v"(reinterpret_cast<__bf16*>(base) + idx), "v"(t) : "memory");
   } else {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(reinterpret_cast<float*>(base) + idx), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(reinterpret_cast<float*>(base) + idx), "v"(v) : "memory");
   }
 }
 
@@ -229,11 +232,18 @@ struct Lds {
   static constexpr int TOTAL = BIAS_OFF + NW * 32 * 4;
 };
 
-template <bool BF16, bool DELTA, int MB, int NW, bool NT>
-__global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
+// KS > 1 (pass at x on its own, NW == 1): the KS waves of a workgroup own the SAME 32
+// features and split the K range between them, each with a private copy of the LDS
+// layout and no barrier inside the loop; the partial accumulators are summed through
+// LDS in a fixed tree order at the end and wave 0 writes the results.  A launch of
+// the pass at x has only N/32 feature tiles, far too few single waves to keep enough
+// loads in flight, and this multiplies them by KS.
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS>
+__global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) {
+  static_assert(KS == 1 || NW == 1, "K is only split in one-tile workgroups");
   using T = Tr<BF16>;
   using LD = Lds<BF16, DELTA, MB, NW>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
   constexpr int BN = 32 * NW;
   constexpr int A_BYTES = LD::A_BYTES;
   constexpr int AD_BYTES = LD::AD_BYTES;
@@ -246,7 +256,10 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   constexpr int WREGS = BF16 ? 4 : 8;
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = KS > 1 ? 0 : wave_id;   // feature sub-tile of this wave inside the workgroup's tile
+  const int kw = KS > 1 ? wave_id : 0;     // which part of K this wave sums
+  unsigned char* lds = lds_all + kw * LD::TOTAL;
   unsigned char* stU = lds + LD::STAGE_OFF + wave * STAGE_BYTES;
   float* biasL = reinterpret_cast<float*>(lds + LD::BIAS_OFF) + wave * 32;
 
@@ -301,6 +314,8 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
   // ragged, and BASE (pass at x: no second product, writes W in operand order) or
   // candidate.
   const bool all_full = full_rows && (K & 63) == 0;
+  const int c_begin = KS > 1 ? n_chunks * kw / KS : 0;
+  const int c_end = KS > 1 ? n_chunks * (kw + 1) / KS : n_chunks;
 
   f32x16 acc[MB];
 #pragma unroll
@@ -369,13 +384,19 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
     if (DBUF) {
       // copies(c) were issued before U(c+1) [8 loads] and W(c+1) [WREGS loads]; the
       // last chunk has no such loads behind its copies and waits for everything
-      if (FULL && !BASE && (STEADY || c + 1 < n_chunks)) {
+      // (the stores of the pass at x, which writes W in operand order, share the counter;
+      // they can only make this wait longer, never let it pass early)
+      if (FULL && (STEADY || c + 1 < c_end)) {
         wait_vmcnt<8 + (SECOND ? WREGS : 0)>();
       } else {
         wait_vmcnt<0>();
       }
-      __syncthreads();  // copies of every wave have landed; everyone is done with buffer buf^1
-      if ((STEADY || c + 1 < n_chunks) && !(dbg & 2)) copy_AD(c + 1, buf ^ 1);
+      if (KS == 1) {
+        __syncthreads();  // copies of every wave have landed; everyone is done with buffer buf^1
+      } else {
+        asm volatile("" ::: "memory");  // private buffers: only the compiler must not move LDS reads above the wait
+      }
+      if ((STEADY || c + 1 < c_end) && !(dbg & 2)) copy_AD(c + 1, buf ^ 1);
       __builtin_amdgcn_sched_barrier(0);  // the wait above counts on the copies being issued before the next loads
     } else {
       __syncthreads();  // single buffer: everyone is done with the previous chunk
@@ -383,7 +404,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
       wait_vmcnt<0>();
       __syncthreads();
     }
-    if (STEADY || c + 2 < n_chunks) load_tile<FULL, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
+    if (STEADY || c + 2 < c_end) load_tile<FULL, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
 
     // Matrix products of this chunk in groups of MB products that share one B
     // operand (k-step t, operand H or D).  The scheduler is fenced so that the LDS
@@ -392,20 +413,20 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
     const unsigned char* bufD = bufA + A_BYTES;
     const int n = lane & 31, h = lane >> 5;
     constexpr int OPS = DELTA ? 2 : 1;
-    constexpr int KS = BF16 ? 4 : 8;   // operand k-steps per chunk (16 k / 8 k each)
-    constexpr int NG = KS * OPS;
+    constexpr int KSTEPS = BF16 ? 4 : 8;   // operand k-steps per chunk (16 k / 8 k each)
+    constexpr int NG = KSTEPS * OPS;
     auto read_group = [&](f32x4 (&fr)[MB], int g) __attribute__((always_inline)) {
       const int t = g / OPS, op = g % OPS;
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
-        fr[mb] = *reinterpret_cast<const f32x4*>((op ? bufD : bufA) + ((mb * KS + t) * 64 + lane) * 16);
+        fr[mb] = *reinterpret_cast<const f32x4*>((op ? bufD : bufA) + ((mb * KSTEPS + t) * 64 + lane) * 16);
     };
     auto read_b = [&](int t) __attribute__((always_inline)) {
       if (BF16) return *reinterpret_cast<const f32x4*>(stU + n * 128 + ((((2 * t + h) ^ (n >> 1)) & 7) << 4));
       return *reinterpret_cast<const f32x4*>(stU + n * 256 + ((((2 * t + h) ^ n) & 15) << 4));
     };
     f32x4 fr[NG][MB];
-    f32x4 bq[KS];
+    f32x4 bq[KSTEPS];
     if (dbg & 1) return;
     bq[0] = read_b(0);
     read_group(fr[0], 0);
@@ -434,7 +455,7 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
       }
       if (BASE && pack && op == 0) *reinterpret_cast<f32x4*>(Wt_wave + ((long long)c * WREGS + t) * 1024) = bq[t];
     }
-    if (SECOND && (STEADY || c + 2 < n_chunks)) load_W(w, c + 2);
+    if (SECOND && (STEADY || c + 2 < c_end)) load_W(w, c + 2);
   };
 
   auto run = [&](auto full_c, auto base_c) __attribute__((always_inline)) {
@@ -445,41 +466,65 @@ __global__ __launch_bounds__(64 * NW) void layer_kernel(const LayerArgs a) {
     float bias_lane = 0.f;
     if (J.b_off >= 0 && lane < 32 && row0 + lane < N) bias_lane = P[J.b_off + row0 + lane];
     __builtin_amdgcn_sched_barrier(0);
-    if (DBUF) copy_AD(0, 0);
+    if (DBUF) copy_AD(c_begin, c_begin & 1);
     __builtin_amdgcn_sched_barrier(0);
-    int c = 0;
-    if (FULL && DBUF && n_chunks >= 4) {
+    int c = c_begin;
+    const float* Ufirst = Urow0 + (c_begin << 6);
+    if (FULL && DBUF && c_end - c_begin >= 4) {
       // steady state: pairs of chunks whose loads (two chunks ahead) all exist
-      load_tile<FULL, NT>(u0, Urow0, lane_off, row0, 0, N, K, lane);
-      load_tile<FULL, NT>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
+      load_tile<FULL, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
+      load_tile<FULL, NT>(u1, Ufirst + 64, lane_off, row0, (c_begin + 1) << 6, N, K, lane);
       if (SECOND) {
-        load_W(w0, 0);
-        load_W(w1, 1);
+        load_W(w0, c_begin);
+        load_W(w1, c_begin + 1);
       }
       if (lane < 32) biasL[lane] = bias_lane;
-      for (; c + 3 < n_chunks; c += 2) {
+      for (; c + 3 < c_end; c += 2) {
         chunk(full_c, base_c, std::true_type{}, u0, w0, c);
         chunk(full_c, base_c, std::true_type{}, u1, w1, c + 1);
       }
     } else {
-      load_tile<FULL, NT>(u0, Urow0, lane_off, row0, 0, N, K, lane);
-      if (n_chunks > 1) load_tile<FULL, NT>(u1, Urow0 + 64, lane_off, row0, 64, N, K, lane);
+      if (c_begin < c_end) load_tile<FULL, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
+      if (c_begin + 1 < c_end) load_tile<FULL, NT>(u1, Ufirst + 64, lane_off, row0, (c_begin + 1) << 6, N, K, lane);
       if (SECOND) {
-        load_W(w0, 0);
-        if (n_chunks > 1) load_W(w1, 1);
+        load_W(w0, c_begin);
+        if (c_begin + 1 < c_end) load_W(w1, c_begin + 1);
       }
       if (lane < 32) biasL[lane] = bias_lane;
     }
     // the last two or three chunks (all of them for a short K): every load is conditional
-    for (; c < n_chunks; c += 2) {
+    for (; c < c_end; c += 2) {
       chunk(full_c, base_c, std::false_type{}, u0, w0, c);
-      if (c + 1 < n_chunks) chunk(full_c, base_c, std::false_type{}, u1, w1, c + 1);
+      if (c + 1 < c_end) chunk(full_c, base_c, std::false_type{}, u1, w1, c + 1);
     }
+    if (KS > 1) wait_vmcnt<0>();  // a wave with an empty K range still has its first copy in flight
   };
   if (is_base) {
     if (all_full) run(std::true_type{}, std::true_type{}); else run(std::false_type{}, std::true_type{});
   } else {
     if (all_full) run(std::true_type{}, std::false_type{}); else run(std::false_type{}, std::false_type{});
+  }
+
+  if (KS > 1) {
+    // sum the KS partial accumulators in a fixed tree: (0+2)+(1+3) for KS = 4
+    float* red = reinterpret_cast<float*>(lds_all);
+    for (int step = KS / 2; step >= 1; step >>= 1) {
+      __syncthreads();  // all waves are out of their loops / done reading the previous round
+      if (kw >= step && kw < 2 * step) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) red[(((kw - step) * MB + mb) * 16 + j) * 64 + lane] = acc[mb][j];
+      }
+      __syncthreads();
+      if (kw < step) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) acc[mb][j] += red[((kw * MB + mb) * 16 + j) * 64 + lane];
+      }
+    }
+    if (kw != 0) return;
   }
 
   // ---- epilogue.  The weight tile is the first operand of the products, so the
@@ -634,13 +679,13 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
 
 int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
 
-template <bool BF16, bool DELTA, int MB, int NW, bool NT>
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1>
 hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
   constexpr int BN = 32 * NW;
-  constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL;
+  constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL * KS;
   static bool attr_set = false;
   if (!attr_set && lds_bytes > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT, KS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -652,8 +697,8 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
     const int units = job_tiles(a.cj, BN) * ((a.n_cand + cc - 1) / cc);
     cand_blocks = ((units + 7) / 8) * 8 * cc;
   }
-  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW, NT>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW), lds_bytes,
-                     stream, a);
+  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW, NT, KS>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW * KS),
+                     lds_bytes, stream, a);
   return hipGetLastError();
 }
 
@@ -664,7 +709,7 @@ int wgs_per_cu_inst() {
   if (cached == 0) {
     constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL;
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, false>),
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, false, 1>),
                                                      64 * NW, lds_bytes) != hipSuccess || n < 1)
       n = 1;
     cached = n;
@@ -697,8 +742,17 @@ bool launch_lines_aligned(const LayerArgs& a) {
   return ok;
 }
 
+constexpr int kSplitK = 4;  // waves that share one feature tile of a lone pass at x
+
 template <bool BF16, bool DELTA, int MB, int NW>
 hipError_t launch_nt(const LayerArgs& a, hipStream_t stream) {
+  // A pass at x on its own, one-tile workgroups, a K long enough to split, and LDS for kSplitK private layouts
+  if constexpr (NW == 1 && !DELTA && Lds<BF16, DELTA, MB, 1>::TOTAL * kSplitK <= 160 * 1024) {
+    if (a.n_cand == 0 && a.has_base && (a.bj.Kp >> 6) >= 2 * kSplitK) {
+      if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, kSplitK>(a, stream);
+      return launch_inst<BF16, DELTA, MB, NW, false, kSplitK>(a, stream);
+    }
+  }
   if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream);
   return launch_inst<BF16, DELTA, MB, NW, false>(a, stream);
 }

@@ -96,6 +96,35 @@ def test_small_shapes(B, case, fwd):
     _check_step(B, w)
 
 
+LONG_K = [("fp32", 32, [3072, 512, 10]), ("bf16", 32, [3072, 512, 10]), ("bf16", 128, [1024, 512, 10]),
+          ("fp32", 64, [1024, 512, 10]), ("fp32", 32, [512, 64, 10]), ("fp32", 20, [640, 96, 10]), ("bf16", 20, [640, 96, 10]),
+          ("fp32", 100, [576, 130, 70, 3])]
+
+
+@pytest.mark.parametrize("fwd,n_r,dims", LONG_K)
+def test_long_k_layers(B, fwd, n_r, dims):
+    """Input widths of eight and more 64-wide chunks: the pass at x on its own splits K
+    over the waves of a workgroup there (both operand types, one to four row blocks, a
+    chunk count that the waves do not share evenly), and fp32 activations leave the
+    kernels through 128-bit stores."""
+    w = WL.make_mlp_workload("longk", 95, dims, 6, 2, n_r, 0.05, 1e-3, fwd, seed=n_r, n_flip=2)
+    _check_step(B, w)
+
+
+def test_workspace_contents_do_not_matter(B):
+    """The scratch memory is written before it is read: a workspace full of NaN gives the
+    same scores, bit for bit, as a zeroed one."""
+    w = WL.make_config(3)
+    mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
+    x, G, F, lab = w.x.cuda(), w.G.contiguous().cuda(), w.features.cuda(), w.labels.cuda()
+    out = []
+    for fill in (0.0, float("nan")):
+        ws = B.alloc_workspace(mdl, w.m, w.n_r, x.device)
+        ws.view(torch.float32).fill_(fill)
+        out.append(npy(B.zeno_score(mdl, x, G, F, w.gamma, w.rho, labels=lab, workspace=ws)))
+    assert np.array_equal(out[0], out[1]) and np.all(np.isfinite(out[0]))
+
+
 @pytest.mark.parametrize("fwd", ["fp32", "bf16"])
 def test_batches_larger_than_one_pass(B, fwd):
     """n_r > 128: several passes over G, the ragged last one shorter."""
