@@ -135,20 +135,39 @@ __device__ inline void store4_masked(float* __restrict__ row, int k, int K, cons
 // Load the wave's 32 x 64 weight tile: instruction j covers rows 4j..4j+3, 256
 // contiguous bytes each.  `tile` is the wave-uniform address of element (row0, k0);
 // `lane_off` = (lane/16)*K + 4*(lane%16) is the lane's element offset inside it.
-// FULL: the whole tile lies inside the matrix (no masking code is generated).
+// MODE 1: the whole tile lies inside the matrix (no masking code is generated).
+// MODE 2: every K chunk is complete but some rows lie at or beyond N: they read row
+// N-1 instead (always in bounds) and the caller discards them, so that a ragged last
+// feature tile runs the same straight-line loop as a full one.
+// MODE 0: K is not a multiple of the chunk width (element-wise guards in the last chunk).
 // NT: streaming loads that do not keep the lines in the caches.  Only chosen when
 // every 256-byte row segment starts on a 128-byte line: a line that two load
 // instructions share would otherwise be fetched from memory twice.
-template <bool FULL, bool NT>
+template <int MODE, bool NT>
 __device__ inline void load_tile(f32x4 (&u)[8], const float* __restrict__ tile, unsigned lane_off, int row0, int k0,
                                  int N, int K, int lane) {
-  if (FULL) {
+  if (MODE != 0) {
+    if (MODE == 1) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (NT) {
-        u[j] = load_stream4(tile + (long long)(4 * j) * K + lane_off);
-      } else {
-        u[j] = *reinterpret_cast<const f32x4_a4*>(tile + (long long)(4 * j) * K + lane_off);
+      for (int j = 0; j < 8; ++j) {
+        if (NT) {
+          u[j] = load_stream4(tile + (long long)(4 * j) * K + lane_off);
+        } else {
+          u[j] = *reinterpret_cast<const f32x4_a4*>(tile + (long long)(4 * j) * K + lane_off);
+        }
+      }
+    } else {
+      const int rsub = lane >> 4, kq = (lane & 15) << 2;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = row0 + 4 * j + rsub;
+        const int rel = (row < N ? row : N - 1) - row0;   // may be negative: the tile starts beyond the matrix
+        const float* p = tile + (long long)rel * K + kq;
+        if (NT) {
+          u[j] = load_stream4(p);
+        } else {
+          u[j] = *reinterpret_cast<const f32x4_a4*>(p);
+        }
       }
     }
   } else {
@@ -308,12 +327,11 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   const bool pack = is_base && J.Wt != nullptr;
   unsigned char* Wt_wave = reinterpret_cast<unsigned char*>(J.Wt) +
                            ((long long)(row0 >> 5) * n_chunks * WREGS * 64 + lane) * 16;
-  // The main loop exists in four versions chosen per wave: FULL (every weight tile
-  // lies inside the matrix: straight-line loads, and the in-order completion of
-  // loads lets a candidate chunk wait for exactly its own activation copies) or
-  // ragged, and BASE (pass at x: no second product, writes W in operand order) or
+  // The main loop exists in six versions chosen per wave: full tile / full K with some
+  // rows beyond the matrix (both: straight-line loads, and the in-order completion of
+  // loads lets a chunk wait for exactly its own activation copies) / ragged in K, and BASE (pass at x: no second product, writes W in operand order) or
   // candidate.
-  const bool all_full = full_rows && (K & 63) == 0;
+  const bool all_full = (K & 63) == 0;
   const int c_begin = KS > 1 ? n_chunks * kw / KS : 0;
   const int c_end = KS > 1 ? n_chunks * (kw + 1) / KS : n_chunks;
 
@@ -369,11 +387,18 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // of every chunk, i.e. no tile would stay in flight across a chunk.
   auto chunk = [&](auto full_c, auto base_c, auto steady_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c)
                    __attribute__((always_inline)) {
-    constexpr bool FULL = decltype(full_c)::value;
+    constexpr int MODE = decltype(full_c)::value;
+    constexpr bool FULL = MODE != 0;
     constexpr bool BASE = decltype(base_c)::value;   // this workgroup runs the pass at x
     constexpr bool STEADY = decltype(steady_c)::value;
     constexpr bool SECOND = DELTA && !BASE;           // second product D W^T present
     const int buf = DBUF ? (c & 1) : 0;
+    if (MODE == 2) {
+      // rows beyond the matrix were read from row N-1: discard them
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) u[j] = (row0 + 4 * j + (lane >> 4) < N) ? u[j] : zero;
+    }
     if (do_norm) {
       float q = 0.f;
 #pragma unroll
@@ -404,7 +429,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       wait_vmcnt<0>();
       __syncthreads();
     }
-    if (STEADY || c + 2 < c_end) load_tile<FULL, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
+    if (STEADY || c + 2 < c_end) load_tile<MODE, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
 
     // Matrix products of this chunk in groups of MB products that share one B
     // operand (k-step t, operand H or D).  The scheduler is fenced so that the LDS
@@ -459,7 +484,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   };
 
   auto run = [&](auto full_c, auto base_c) __attribute__((always_inline)) {
-    constexpr bool FULL = decltype(full_c)::value;
+    constexpr int MODE = decltype(full_c)::value;
+    constexpr bool FULL = MODE != 0;
     constexpr bool SECOND = DELTA && !decltype(base_c)::value;
     // The wave's 32 bias values are requested first of all and parked in LDS, so
     // that the epilogue does not start with a round trip to memory.
@@ -472,8 +498,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     const float* Ufirst = Urow0 + (c_begin << 6);
     if (FULL && DBUF && c_end - c_begin >= 4) {
       // steady state: pairs of chunks whose loads (two chunks ahead) all exist
-      load_tile<FULL, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
-      load_tile<FULL, NT>(u1, Ufirst + 64, lane_off, row0, (c_begin + 1) << 6, N, K, lane);
+      load_tile<MODE, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
+      load_tile<MODE, NT>(u1, Ufirst + 64, lane_off, row0, (c_begin + 1) << 6, N, K, lane);
       if (SECOND) {
         load_W(w0, c_begin);
         load_W(w1, c_begin + 1);
@@ -484,8 +510,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
         chunk(full_c, base_c, std::true_type{}, u1, w1, c + 1);
       }
     } else {
-      if (c_begin < c_end) load_tile<FULL, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
-      if (c_begin + 1 < c_end) load_tile<FULL, NT>(u1, Ufirst + 64, lane_off, row0, (c_begin + 1) << 6, N, K, lane);
+      if (c_begin < c_end) load_tile<MODE, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
+      if (c_begin + 1 < c_end) load_tile<MODE, NT>(u1, Ufirst + 64, lane_off, row0, (c_begin + 1) << 6, N, K, lane);
       if (SECOND) {
         load_W(w0, c_begin);
         if (c_begin + 1 < c_end) load_W(w1, c_begin + 1);
@@ -499,10 +525,17 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     }
     if (KS > 1) wait_vmcnt<0>();  // a wave with an empty K range still has its first copy in flight
   };
+  using M0 = std::integral_constant<int, 0>;
+  using M1 = std::integral_constant<int, 1>;
+  using M2 = std::integral_constant<int, 2>;
   if (is_base) {
-    if (all_full) run(std::true_type{}, std::true_type{}); else run(std::false_type{}, std::true_type{});
+    if (all_full && full_rows) run(M1{}, std::true_type{});
+    else if (all_full) run(M2{}, std::true_type{});
+    else run(M0{}, std::true_type{});
   } else {
-    if (all_full) run(std::true_type{}, std::false_type{}); else run(std::false_type{}, std::false_type{});
+    if (all_full && full_rows) run(M1{}, std::false_type{});
+    else if (all_full) run(M2{}, std::false_type{});
+    else run(M0{}, std::false_type{});
   }
 
   if (KS > 1) {
