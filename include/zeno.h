@@ -135,6 +135,20 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
 zeno_status_t zeno_aggregate(const float* G, int64_t ldg, const float* scores, int32_t m, int64_t d, int32_t b,
                              float* out, int32_t* selected, void* stream);
 
+/* Definition 3 followed by the server's update of Algorithm 1 in the same pass over
+ * the chosen rows:  x_next = x - gamma * Zeno_b(G).  The step is taken from the
+ * float64 average before it is rounded (x_next[j] = fl32(x[j] - gamma * avg_j), product
+ * and difference in float64), so it costs one read of x and one write of x_next
+ * instead of a separate pass over d values.
+ *   x       DEVICE [d]   current parameters
+ *   x_next  DEVICE [d]   out; may be x itself (in place)
+ *   out     DEVICE [d]   the aggregate as zeno_aggregate writes it, or NULL if only x_next is wanted
+ *   gamma   finite, >= 0
+ * Other arguments and errors as for zeno_aggregate. */
+zeno_status_t zeno_aggregate_update(const float* G, int64_t ldg, const float* scores, int32_t m, int64_t d,
+                                    int32_t b, float gamma, const float* x, float* x_next, float* out,
+                                    int32_t* selected, void* stream);
+
 /* Mean baseline (Section 6.1.1): out[j] = (1/m) sum_i G[i][j]. */
 zeno_status_t zeno_mean(const float* G, int64_t ldg, int32_t m, int64_t d, float* out, void* stream);
 
@@ -162,7 +176,8 @@ typedef enum {
   ZENO_KERNEL_COMBINE = 4,    /* mean, norm and the three-term score */
   ZENO_KERNEL_AVERAGE = 5,    /* selection + average of the chosen rows */
   ZENO_KERNEL_MEAN = 6,
-  ZENO_KERNEL_MEDIAN = 7
+  ZENO_KERNEL_MEDIAN = 7,
+  ZENO_KERNEL_AVERAGE_UPDATE = 8 /* selection + average + x_next = x - gamma * average */
 } zeno_kernel_t;
 
 typedef struct {

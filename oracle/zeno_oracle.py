@@ -18,8 +18,11 @@ Pins (see tests/test_oracle_*.py): least-squares closed form, b=0 equals Mean,
 b=m-1 equals the arg-max row, Lemma 1 (bounded score), the Assumption 2
 sandwich for convex losses, ln C at zero parameters, library cross-checks for
 logsumexp / mean / median / an MLP forward, brute-force subset enumeration,
-the 1-D example in the Discussion section for Mean / Median / Krum, and the
-(m+1) forward-evaluation count of the Discussion section.
+the 1-D example in the Discussion section for Mean / Median / Krum, the
+(m+1) forward-evaluation count of the Discussion section, and for the server's
+update of Algorithm 1: the descent it achieves equals the score of the
+aggregate (Definition 2 at rho = 0), and iterating it converges under a faulty
+majority where the Mean diverges.
 """
 from __future__ import annotations
 
@@ -171,6 +174,18 @@ def krum(G, b):
         if val < best_val:
             best, best_val = i, val
     return G[best].copy(), best
+
+
+def sgd_update(x, v, gamma):
+    """The server's update of Algorithm 1: x_next = x - gamma v, in float64."""
+    return np.asarray(x, dtype=np.float64) - float(gamma) * np.asarray(v, dtype=np.float64)
+
+
+def zeno_update(x, G, score_values, b, gamma):
+    """Algorithm 1, server side after the scores: x_next = x - gamma Zeno_b(G).
+    Returns (x_next float64, selected indices)."""
+    v, sel = zeno_aggregate(G, score_values, b)
+    return sgd_update(x, v, gamma), sel
 
 
 def zeno_step(x, G, b, gamma, rho, dims, has_bias, loss, features, labels=None, targets=None):

@@ -22,10 +22,10 @@ FWD = {"fp32": 0, "bf16": 1}
 STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported size", 3: "workspace", 4: "device"}
 
 EXPORTS = ["zeno_model_create", "zeno_model_destroy", "zeno_model_num_params",
-           "zeno_score_workspace_bytes", "zeno_score", "zeno_aggregate", "zeno_mean",
+           "zeno_score_workspace_bytes", "zeno_score", "zeno_aggregate", "zeno_aggregate_update", "zeno_mean",
            "zeno_median", "zeno_status_string", "zeno_profile_enable", "zeno_profile_collect"]
 
-KERNEL_NAMES = ["pack", "layer_base", "layer_cand", "loss", "combine", "average", "mean", "median"]
+KERNEL_NAMES = ["pack", "layer_base", "layer_cand", "loss", "combine", "average", "mean", "median", "average_update"]
 
 
 class ZenoError(RuntimeError):
@@ -81,6 +81,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.zeno_score.restype = ctypes.c_int
     lib.zeno_aggregate.argtypes = [vp, i64, vp, i32, i64, i32, vp, vp, vp]
     lib.zeno_aggregate.restype = ctypes.c_int
+    lib.zeno_aggregate_update.argtypes = [vp, i64, vp, i32, i64, i32, f32, vp, vp, vp, vp, vp]
+    lib.zeno_aggregate_update.restype = ctypes.c_int
     lib.zeno_mean.argtypes = [vp, i64, i32, i64, vp, vp]
     lib.zeno_mean.restype = ctypes.c_int
     lib.zeno_median.argtypes = [vp, i64, i32, i64, vp, vp]
@@ -227,6 +229,31 @@ def zeno_aggregate(G, scores, b, *, out=None, selected=None, want_selected=True)
     if st != 0:
         raise ZenoError(st, "zeno_aggregate")
     return out, selected
+
+
+def zeno_aggregate_update(G, scores, b, gamma, x, *, x_next=None, out=None, want_out=True, selected=None,
+                          want_selected=True):
+    """Zeno_b and the server's SGD step in one pass: x_next = x - gamma * Zeno_b(G)
+    (Algorithm 1, server side).  x_next=x updates in place.  Returns (x_next, out, selected)."""
+    lib = load_library()
+    m, d = int(G.shape[0]), int(G.shape[1])
+    if x.numel() != d:
+        raise ValueError("x does not match the width of G")
+    if x_next is None:
+        x_next = torch.empty(d, dtype=torch.float32, device=G.device)
+    if out is None and want_out:
+        out = torch.empty(d, dtype=torch.float32, device=G.device)
+    if selected is None and want_selected and 0 <= b < m:
+        selected = torch.empty(m - b, dtype=torch.int32, device=G.device)
+    g_ptr, ldg = _rows(G)
+    st = lib.zeno_aggregate_update(g_ptr, ldg, _dev(scores, torch.float32, "scores"), m, d, int(b), float(gamma),
+                                   _dev(x, torch.float32, "x"), _dev(x_next, torch.float32, "x_next"),
+                                   _dev(out, torch.float32, "out") if out is not None else None,
+                                   _dev(selected, torch.int32, "selected") if selected is not None else None,
+                                   _stream())
+    if st != 0:
+        raise ZenoError(st, "zeno_aggregate_update")
+    return x_next, out, selected
 
 
 def zeno_mean(G, *, out=None):

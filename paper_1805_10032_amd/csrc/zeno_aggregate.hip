@@ -65,12 +65,24 @@ __device__ inline void store_burst(float* p, const f32x4& v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 
-template <bool ALL>
+// The SGD step of Algorithm 1 (server side), x_next = x - gamma * aggregate, from the
+// float64 average before it is rounded: one rounding to fp32 in all.  Contraction is
+// off so that the product and the difference are rounded separately, as written.
+__device__ inline float sgd_step(float x, double gamma, double avg) {
+#pragma clang fp contract(off)
+  const double step = gamma * avg;
+  return (float)((double)x - step);
+}
+
+// UPDATE: also (or only, out == nullptr) write x_next = x - gamma * average; x_next may
+// be x itself (every column is read and written by one thread).
+template <bool ALL, bool UPDATE>
 __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* __restrict__ G,
                                                                   const float* __restrict__ scores, int m,
                                                                   long long d, long long ldg, int b, int n_blocks,
                                                                   float* __restrict__ out,
-                                                                  int32_t* __restrict__ selected) {
+                                                                  int32_t* __restrict__ selected, float gamma,
+                                                                  const float* x, float* x_next) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   // [selected row list][burst buffer]; the selection's scratch (keys, flags) lies
   // in the burst buffer, which is not used before the selection is over
@@ -84,6 +96,8 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
   }
 
   const double n = (double)n_sel;
+  // second burst buffer (new parameters) behind the first (average) when both are written
+  const int xoff = (UPDATE && out != nullptr) ? n_blocks * kBlockVec : 0;
   const long long n_vec = d / 4;
   // balanced contiguous share of the column blocks, worked through in bursts of n_blocks
   const long long blocks_total = (n_vec + kBlockVec - 1) / kBlockVec;
@@ -104,6 +118,11 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
       for (int v = 0; v < kVec; ++v) {
         const long long c = c0 + v * kThreads;
         col[v] = (c < n_vec ? c : n_vec - 1) * 4;
+      }
+      f32x4 xv[kVec];
+      if (UPDATE) {
+#pragma unroll
+        for (int v = 0; v < kVec; ++v) xv[v] = *reinterpret_cast<const f32x4_a4*>(x + col[v]);
       }
       constexpr int RB = ALL ? kRowsAll : kRowsSel;
       int s = 0;
@@ -148,17 +167,27 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
       }
 #pragma unroll
       for (int v = 0; v < kVec; ++v) {
-        f32x4 r;
+        f32x4 r, xn;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) r[e] = (float)(acc[v][e] / n);
-        burst[i * kBlockVec + v * kThreads + threadIdx.x] = r;
+        for (int e = 0; e < 4; ++e) {
+          const double avg = acc[v][e] / n;
+          r[e] = (float)avg;
+          if (UPDATE) xn[e] = sgd_step(xv[v][e], (double)gamma, avg);
+        }
+        const int slot = i * kBlockVec + v * kThreads + threadIdx.x;
+        if (!UPDATE || out != nullptr) burst[slot] = r;
+        if (UPDATE) burst[xoff + slot] = xn;
       }
     }
     __syncthreads();
     const long long g0 = g * kBlockVec;
     const long long left = n_vec - g0;
     const int n_out = (int)(left < (long long)nb * kBlockVec ? left : (long long)nb * kBlockVec);
-    for (int j = threadIdx.x; j < n_out; j += kThreads) store_burst(out + (g0 + j) * 4, burst[j]);
+    if (!UPDATE || out != nullptr)
+      for (int j = threadIdx.x; j < n_out; j += kThreads) store_burst(out + (g0 + j) * 4, burst[j]);
+    if (UPDATE)
+      for (int j = threadIdx.x; j < n_out; j += kThreads)
+        store_burst(x_next + (g0 + j) * 4, burst[xoff + j]);
     __syncthreads();
   }
   // d mod 4 trailing columns
@@ -169,7 +198,8 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
         const long long row = ALL ? s : sel_list[s];
         a += (double)G[row * ldg + j];
       }
-      out[j] = (float)(a / n);
+      if (!UPDATE || out != nullptr) out[j] = (float)(a / n);
+      if (UPDATE) x_next[j] = sgd_step(x[j], (double)gamma, a / n);
     }
   }
 }
@@ -177,12 +207,16 @@ __global__ __launch_bounds__(kThreads) void masked_average_kernel(const float* _
 }  // namespace
 
 hipError_t launch_masked_average(const float* G, long long ldg, const float* scores, int m, long long d, int b,
-                                 float* out, int32_t* selected, hipStream_t stream) {
+                                 float* out, int32_t* selected, hipStream_t stream, float gamma, const float* x,
+                                 float* x_next) {
+  const bool update = x_next != nullptr;
+  const int n_bufs = (update && out != nullptr) ? 2 : 1;   // burst buffers: the average, the new parameters
+  const int max_blocks = kMaxBlocks / n_bufs;
   const long long n_vec = d / 4;
   // burst length: as long as LDS allows while at least ~512 workgroups' worth of groups remain
   long long nb = n_vec / ((long long)kBlockVec * 512);
-  const int n_blocks = (int)(nb < 1 ? 1 : (nb > kMaxBlocks ? kMaxBlocks : nb));
-  const size_t lds = ZENO_MAX_CANDIDATES * sizeof(int) + (size_t)n_blocks * kBlockVec * 16;
+  const int n_blocks = (int)(nb < 1 ? 1 : (nb > max_blocks ? max_blocks : nb));
+  const size_t lds = ZENO_MAX_CANDIDATES * sizeof(int) + (size_t)n_bufs * n_blocks * kBlockVec * 16;
   // as many workgroups as the chip holds at once (LDS-limited), each with a balanced share of the blocks
   static int n_cu = 0;
   if (n_cu == 0) {
@@ -198,22 +232,27 @@ hipError_t launch_masked_average(const float* G, long long ldg, const float* sco
   const int grid = (int)(blocks_total < 1 ? 1 : (blocks_total > resident ? resident : blocks_total));
   static bool attr_set = false;
   if (!attr_set) {
-    const size_t lds_max = ZENO_MAX_CANDIDATES * sizeof(int) + (size_t)kMaxBlocks * kBlockVec * 16;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&masked_average_kernel<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&masked_average_kernel<false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_max);
-    if (e != hipSuccess) return e;
+    const int lds_max = (int)(ZENO_MAX_CANDIDATES * sizeof(int) + (size_t)kMaxBlocks * kBlockVec * 16);
+    const void* kernels[4] = {reinterpret_cast<const void*>(&masked_average_kernel<true, false>),
+                              reinterpret_cast<const void*>(&masked_average_kernel<false, false>),
+                              reinterpret_cast<const void*>(&masked_average_kernel<true, true>),
+                              reinterpret_cast<const void*>(&masked_average_kernel<false, true>)};
+    for (const void* k : kernels) {
+      hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_max);
+      if (e != hipSuccess) return e;
+    }
     attr_set = true;
   }
-  if (scores == nullptr) {
-    hipLaunchKernelGGL(masked_average_kernel<true>, dim3(grid), dim3(kThreads), lds, stream, G, scores, m, d, ldg,
-                       0, n_blocks, out, selected);
-  } else {
-    hipLaunchKernelGGL(masked_average_kernel<false>, dim3(grid), dim3(kThreads), lds, stream, G, scores, m, d, ldg,
-                       b, n_blocks, out, selected);
-  }
+  const bool all = scores == nullptr;
+  const int bb = all ? 0 : b;
+#define ZENO_LAUNCH_AVG(ALLV, UPD)                                                                                  \
+  hipLaunchKernelGGL((masked_average_kernel<ALLV, UPD>), dim3(grid), dim3(kThreads), lds, stream, G, scores, m, d, \
+                     ldg, bb, n_blocks, out, selected, gamma, x, x_next)
+  if (all && !update) ZENO_LAUNCH_AVG(true, false);
+  else if (all) ZENO_LAUNCH_AVG(true, true);
+  else if (!update) ZENO_LAUNCH_AVG(false, false);
+  else ZENO_LAUNCH_AVG(false, true);
+#undef ZENO_LAUNCH_AVG
   return hipGetLastError();
 }
 

@@ -329,6 +329,22 @@ zeno_status_t zeno_aggregate(const float* G, int64_t ldg, const float* scores, i
   return ZENO_OK;
 }
 
+zeno_status_t zeno_aggregate_update(const float* G, int64_t ldg, const float* scores, int32_t m, int64_t d,
+                                    int32_t b, float gamma, const float* x, float* x_next, float* out,
+                                    int32_t* selected, void* stream) {
+  if (G == nullptr || scores == nullptr || x == nullptr || x_next == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || b < 0 || b >= m || d < 1 || ldg < d) return ZENO_ERR_INVALID_ARG;
+  if (!std::isfinite(gamma) || gamma < 0.f) return ZENO_ERR_INVALID_ARG;
+  if (!aligned(G, 4) || !aligned(scores, 4) || !aligned(x, 4) || !aligned(x_next, 4) || !aligned(out, 4) ||
+      !aligned(selected, 4))
+    return ZENO_ERR_INVALID_ARG;
+  ProfScope ps(ZENO_KERNEL_AVERAGE_UPDATE, 0, 4.0 * (double)d * (m - b + 2 + (out != nullptr ? 1 : 0)),
+               reinterpret_cast<hipStream_t>(stream));
+  ZENO_TRY(launch_masked_average(G, ldg, scores, m, d, b, out, selected, reinterpret_cast<hipStream_t>(stream), gamma,
+                                 x, x_next));
+  return ZENO_OK;
+}
+
 zeno_status_t zeno_mean(const float* G, int64_t ldg, int32_t m, int64_t d, float* out, void* stream) {
   if (G == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
   if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1 || ldg < d) return ZENO_ERR_INVALID_ARG;

@@ -86,8 +86,10 @@ hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, 
                        double* sample_diff, hipStream_t stream);
 hipError_t launch_score_combine(const double* sample_diff, const double* norm_partials, int P, int m,
                                 int n_r_total, float rho, float* scores, hipStream_t stream);
+// x_next != nullptr: also write x_next = x - gamma * average (out may then be nullptr)
 hipError_t launch_masked_average(const float* G, long long ldg, const float* scores, int m, long long d, int b,
-                                 float* out, int32_t* selected, hipStream_t stream);
+                                 float* out, int32_t* selected, hipStream_t stream, float gamma = 0.f,
+                                 const float* x = nullptr, float* x_next = nullptr);
 hipError_t launch_median(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream);
 
 }  // namespace zeno

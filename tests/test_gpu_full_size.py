@@ -100,6 +100,10 @@ def test_full_size_parity(cfg, capsys):
         ref_sel += cols[int(i)].astype(np.float64)
     ref_sel /= len(sel_np)
     assert np.array_equal(npy(out[idx]), ref_sel.astype(np.float32))
+    # the same pass with the server's SGD step (Algorithm 1): x_next = x - gamma * average
+    x_next, _, _ = B.zeno_aggregate_update(w.G, s_gpu, w.b, w.gamma, w.x, want_out=False, want_selected=False)
+    ref_next = O.sgd_update(npy(w.x[idx]), ref_sel, float(np.float32(w.gamma)))
+    assert np.array_equal(npy(x_next[idx]), ref_next.astype(np.float32))
     assert np.array_equal(npy(mean[idx]), O.mean(cols).astype(np.float32))
     assert np.array_equal(npy(med[idx]), O.median(cols).astype(np.float32))
-    _say(capsys, "aggregate / mean / median bit-exact on 20128 sampled coordinates\n")
+    _say(capsys, "aggregate / update / mean / median bit-exact on 20128 sampled coordinates\n")

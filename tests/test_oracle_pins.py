@@ -289,3 +289,60 @@ def test_discussion_one_dimensional_example():
     assert chosen[0] == vals["krum"][0] and idx in (0, 1)
     assert abs(O.mean(G)[0] - vals["mean"][0]) < 1e-15
     assert abs(O.median(G)[0] - vals["median"][0]) < 1e-15
+
+
+# ---------------------------------------------------------------- server update (Algorithm 1)
+def test_update_descent_equals_the_score_of_the_aggregate():
+    """x_next = x - gamma * Zeno_b(G) (Algorithm 1): the loss decrease the update achieves on the
+    server's batch is, by Definition 2 with rho = 0, the score of the aggregate itself.  A wrong
+    sign or a misplaced gamma in the update breaks the equality."""
+    w = WL.make_config(1)
+    x, G = _np(w.x).astype(np.float64), _np(w.G).astype(np.float64)
+    args = (w.dims, w.has_bias, w.loss, _np(w.features), _np(w.labels), _np(w.targets))
+    s = _oracle_scores(w)
+    x_next, sel = O.zeno_update(x, G, s, w.b, w.gamma)
+    v, sel2 = O.zeno_aggregate(G, s, w.b)
+    assert np.array_equal(sel, sel2)
+    f0 = O.f_r(x, *args)
+    descent = f0 - O.f_r(x_next, *args)
+    assert descent == pytest.approx(O.score(x, v, w.gamma, 0.0, f0, *args), rel=1e-12, abs=1e-15)
+    assert descent > 0.0                      # the honest rows of this workload are descent directions
+
+
+def test_update_special_cases():
+    rng = np.random.default_rng(5)
+    x, v = rng.normal(size=9), rng.normal(size=9)
+    G = np.tile(v, (6, 1))
+    s = rng.normal(size=6)
+    assert np.array_equal(O.zeno_update(x, G, s, 2, 0.0)[0], x)                 # gamma = 0
+    assert np.allclose(O.zeno_update(x, G, s, 2, 0.3)[0], x - 0.3 * v, rtol=0, atol=1e-15)   # identical rows
+    assert np.array_equal(O.zeno_update(x, G * 0.0, s, 2, 0.3)[0], x)           # zero candidates
+
+
+def test_update_iterated_converges_with_a_faulty_majority_where_mean_diverges():
+    """Least squares, m = 10 workers of which q = 6 send -4 x the true gradient (Section 6.4's
+    sign-flipping at q > m/2): iterating the oracle's Zeno step with b = 6 drives the loss down,
+    the same loop with the Mean drives it up (Theorem 1 needs only one honest worker)."""
+    rng = np.random.default_rng(11)
+    n, d, m, q, gamma, rho = 64, 12, 10, 6, 0.05, 1e-3
+    A = rng.normal(size=(n, d))
+    y = A @ rng.normal(size=d)
+    dims, args = [d, 1], None
+    def loss(x):
+        return O.f_r(x, dims, False, O.LOSS_SQUARED, A, None, y)
+    def rows(x):
+        g = A.T @ (A @ x - y) / n
+        G = np.empty((m, d))
+        for i in range(m):
+            G[i] = -4.0 * g if i < q else g + rng.normal(size=d) * 1e-3
+        return G
+    x_z = x_m = rng.normal(size=d)
+    f_start = loss(x_z)
+    for _ in range(60):
+        Gz = rows(x_z)
+        s = O.scores(x_z, Gz, gamma, rho, dims, False, O.LOSS_SQUARED, A, None, y)
+        x_z, sel = O.zeno_update(x_z, Gz, s, q, gamma)
+        assert set(sel.tolist()) == set(range(q, m))
+        x_m = O.sgd_update(x_m, O.mean(rows(x_m)), gamma)
+    assert loss(x_z) < 0.05 * f_start
+    assert loss(x_m) > 10.0 * f_start
