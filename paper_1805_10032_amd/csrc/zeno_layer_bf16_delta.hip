@@ -1,0 +1,4 @@
+// Streaming layer kernel, instantiations for bf16 operands with the second product.
+#include "zeno_layer_impl.h"
+
+ZENO_LAYER_INSTANCE(bf16_delta, true, true)

@@ -1,0 +1,841 @@
+// Streaming layer kernel of the Stochastic Descendant Score (Definition 2).
+//
+// For one linear layer l and every source s of the launch (candidate rows G[s],
+// s < m, and the current parameters x as source m) a workgroup owns BN = 32*NW
+// output features and streams the corresponding rows of that source's weight
+// block from HBM exactly once, K-chunk by K-chunk:
+//
+//   source m (pass at x):   Z0   = H0 W^T + b                 (pre-activations at x)
+//   source s < m:           dZ_s = -gamma ( H_s U_s^T + D_s W^T + ub_s )
+//
+// where H_s are candidate s's input activations, U_s / ub_s its weight / bias
+// block, and D_s = (H_s - H0) * (-1/gamma) the scaled change of the input
+// activations (absent at the first layer, where H_s = H0 = the batch).  dZ_s is
+// the change of the pre-activations caused by moving x to x - gamma u_s, so the
+// perturbed parameters are never formed and f_r(x) - f_r(x - gamma u) is later
+// obtained without subtracting two nearly equal losses.  ||u_s||^2 is
+// accumulated from the same registers that feed the matrix cores.
+//
+// Matrix-core mapping (wave64): each wave owns 32 output features (the rows of its
+// 32x32 accumulator blocks, i.e. the weight tile is the FIRST operand) and all
+// MB*32 sample rows (the columns = lanes), so that the results leave the
+// accumulators already in the order the next layer's operand is stored in.
+//  * U tile (32 features x 64 k, fp32 in HBM): fully coalesced 128-bit loads (4
+//    rows x 256 B per instruction, scalar base + per-lane offset), two chunks in
+//    flight per wave; converted and passed through a wave-private, XOR-swizzled
+//    LDS tile to reach the operand layout (lane = feature, 8 consecutive k).
+//  * Activation operands H_s, D_s: stored in global memory already in operand
+//    order ("tiled"), copied asynchronously global -> LDS (no registers) into a
+//    double buffer and shared by the waves of the workgroup: one barrier per chunk.
+//  * W operand of the second product: written in operand order by the pass at x,
+//    loaded straight into registers.
+#ifndef ZENO_LAYER_IMPL_H_
+#define ZENO_LAYER_IMPL_H_
+
+#include <type_traits>
+
+#include "zeno_internal.h"
+
+namespace zeno {
+
+namespace {
+
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+constexpr int kSrcChunk = 16;  // sources per scheduling unit (one feature tile each)
+
+template <bool BF16>
+struct Tr;
+template <>
+struct Tr<true> {
+  static constexpr int ESIZE = 2;
+  static constexpr int CH_BYTES = 32 * 64 * 2;  // one 32-row block of a 64-wide K chunk, tiled operand
+};
+template <>
+struct Tr<false> {
+  static constexpr int ESIZE = 4;
+  static constexpr int CH_BYTES = 32 * 64 * 4;
+};
+
+// Element index of (row r, column k) inside a tiled activation operand of padded
+// width Kp.  bf16: blocks of 32 rows x 16 k, lane = r%32 + 32*((k%16)/8), 8
+// consecutive k per lane (the operand layout of the 32x32x16 bf16 matrix
+// instruction).  fp32: blocks of 32 rows x 8 k, lane = r%32 + 32*((k%8)/4), the
+// four values of a lane feed four consecutive 32x32x2 fp32 instructions.
+template <bool BF16>
+__host__ __device__ inline long long tiled_index(int r, int k, int Kp) {
+  if (BF16) {
+    return ((((long long)(r >> 5) * (Kp >> 4) + (k >> 4)) * 64 + (r & 31) + 32 * ((k & 15) >> 3)) << 3) + (k & 7);
+  } else {
+    return ((((long long)(r >> 5) * (Kp >> 3) + (k >> 3)) * 64 + (r & 31) + 32 * ((k & 7) >> 2)) << 2) + (k & 3);
+  }
+}
+
+template <bool BF16>
+__device__ inline void store_tiled(void* base, int r, int k, int Kp, float v) {
+  const long long idx = tiled_index<BF16>(r, k, Kp);
+  if (BF16) {
+    reinterpret_cast<__bf16*>(base)[idx] = (__bf16)v;
+  } else {
+    reinterpret_cast<float*>(base)[idx] = v;
+  }
+}
+
+// Four consecutive columns k0..k0+3 (k0 a multiple of 4) of row r of a tiled
+// operand: they are adjacent in memory (8 bytes as bf16, 16 bytes as fp32).
+template <bool BF16>
+__device__ inline void store_tiled4(void* base, int r, int k0, int Kp, const f32x4& v) {
+  const long long idx = tiled_index<BF16>(r, k0, Kp);
+  // write-through stores (system-scope bit): the results are not kept as dirty lines
+  // in the L2, where the streaming weight loads would have to displace them.  The
+  // s_nop after the 128-bit store is required: the hardware still reads the data
+  // registers of a store wider than 64 bits for two more cycles, and the compiler,
+  // which adds these wait states to its own stores, does not look inside assembly.
+  if (BF16) {
+    bf16x4 t;
+    t[0] = (__bf16)v[0]; t[1] = (__bf16)v[1]; t[2] = (__bf16)v[2]; t[3] = (__bf16)v[3];
+    asm volatile("global_store_dwordx2 %0, %1, off sc1" ::"v"(reinterpret_cast<__bf16*>(base) + idx), "v"(t) : "memory");
+  } else {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(reinterpret_cast<float*>(base) + idx), "v"(v) : "memory");
+  }
+}
+
+// Output features a launch must cover: a hidden layer also writes the zero
+// padding of the next layer's tiled operand (width rounded up to 64).
+__host__ __device__ inline int cover_rows(int N, int last) { return last ? N : (N + 63) / 64 * 64; }
+
+// NaN-propagating ReLU (fmaxf would swallow a NaN coming from a faulty row).
+__device__ inline float relu_nan(float v) { return (v <= 0.0f) ? 0.0f : v; }
+
+__device__ inline f32x4 load4_masked(const float* __restrict__ row, int k, int K, bool row_ok) {
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (row_ok) {
+    if (k + 4 <= K) {
+      const f4u t = *reinterpret_cast<const f4u*>(row + k);
+      v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+      if (k < K) v[0] = row[k];
+      if (k + 1 < K) v[1] = row[k + 1];
+      if (k + 2 < K) v[2] = row[k + 2];
+    }
+  }
+  return v;
+}
+
+// Store v[0..3] to row[k..k+3], dropping the elements at or beyond K (4-byte aligned row).
+__device__ inline void store4_masked(float* __restrict__ row, int k, int K, const f32x4& v) {
+  if (k + 4 <= K) {
+    f4u t;
+    t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
+    *reinterpret_cast<f4u*>(row + k) = t;
+  } else {
+    if (k < K) row[k] = v[0];
+    if (k + 1 < K) row[k + 1] = v[1];
+    if (k + 2 < K) row[k + 2] = v[2];
+  }
+}
+
+// Load the wave's 32 x 64 weight tile: instruction j covers rows 4j..4j+3, 256
+// contiguous bytes each.  `tile` is the wave-uniform address of element (row0, k0);
+// `lane_off` = (lane/16)*K + 4*(lane%16) is the lane's element offset inside it.
+// MODE 1: the whole tile lies inside the matrix (no masking code is generated).
+// MODE 2: every K chunk is complete but some rows lie at or beyond N: they read row
+// N-1 instead (always in bounds) and the caller discards them, so that a ragged last
+// feature tile runs the same straight-line loop as a full one.
+// MODE 0: K is not a multiple of the chunk width (element-wise guards in the last chunk).
+// NT: streaming loads that do not keep the lines in the caches.  Only chosen when
+// every 256-byte row segment starts on a 128-byte line: a line that two load
+// instructions share would otherwise be fetched from memory twice.
+template <int MODE, bool NT>
+__device__ inline void load_tile(f32x4 (&u)[8], const float* __restrict__ tile, unsigned lane_off, int row0, int k0,
+                                 int N, int K, int lane) {
+  if (MODE != 0) {
+    if (MODE == 1) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (NT) {
+          u[j] = load_stream4(tile + (long long)(4 * j) * K + lane_off);
+        } else {
+          u[j] = *reinterpret_cast<const f32x4_a4*>(tile + (long long)(4 * j) * K + lane_off);
+        }
+      }
+    } else {
+      const int rsub = lane >> 4, kq = (lane & 15) << 2;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = row0 + 4 * j + rsub;
+        const int rel = (row < N ? row : N - 1) - row0;   // may be negative: the tile starts beyond the matrix
+        const float* p = tile + (long long)rel * K + kq;
+        if (NT) {
+          u[j] = load_stream4(p);
+        } else {
+          u[j] = *reinterpret_cast<const f32x4_a4*>(p);
+        }
+      }
+    }
+  } else {
+    // Ragged tile.  Rows beyond the matrix read row N-1 instead (always in bounds)
+    // and are zeroed afterwards; only the last K chunk of a width that is not a
+    // multiple of 64 takes the element-wise path.
+    const int rsub = lane >> 4, kq = (lane & 15) << 2;
+    const bool k_full = k0 + 64 <= K;  // wave-uniform
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int row = row0 + 4 * j + rsub;
+      const int back = row < N ? 0 : row - (N - 1);
+      const float* p = tile + (long long)(4 * j + rsub - back) * K;
+      f32x4 v;
+      if (k_full) {
+        v = *reinterpret_cast<const f32x4_a4*>(p + kq);
+      } else {
+        v = load4_masked(p, kq, K - k0, true);
+      }
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      u[j] = row < N ? v : zero;
+    }
+  }
+}
+
+// Wave-private staging tile, unpadded and XOR-swizzled on 16-byte segments so that
+// both the row-wise writes and the operand reads (lane = row) are conflict-free.
+template <bool BF16>
+__device__ inline void stage_tile(const f32x4 (&u)[8], unsigned char* st, int lane) {
+  const int rsub = lane >> 4, kq = lane & 15;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int r = 4 * j + rsub;
+    if (BF16) {
+      const bf16x4 h = __builtin_convertvector(u[j], bf16x4);
+      *reinterpret_cast<bf16x4*>(st + r * 128 + ((((kq >> 1) ^ (r >> 1)) & 7) << 4) + ((kq & 1) << 3)) = h;
+    } else {
+      *reinterpret_cast<f32x4*>(st + r * 256 + (((kq ^ r) & 15) << 4)) = u[j];
+    }
+  }
+}
+
+// s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding: vmcnt in
+// bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+template <int N>
+__device__ inline void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Asynchronous 16-byte-per-lane copy from global memory straight into LDS: lane i's
+// 16 bytes at `src` (a per-lane address) land at dst + 16 i, dst wave-uniform.  The
+// instruction is issued through inline assembly on purpose.  The compiler's own
+// wait-count bookkeeping treats such a copy as a possible writer of every LDS
+// address and then drains ALL outstanding loads (vmcnt(0)) before the next LDS
+// read, which would also drain the weight tiles that are meant to stay in flight
+// across chunks.  Issued this way the copy is invisible to that bookkeeping; the
+// kernel waits for it explicitly (wait_vmcnt, loads complete in order) before the
+// workgroup barrier that publishes the buffer.  Hidden loads only make the
+// compiler's own counts for its ordinary loads stricter than needed, never laxer.
+// m0 (the LDS base of the copy) is written inside the statement and is not on the
+// clobber list: the compiler reserves it and uses it for nothing else in this file.
+__device__ inline void lds_dma16(const unsigned char* src, unsigned char* dst) {
+  const unsigned lds_off = (unsigned)(uintptr_t)(lptr_t)dst;  // byte offset inside the workgroup's LDS
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(src), "s"(lds_off)
+               : "memory");
+}
+
+// LDS layout of a workgroup: [activation chunk buffers (one or two)] [one staging
+// tile per wave] [32 bias values per wave].
+template <bool BF16, bool DELTA, int MB, int NW>
+struct Lds {
+  using T = Tr<BF16>;
+  static constexpr int A_BYTES = MB * T::CH_BYTES;            // one operand, one chunk
+  static constexpr int AD_BYTES = A_BYTES * (DELTA ? 2 : 1);  // H (and D), one chunk
+  static constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
+  static constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
+  static constexpr int STAGE_OFF = AD_BYTES * (DBUF ? 2 : 1);
+  static constexpr int BIAS_OFF = STAGE_OFF + NW * STAGE_BYTES;
+  static constexpr int TOTAL = BIAS_OFF + NW * 32 * 4;
+};
+
+// KS > 1 (pass at x on its own, NW == 1): the KS waves of a workgroup own the SAME 32
+// features and split the K range between them, each with a private copy of the LDS
+// layout and no barrier inside the loop; the partial accumulators are summed through
+// LDS in a fixed tree order at the end and wave 0 writes the results.  A launch of
+// the pass at x has only N/32 feature tiles, far too few single waves to keep enough
+// loads in flight, and this multiplies them by KS.
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS>
+__global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) {
+  static_assert(KS == 1 || NW == 1, "K is only split in one-tile workgroups");
+  using T = Tr<BF16>;
+  using LD = Lds<BF16, DELTA, MB, NW>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
+  constexpr int BN = 32 * NW;
+  constexpr int A_BYTES = LD::A_BYTES;
+  constexpr int AD_BYTES = LD::AD_BYTES;
+  constexpr int AD_KB = AD_BYTES / 1024;               // 1 KB async copies per chunk
+  constexpr int A_KB = A_BYTES / 1024;
+  constexpr int BLOCK_KB = T::CH_BYTES / 1024;
+  constexpr int STAGE_BYTES = LD::STAGE_BYTES;
+  constexpr bool DBUF = LD::DBUF;
+  constexpr int COPIES = (AD_KB + NW - 1) / NW;        // async copies issued per wave per chunk
+  constexpr int WREGS = BF16 ? 4 : 8;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = KS > 1 ? 0 : wave_id;   // feature sub-tile of this wave inside the workgroup's tile
+  const int kw = KS > 1 ? wave_id : 0;     // which part of K this wave sums
+  unsigned char* lds = lds_all + kw * LD::TOTAL;
+  unsigned char* stU = lds + LD::STAGE_OFF + wave * STAGE_BYTES;
+  float* biasL = reinterpret_cast<float*>(lds + LD::BIAS_OFF) + wave * 32;
+
+  // Which job: the leading base_blocks block indices run the pass at x (one
+  // feature tile each), the rest the candidates.
+  // Candidates: workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8), each
+  // with its own L2.  The work is cut into units of one feature tile x a chunk of up
+  // to kSrcChunk candidates; units go round-robin to the XCDs and the workgroups of
+  // a unit occupy consecutive slots of their XCD.  The workgroups that run together
+  // on an XCD therefore stream the SAME rows of W (second product) at about the
+  // same time and share them through that L2, while everything that is private to
+  // a candidate (its activations) is reused inside the workgroup through LDS.
+  const bool is_base = (int)blockIdx.x < a.base_blocks;
+  const LayerJob& J = is_base ? a.bj : a.cj;
+  const int N = J.N, K = J.K, last = J.last, Np = J.Np;
+  const int n_chunks = J.Kp >> 6;
+  const int n_tiles = (cover_rows(N, last) + BN - 1) / BN;
+  int nt, s = 0;
+  if (is_base) {
+    nt = blockIdx.x;
+    if (nt >= n_tiles) return;
+  } else {
+    const int bid = blockIdx.x - a.base_blocks;
+    const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
+    const int n_cchunks = (a.n_cand + cc - 1) / cc;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int unit = (slot / cc) * 8 + xcd;
+    if (unit >= n_tiles * n_cchunks) return;
+    nt = unit / n_cchunks;
+    s = (unit % n_cchunks) * cc + slot % cc;
+    if (s >= a.n_cand) return;
+  }
+  const float* __restrict__ P = is_base ? a.x : a.G + (long long)s * a.ldg;
+  const int row0 = nt * BN + wave * 32;
+  const float* __restrict__ Urow0 = P + J.w_off + (long long)row0 * K;  // wave-uniform
+  const unsigned lane_off = (unsigned)(lane >> 4) * (unsigned)K + ((lane & 15) << 2);
+  const bool full_rows = row0 + 32 <= N;
+
+  const unsigned char* Ag = reinterpret_cast<const unsigned char*>(J.A_base);
+  if (!is_base && a.A_cand != nullptr) Ag = reinterpret_cast<const unsigned char*>(a.A_cand) + (long long)s * a.A_stride;
+  // The pass at x has no second product: its D operand is a harmless alias of H
+  // and its products are skipped.
+  const bool has_delta = DELTA && !is_base;
+  const unsigned char* Dg = has_delta ? reinterpret_cast<const unsigned char*>(a.D_cand) + (long long)s * a.A_stride : Ag;
+
+  const bool pack = is_base && J.Wt != nullptr;
+  unsigned char* Wt_wave = reinterpret_cast<unsigned char*>(J.Wt) +
+                           ((long long)(row0 >> 5) * n_chunks * WREGS * 64 + lane) * 16;
+  // The main loop exists in six versions chosen per wave: full tile / full K with some
+  // rows beyond the matrix (both: straight-line loads, and the in-order completion of
+  // loads lets a chunk wait for exactly its own activation copies) / ragged in K, and BASE (pass at x: no second product, writes W in operand order) or
+  // candidate.
+  const bool all_full = (K & 63) == 0;
+  const int c_begin = KS > 1 ? n_chunks * kw / KS : 0;
+  const int c_end = KS > 1 ? n_chunks * (kw + 1) / KS : n_chunks;
+
+  f32x16 acc[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[mb][j] = 0.f;
+
+#ifdef ZENO_TIMING_EXPERIMENTS
+  // Timing experiments only (results are wrong): bit 0 skips the matrix products
+  // and their LDS reads, bit 1 the activation copies, bit 2 the staging writes,
+  // bit 3 the epilogue, bit 4 the norm.
+  const int dbg = a.dbg;
+#else
+  constexpr int dbg = 0;
+#endif
+  const bool do_norm = (a.norm_partials != nullptr) && !is_base && !(dbg & 16);
+  double nrm = 0.0;
+
+  f32x4 u0[8], u1[8];
+  f32x4 w0[WREGS], w1[WREGS];
+
+  // Asynchronous copy of chunk c of the tiled activation operands into LDS buffer
+  // `buf`: AD_KB pieces of 1 KB (64 lanes x 16 B land at consecutive LDS addresses),
+  // dealt round-robin to the waves.
+  auto copy_AD = [&](int c, int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < COPIES; ++i) {
+      const int q = wave + i * NW;
+      if (AD_KB % NW == 0 || q < AD_KB) {
+        const int op = q / A_KB, piece = q % A_KB;
+        const int mb = piece / BLOCK_KB, within = piece % BLOCK_KB;
+        const unsigned char* src = (op ? Dg : Ag) + ((long long)mb * n_chunks + c) * T::CH_BYTES + within * 1024 + lane * 16;
+        unsigned char* dst = lds + buf * AD_BYTES + q * 1024;
+        lds_dma16(src, dst);
+      }
+    }
+  };
+  auto load_W = [&](f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
+#pragma unroll
+    for (int r = 0; r < WREGS; ++r)
+      w[r] = *reinterpret_cast<const f32x4*>(Wt_wave + ((long long)c * WREGS + r) * 1024);
+  };
+
+  // One K chunk.  Its weight tile sits in registers u (loaded two chunks ago); its
+  // activation operands were copied into LDS buffer c&1 during the previous chunk.
+  // Issue order per chunk: copies(c+1), U(c+2), [matrix products of c], W(c+2).
+  // STEADY: the caller guarantees c + 2 < n_chunks, so every load of the chunk is
+  // unconditional.  That matters for more than the saved branches: the compiler
+  // derives its wait counts from the worst path through the loop, and a path on
+  // which the later tile was NOT requested makes it wait for all loads at the top
+  // of every chunk, i.e. no tile would stay in flight across a chunk.
+  auto chunk = [&](auto full_c, auto base_c, auto steady_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c)
+                   __attribute__((always_inline)) {
+    constexpr int MODE = decltype(full_c)::value;
+    constexpr bool FULL = MODE != 0;
+    constexpr bool BASE = decltype(base_c)::value;   // this workgroup runs the pass at x
+    constexpr bool STEADY = decltype(steady_c)::value;
+    constexpr bool SECOND = DELTA && !BASE;           // second product D W^T present
+    const int buf = DBUF ? (c & 1) : 0;
+    if (MODE == 2) {
+      // rows beyond the matrix were read from row N-1: discard them
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) u[j] = (row0 + 4 * j + (lane >> 4) < N) ? u[j] : zero;
+    }
+    if (do_norm) {
+      float q = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) q += (u[j][0] * u[j][0] + u[j][1] * u[j][1]) + (u[j][2] * u[j][2] + u[j][3] * u[j][3]);
+      nrm += (double)q;
+    }
+    if (!(dbg & 4)) stage_tile<BF16>(u, stU, lane);
+    if (DBUF) {
+      // copies(c) were issued before U(c+1) [8 loads] and W(c+1) [WREGS loads]; the
+      // last chunk has no such loads behind its copies and waits for everything
+      // (the stores of the pass at x, which writes W in operand order, share the counter;
+      // they can only make this wait longer, never let it pass early)
+      if (FULL && (STEADY || c + 1 < c_end)) {
+        wait_vmcnt<8 + (SECOND ? WREGS : 0)>();
+      } else {
+        wait_vmcnt<0>();
+      }
+      if (KS == 1) {
+        __syncthreads();  // copies of every wave have landed; everyone is done with buffer buf^1
+      } else {
+        asm volatile("" ::: "memory");  // private buffers: only the compiler must not move LDS reads above the wait
+      }
+      if ((STEADY || c + 1 < c_end) && !(dbg & 2)) copy_AD(c + 1, buf ^ 1);
+      __builtin_amdgcn_sched_barrier(0);  // the wait above counts on the copies being issued before the next loads
+    } else {
+      __syncthreads();  // single buffer: everyone is done with the previous chunk
+      copy_AD(c, 0);
+      wait_vmcnt<0>();
+      __syncthreads();
+    }
+    if (STEADY || c + 2 < c_end) load_tile<MODE, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
+
+    // Matrix products of this chunk in groups of MB products that share one B
+    // operand (k-step t, operand H or D).  The scheduler is fenced so that the LDS
+    // reads of group g+1 are issued right behind the products of group g.
+    const unsigned char* bufA = lds + buf * AD_BYTES;
+    const unsigned char* bufD = bufA + A_BYTES;
+    const int n = lane & 31, h = lane >> 5;
+    constexpr int OPS = DELTA ? 2 : 1;
+    constexpr int KSTEPS = BF16 ? 4 : 8;   // operand k-steps per chunk (16 k / 8 k each)
+    constexpr int NG = KSTEPS * OPS;
+    auto read_group = [&](f32x4 (&fr)[MB], int g) __attribute__((always_inline)) {
+      const int t = g / OPS, op = g % OPS;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+        fr[mb] = *reinterpret_cast<const f32x4*>((op ? bufD : bufA) + ((mb * KSTEPS + t) * 64 + lane) * 16);
+    };
+    auto read_b = [&](int t) __attribute__((always_inline)) {
+      if (BF16) return *reinterpret_cast<const f32x4*>(stU + n * 128 + ((((2 * t + h) ^ (n >> 1)) & 7) << 4));
+      return *reinterpret_cast<const f32x4*>(stU + n * 256 + ((((2 * t + h) ^ n) & 15) << 4));
+    };
+    f32x4 fr[NG][MB];
+    f32x4 bq[KSTEPS];
+    if (dbg & 1) return;
+    bq[0] = read_b(0);
+    read_group(fr[0], 0);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const int t = g / OPS, op = g % OPS;
+      __builtin_amdgcn_sched_barrier(0);
+      const f32x4 bv = op ? w[t] : bq[t];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        if (op == 1 && !SECOND) break;  // the pass at x has no second product
+        if (BF16) {
+          acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bv),
+                                                            __builtin_bit_cast(bf16x8, fr[g][mb]), acc[mb], 0, 0, 0);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[e], fr[g][mb][e], acc[mb], 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // the reads of the next group are issued behind this group's products and
+      // complete while the matrix pipeline works through them
+      if (g + 1 < NG) {
+        read_group(fr[g + 1], g + 1);
+        if ((g + 1) % OPS == 0) bq[(g + 1) / OPS] = read_b((g + 1) / OPS);
+      }
+      if (BASE && pack && op == 0) *reinterpret_cast<f32x4*>(Wt_wave + ((long long)c * WREGS + t) * 1024) = bq[t];
+    }
+    if (SECOND && (STEADY || c + 2 < c_end)) load_W(w, c + 2);
+  };
+
+  auto run = [&](auto full_c, auto base_c) __attribute__((always_inline)) {
+    constexpr int MODE = decltype(full_c)::value;
+    constexpr bool FULL = MODE != 0;
+    constexpr bool SECOND = DELTA && !decltype(base_c)::value;
+    // The wave's 32 bias values are requested first of all and parked in LDS, so
+    // that the epilogue does not start with a round trip to memory.
+    float bias_lane = 0.f;
+    if (J.b_off >= 0 && lane < 32 && row0 + lane < N) bias_lane = P[J.b_off + row0 + lane];
+    __builtin_amdgcn_sched_barrier(0);
+    if (DBUF) copy_AD(c_begin, c_begin & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    int c = c_begin;
+    const float* Ufirst = Urow0 + (c_begin << 6);
+    if (FULL && DBUF && c_end - c_begin >= 4) {
+      // steady state: pairs of chunks whose loads (two chunks ahead) all exist
+      load_tile<MODE, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
+      load_tile<MODE, NT>(u1, Ufirst + 64, lane_off, row0, (c_begin + 1) << 6, N, K, lane);
+      if (SECOND) {
+        load_W(w0, c_begin);
+        load_W(w1, c_begin + 1);
+      }
+      if (lane < 32) biasL[lane] = bias_lane;
+      for (; c + 3 < c_end; c += 2) {
+        chunk(full_c, base_c, std::true_type{}, u0, w0, c);
+        chunk(full_c, base_c, std::true_type{}, u1, w1, c + 1);
+      }
+    } else {
+      if (c_begin < c_end) load_tile<MODE, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
+      if (c_begin + 1 < c_end) load_tile<MODE, NT>(u1, Ufirst + 64, lane_off, row0, (c_begin + 1) << 6, N, K, lane);
+      if (SECOND) {
+        load_W(w0, c_begin);
+        if (c_begin + 1 < c_end) load_W(w1, c_begin + 1);
+      }
+      if (lane < 32) biasL[lane] = bias_lane;
+    }
+    // the last two or three chunks (all of them for a short K): every load is conditional
+    for (; c < c_end; c += 2) {
+      chunk(full_c, base_c, std::false_type{}, u0, w0, c);
+      if (c + 1 < c_end) chunk(full_c, base_c, std::false_type{}, u1, w1, c + 1);
+    }
+    if (KS > 1) wait_vmcnt<0>();  // a wave with an empty K range still has its first copy in flight
+  };
+  using M0 = std::integral_constant<int, 0>;
+  using M1 = std::integral_constant<int, 1>;
+  using M2 = std::integral_constant<int, 2>;
+  if (is_base) {
+    if (all_full && full_rows) run(M1{}, std::true_type{});
+    else if (all_full) run(M2{}, std::true_type{});
+    else run(M0{}, std::true_type{});
+  } else {
+    if (all_full && full_rows) run(M1{}, std::false_type{});
+    else if (all_full) run(M2{}, std::false_type{});
+    else run(M0{}, std::false_type{});
+  }
+
+  if (KS > 1) {
+    // sum the KS partial accumulators in a fixed tree: (0+2)+(1+3) for KS = 4
+    float* red = reinterpret_cast<float*>(lds_all);
+    for (int step = KS / 2; step >= 1; step >>= 1) {
+      __syncthreads();  // all waves are out of their loops / done reading the previous round
+      if (kw >= step && kw < 2 * step) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) red[(((kw - step) * MB + mb) * 16 + j) * 64 + lane] = acc[mb][j];
+      }
+      __syncthreads();
+      if (kw < step) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) acc[mb][j] += red[((kw * MB + mb) * 16 + j) * 64 + lane];
+      }
+    }
+    if (kw != 0) return;
+  }
+
+  // ---- epilogue.  The weight tile is the first operand of the products, so the
+  // accumulators hold features along the registers and samples along the lanes:
+  // element j of block mb in lane (n, h) is sample row 32 mb + n and output feature
+  // row0 + 8 (j/4) + 4 h + j%4.  Four consecutive features of one sample are
+  // adjacent in the tiled operand of the next layer, so a lane stores them as one
+  // piece and a wave's store instruction covers one contiguous 512 B / 1 KB run.
+  if (dbg & 8) {
+    if (acc[0][0] == 12345.f) a.dZ[0] = 1.f;
+    return;
+  }
+  const int n = lane & 31, h = lane >> 5;
+  f32x4 bias[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    bias[q] = *reinterpret_cast<const f32x4*>(biasL + 8 * q + 4 * h);   // written by this wave before the main loop
+    // every feature of the tile sits in exactly one of the two lanes with n == 0
+    if (do_norm && n == 0)
+      nrm += (double)((bias[q][0] * bias[q][0] + bias[q][1] * bias[q][1]) + (bias[q][2] * bias[q][2] + bias[q][3] * bias[q][3]));
+  }
+
+  if (full_rows) {
+    // All 32 features of the wave exist: no per-element guards.  Rows beyond the
+    // batch read row n_r-1 instead (in bounds) and are masked afterwards, so every
+    // load is unconditional and all of them are in flight together.
+    const bool hidden_cand = !is_base && !last;
+    f32x4 z0v[MB][4];
+    if (hidden_cand) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int r = 32 * mb + n;
+        const int rc = r < a.n_r ? r : a.n_r - 1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          z0v[mb][q] = *reinterpret_cast<const f32x4_a4*>(J.Z0 + (long long)rc * N + row0 + 8 * q + 4 * h);
+      }
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int r = 32 * mb + n;
+      const bool row_ok = r < a.n_r;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int f0 = row0 + 8 * q + 4 * h;
+        f32x4 val;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) val[i] = acc[mb][4 * q + i] + bias[q][i];
+        if (is_base) {
+          if (row_ok) *reinterpret_cast<f32x4_a4*>(J.Z0 + (long long)r * N + f0) = val;
+          if (!last) {
+            f32x4 hv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hv[i] = row_ok ? relu_nan(val[i]) : 0.f;
+            store_tiled4<BF16>(J.H_base, r, f0, Np, hv);
+          }
+        } else {
+          f32x4 dz;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dz[i] = -a.gamma * val[i];
+          if (last) {
+            if (row_ok) *reinterpret_cast<f32x4_a4*>(a.dZ + ((long long)s * a.n_r + r) * N + f0) = dz;
+          } else {
+            f32x4 hv, dv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float z0 = z0v[mb][q][i];
+              const float hr = relu_nan(z0 + dz[i]);
+              // relu(z0 + dz) - relu(z0) without cancellation
+              const float dd = (z0 > 0.f) ? ((dz[i] < -z0) ? -z0 : dz[i]) : hr;
+              hv[i] = row_ok ? hr : 0.f;
+              dv[i] = row_ok ? dd * a.neg_inv_gamma : 0.f;
+            }
+            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.H_cand) + (long long)s * a.H_stride, r, f0, Np, hv);
+            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.Dl_cand) + (long long)s * a.H_stride, r, f0, Np, dv);
+          }
+        }
+      }
+    }
+  } else {
+    // ragged tile: per-element guards
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int r = 32 * mb + n;
+      const bool row_ok = r < a.n_r;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int f0 = row0 + 8 * q + 4 * h;
+        f32x4 val;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) val[i] = acc[mb][4 * q + i] + bias[q][i];
+        if (is_base) {
+          if (row_ok) store4_masked(J.Z0 + (long long)r * N, f0, N, val);
+          if (!last && f0 < Np) {
+            f32x4 hv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hv[i] = (row_ok && f0 + i < N) ? relu_nan(val[i]) : 0.f;
+            store_tiled4<BF16>(J.H_base, r, f0, Np, hv);
+          }
+        } else {
+          f32x4 dz;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dz[i] = -a.gamma * val[i];
+          if (last) {
+            if (row_ok) store4_masked(a.dZ + ((long long)s * a.n_r + r) * N, f0, N, dz);
+          } else if (f0 < Np) {
+            const f32x4 z0 = load4_masked(J.Z0 + (long long)r * N, f0, N, row_ok);
+            f32x4 hv, dv;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const bool ok = row_ok && f0 + i < N;
+              const float hr = relu_nan(z0[i] + dz[i]);
+              // relu(z0 + dz) - relu(z0) without cancellation
+              const float dd = (z0[i] > 0.f) ? ((dz[i] < -z0[i]) ? -z0[i] : dz[i]) : hr;
+              hv[i] = ok ? hr : 0.f;
+              dv[i] = ok ? dd * a.neg_inv_gamma : 0.f;
+            }
+            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.H_cand) + (long long)s * a.H_stride, r, f0, Np, hv);
+            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.Dl_cand) + (long long)s * a.H_stride, r, f0, Np, dv);
+          }
+        }
+      }
+    }
+  }
+
+  if (do_norm) {
+    // fixed-order reduction: lanes by xor-shuffle tree, then waves in order
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
+    __syncthreads();
+    double* red = reinterpret_cast<double*>(lds);
+    if (lane == 0) red[wave] = nrm;
+    __syncthreads();
+    if (tid == 0) {
+      double t = 0.0;
+      for (int wv = 0; wv < NW; ++wv) t += red[wv];
+      a.norm_partials[(long long)s * a.P + a.p_off + nt] = t;
+    }
+  }
+}
+
+template <bool BF16>
+__global__ void pack_features_kernel(const float* __restrict__ features, int n_r, int K, int Kp, int n_pad,
+                                     void* __restrict__ tiled) {
+  const long long total = (long long)n_pad * Kp;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int r = (int)(i / Kp), k = (int)(i % Kp);
+    const float v = (r < n_r && k < K) ? features[(long long)r * K + k] : 0.f;
+    store_tiled<BF16>(tiled, r, k, Kp, v);
+  }
+}
+
+int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
+
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1>
+hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
+  constexpr int BN = 32 * NW;
+  constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL * KS;
+  static bool attr_set = false;
+  if (!attr_set && lds_bytes > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT, KS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) + 7) / 8 * 8 : 0;
+  int cand_blocks = 0;
+  if (a.n_cand > 0) {
+    const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
+    const int units = job_tiles(a.cj, BN) * ((a.n_cand + cc - 1) / cc);
+    cand_blocks = ((units + 7) / 8) * 8 * cc;
+  }
+  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW, NT, KS>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW * KS),
+                     lds_bytes, stream, a);
+  return hipGetLastError();
+}
+
+// Workgroups of this instantiation that fit on one compute unit (cached).
+template <bool BF16, bool DELTA, int MB, int NW>
+int wgs_per_cu_inst() {
+  static int cached = 0;
+  if (cached == 0) {
+    constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, false, 1>),
+                                                     64 * NW, lds_bytes) != hipSuccess || n < 1)
+      n = 1;
+    cached = n;
+  }
+  return cached;
+}
+
+template <bool BF16, bool DELTA, int MB>
+int wgs_per_cu_nw(int NW) {
+  if (NW == 8) return wgs_per_cu_inst<BF16, DELTA, MB, 8>();
+  if (NW == 4) return wgs_per_cu_inst<BF16, DELTA, MB, 4>();
+  return wgs_per_cu_inst<BF16, DELTA, MB, 1>();
+}
+
+template <bool BF16, bool DELTA>
+int wgs_per_cu_mb(int MB, int NW) {
+  if (MB == 1) return wgs_per_cu_nw<BF16, DELTA, 1>(NW);
+  if (MB == 2) return wgs_per_cu_nw<BF16, DELTA, 2>(NW);
+  return wgs_per_cu_nw<BF16, DELTA, 4>(NW);
+}
+
+// Streaming loads are used when every row segment a load instruction covers
+// starts on a 128-byte line: base pointers, row pitch, block offset and row
+// length of every job in the launch are multiples of 128 bytes.
+bool job_lines_aligned(const LayerJob& j) { return j.w_off % 32 == 0 && j.K % 32 == 0; }
+bool launch_lines_aligned(const LayerArgs& a) {
+  bool ok = true;
+  if (a.n_cand > 0) ok = ok && reinterpret_cast<uintptr_t>(a.G) % 128 == 0 && a.ldg % 32 == 0 && job_lines_aligned(a.cj);
+  if (a.has_base) ok = ok && reinterpret_cast<uintptr_t>(a.x) % 128 == 0 && job_lines_aligned(a.bj);
+  return ok;
+}
+
+constexpr int kSplitK = 4;  // waves that share one feature tile of a lone pass at x
+
+template <bool BF16, bool DELTA, int MB, int NW>
+hipError_t launch_nt(const LayerArgs& a, hipStream_t stream) {
+  // A pass at x on its own, one-tile workgroups, a K long enough to split, and LDS for kSplitK private layouts
+  if constexpr (NW == 1 && !DELTA && Lds<BF16, DELTA, MB, 1>::TOTAL * kSplitK <= 160 * 1024) {
+    if (a.n_cand == 0 && a.has_base && (a.bj.Kp >> 6) >= 2 * kSplitK) {
+      if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, kSplitK>(a, stream);
+      return launch_inst<BF16, DELTA, MB, NW, false, kSplitK>(a, stream);
+    }
+  }
+  if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream);
+  return launch_inst<BF16, DELTA, MB, NW, false>(a, stream);
+}
+
+template <bool BF16, bool DELTA, int MB>
+hipError_t launch_nw(const LayerArgs& a, int NW, hipStream_t stream) {
+  if (NW == 8) return launch_nt<BF16, DELTA, MB, 8>(a, stream);
+  if (NW == 4) return launch_nt<BF16, DELTA, MB, 4>(a, stream);
+  return launch_nt<BF16, DELTA, MB, 1>(a, stream);
+}
+
+template <bool BF16, bool DELTA>
+hipError_t launch_mb(const LayerArgs& a, int MB, int NW, hipStream_t stream) {
+  if (MB == 1) return launch_nw<BF16, DELTA, 1>(a, NW, stream);
+  if (MB == 2) return launch_nw<BF16, DELTA, 2>(a, NW, stream);
+  return launch_nw<BF16, DELTA, 4>(a, NW, stream);
+}
+
+// Waves per workgroup (32 output features each): the widest workgroup that still
+// gives every compute unit work, since a wider workgroup re-reads less of the
+// activations per byte of weights; narrow layers fall back to one wave to spread
+// over more compute units.
+int pick_nw(int rows, int n_src) {
+  if ((long long)((rows + 255) / 256) * n_src >= 256) return 8;
+  if ((long long)((rows + 127) / 128) * n_src >= 256) return 4;
+  return 1;
+}
+
+// Waves per workgroup of a launch, from the job that dominates it.
+int launch_nw_for(const LayerArgs& a) {
+  if (a.n_cand > 0) return pick_nw(cover_rows(a.cj.N, a.cj.last), a.n_cand);
+  return pick_nw(cover_rows(a.bj.N, a.bj.last), 1);
+}
+
+}  // namespace
+
+}  // namespace zeno
+
+// The kernel is compiled in four translation units, one per (operand type, second
+// product) pair, so that the instantiations build in parallel; each defines the two
+// entry points the dispatcher in zeno_layer.hip calls.
+#define ZENO_LAYER_INSTANCE(NAME, BF16, DELTA)                                                    \
+  namespace zeno {                                                                                \
+  hipError_t launch_layer_##NAME(const LayerArgs& a, int MB, int NW, hipStream_t stream) {        \
+    return launch_mb<BF16, DELTA>(a, MB, NW, stream);                                             \
+  }                                                                                               \
+  int wgs_per_cu_##NAME(int MB, int NW) { return wgs_per_cu_mb<BF16, DELTA>(MB, NW); }            \
+  }
+
+#endif  // ZENO_LAYER_IMPL_H_
