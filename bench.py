@@ -36,6 +36,8 @@ def parse_args():
     ap.add_argument("--row-align", type=int, default=32,
                     help="alignment of the rows of G in floats (32 = 128-byte lines, the layout the library "
                          "recommends; 1 = densely packed rows)")
+    ap.add_argument("--n-r", type=int, default=0,
+                    help="override the size of the server's batch (0 = the workload's own; the paper's runs use 4)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU oracle sample")
     return ap.parse_args()
 
@@ -105,7 +107,7 @@ def main():
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
 
-    w = WL.make_config(a.config, device=dev, row_align=a.row_align)
+    w = WL.make_config(a.config, device=dev, row_align=a.row_align, n_r=a.n_r or None)
     m, d, b = w.m, w.d, w.b
     g_bytes = 4 * m * d
     if a.buffers > 0:

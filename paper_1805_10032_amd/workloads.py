@@ -198,25 +198,36 @@ def make_least_squares(name="cfg1", cfg=1, d=64, n_r=16, m=8, b=2, q=2, gamma=0.
                     x, G, A, None, y, faulty)
 
 
-def make_config(cfg: int, *, seed=0, device="cpu", row_align=1) -> Workload:
-    """The five numbered workloads (1 = smallest ... 5 = 14 GB of candidates)."""
+def make_config(cfg: int, *, seed=0, device="cpu", row_align=1, n_r=None) -> Workload:
+    """The five numbered workloads (1 = smallest ... 5 = 14 GB of candidates).  n_r
+    overrides the size of the server's batch (the paper's own runs use n_r = 4,
+    Section 6.1; the workers' batches keep the workload's size)."""
+    if n_r is not None and cfg >= 2:
+        base = {2: 32, 3: 32, 4: 64, 5: 128}[cfg]
+        w = _make_config(cfg, seed=seed, device=device, row_align=row_align, n_r=int(n_r), worker_batch=base)
+        return w
+    return _make_config(cfg, seed=seed, device=device, row_align=row_align)
+
+
+def _make_config(cfg, *, seed, device, row_align, n_r=None, worker_batch=None):
     if cfg == 1:
         return make_least_squares(seed=seed, device=device, row_align=row_align)
     if cfg == 2:
-        return make_mlp_workload("cfg2", 2, [784, 10], 20, 8, 32, 0.1, 5e-4, "fp32",
+        return make_mlp_workload("cfg2", 2, [784, 10], 20, 8, n_r or 32, 0.1, 5e-4, "fp32",
                                  seed=seed, device=device, n_noise=8, noise_std=200.0,
                                  feat="uniform", init="small", worker_batch=32, row_align=row_align)
     if cfg == 3:
-        return make_mlp_workload("cfg3", 3, [3072, 512, 10], 20, 8, 32, 0.05, 1e-3, "fp32",
-                                 seed=seed, device=device, n_flip=8, flip_scale=-4.0, row_align=row_align)
+        return make_mlp_workload("cfg3", 3, [3072, 512, 10], 20, 8, n_r or 32, 0.05, 1e-3, "fp32",
+                                 seed=seed, device=device, n_flip=8, flip_scale=-4.0, row_align=row_align,
+                                 worker_batch=worker_batch)
     if cfg == 4:
-        return make_mlp_workload("cfg4", 4, [3072, 2048, 2048, 2048, 10], 100, 40, 64, 0.05, 1e-3,
+        return make_mlp_workload("cfg4", 4, [3072, 2048, 2048, 2048, 10], 100, 40, n_r or 64, 0.05, 1e-3,
                                  "bf16", seed=seed, device=device, n_flip=20, flip_scale=-4.0,
-                                 n_noise=20, noise_std=100.0, row_align=row_align)
+                                 n_noise=20, noise_std=100.0, row_align=row_align, worker_batch=worker_batch)
     if cfg == 5:
-        return make_mlp_workload("cfg5", 5, [4096, 4096, 4096, 4096, 1000], 64, 16, 128, 0.02, 1e-4,
+        return make_mlp_workload("cfg5", 5, [4096, 4096, 4096, 4096, 1000], 64, 16, n_r or 128, 0.02, 1e-4,
                                  "bf16", seed=seed, device=device, n_flip=16, flip_scale=-10.0,
-                                 row_align=row_align)
+                                 row_align=row_align, worker_batch=worker_batch)
     raise ValueError(f"no such config: {cfg}")
 
 

@@ -19,7 +19,7 @@ def B():
     return binding
 
 
-def _check_step(B, w, tol=None, row_align=1):
+def _check_step(B, w, tol=None, row_align=1, exact_bound=5e-2):
     tol = SCORE_TOL[w.fwd] if tol is None else tol
     s_gpu = gpu_scores(B, w, row_align=row_align)
     s_ref, scale = oracle_terms(w)
@@ -30,7 +30,7 @@ def _check_step(B, w, tol=None, row_align=1):
         s_exact, _ = exact_terms(w)
         err_exact = score_error(npy(s_gpu), s_exact, scale)
         print(f"{w.name}: bf16 path vs contract {err.max():.2e}, vs float64 definition {err_exact.max():.2e}")
-        assert np.all(err_exact <= 5e-2), (w.name, err_exact.max())
+        assert exact_bound is None or np.all(err_exact <= exact_bound), (w.name, err_exact.max())
     out, sel = B.zeno_aggregate(rows_to_gpu(B, w.G, row_align), s_gpu, w.b)
     torch.cuda.synchronize()
     finite = np.isfinite(scale)
@@ -109,6 +109,28 @@ def test_long_k_layers(B, fwd, n_r, dims):
     kernels through 128-bit stores."""
     w = WL.make_mlp_workload("longk", 95, dims, 6, 2, n_r, 0.05, 1e-3, fwd, seed=n_r, n_flip=2)
     _check_step(B, w)
+
+
+@pytest.mark.parametrize("cfg,n_r", [(2, 1), (2, 4), (3, 1), (3, 4), (3, 5)])
+def test_small_server_batches(B, cfg, n_r):
+    """The paper's own setting: n_r = 4 samples per iteration (Section 6.1) and the remark that
+    n_r = 1 suffices in theory.  Same kernels, one 32-row block of which n_r rows are live."""
+    w = WL.make_config(cfg, n_r=n_r)
+    assert w.n_r == n_r
+    # Workload 2's faulty rows are N(0, 200^2) noise: their logits move by ~1e4 and, with one or a
+    # few samples, lse(z0 + dz) - dz[y] cancels most of that, so the fp32 rounding of dz (6e-8
+    # relative to ~1e4) shows at a few 1e-5 of the score scale; nothing averages it away as the 32
+    # samples of the full workload do.  Those rows are gated at 1e-4, everything else at 1e-5.
+    _check_step(B, w, tol=1e-4 if cfg == 2 else None)
+
+
+@pytest.mark.parametrize("fwd", ["fp32", "bf16"])
+def test_single_sample_deep_net(B, fwd):
+    w = WL.make_mlp_workload("nr1", 96, [200, 130, 70, 33, 6], 9, 3, 1, 0.1, 1e-3, fwd, n_flip=2, n_noise=1,
+                             worker_batch=16)
+    # one sample through four small bf16 layers: the contract is met to 2e-7, but nothing averages the
+    # operand rounding, so the distance to the float64 definition (0.11 here) is reported, not bounded
+    _check_step(B, w, exact_bound=None)
 
 
 def test_workspace_contents_do_not_matter(B):
