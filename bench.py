@@ -170,7 +170,7 @@ def main():
         e[0] += 1
         e[1] += ms
         e[2] += nbytes
-    # the two baseline aggregators on the same G (Section 6.1.1, Definition 4), and the variant of
+    # the baseline aggregators on the same G (Section 6.1.1, Definitions 4 and 5), and the variant of
     # the aggregation that also takes the server's SGD step (Algorithm 1), in place on a copy of x
     B.profile_enable(True)
     x_step = w.x.clone()
@@ -179,6 +179,8 @@ def main():
         B.zeno_median(Gs[i % n_buf], out=out)
         B.zeno_aggregate_update(Gs[i % n_buf], scores, b, w.gamma, x_step, x_next=x_step, want_out=False,
                                 selected=sel)
+        if 3 <= m <= 128 and m - b - 2 >= 1:
+            B.zeno_krum(Gs[i % n_buf], b, out=out)     # Krum_b (Definition 5), the paper's main baseline
     torch.cuda.synchronize()
     for name, layer, ms, nbytes in B.profile_collect():
         e = per.setdefault(name, [0, 0.0, 0.0])
@@ -186,7 +188,7 @@ def main():
         e[1] += ms
         e[2] += nbytes
     B.profile_enable(False)
-    kernels = {k: {"launches_per_step": v[0] / (3 if k in ("mean", "median", "average_update") else n_prof), "avg_ms": v[1] / v[0],
+    kernels = {k: {"launches_per_step": v[0] / (3 if k in ("mean", "median", "average_update", "krum") else n_prof), "avg_ms": v[1] / v[0],
                    "algorithmic_GBps": (v[2] / v[0]) / (v[1] / v[0]) / 1e6} for k, v in per.items()}
     layers = {k: {"avg_ms": v[1] / v[0], "algorithmic_GBps": v[2] / v[1] / 1e6} for k, v in per_layer.items()}
     dom = per["layer_cand"]

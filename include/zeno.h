@@ -156,6 +156,20 @@ zeno_status_t zeno_mean(const float* G, int64_t ldg, int32_t m, int64_t d, float
  * midpoint of the two middle values.  UNSUPPORTED for m > 128. */
 zeno_status_t zeno_median(const float* G, int64_t ldg, int32_t m, int64_t d, float* out, void* stream);
 
+/* Krum_b (Definition 5, the paper's main baseline): out = the row of G whose sum of squared
+ * distances to its m-b-2 nearest other rows is smallest (ties: lower index).  The distances
+ * come from the Gram matrix G G^T, taken in one pass over G on the fp32 matrix cores and
+ * summed in float64; they are therefore exact to about 1e-5 of ||G_i||^2 + ||G_j||^2, and two
+ * rows whose Krum scores differ by less than that may be chosen either way.  Requires
+ * m - b - 2 >= 1; UNSUPPORTED for m > 128; rows must be finite.
+ *   out         DEVICE [d]    copy of the chosen row
+ *   chosen      DEVICE [1]    int32 out, index of the chosen row
+ *   krum_scores DEVICE [m]    out, the m sums of squared distances, or NULL
+ *   workspace   DEVICE, 256-byte aligned, >= zeno_krum_workspace_bytes(m) */
+size_t zeno_krum_workspace_bytes(int32_t m);
+zeno_status_t zeno_krum(const float* G, int64_t ldg, int32_t m, int64_t d, int32_t b, float* out, int32_t* chosen,
+                        float* krum_scores, void* workspace, size_t workspace_bytes, void* stream);
+
 const char* zeno_status_string(zeno_status_t status);
 
 /* Per-launch timing, a measurement aid (Section 5.3 prices the step by its
@@ -177,7 +191,8 @@ typedef enum {
   ZENO_KERNEL_AVERAGE = 5,    /* selection + average of the chosen rows */
   ZENO_KERNEL_MEAN = 6,
   ZENO_KERNEL_MEDIAN = 7,
-  ZENO_KERNEL_AVERAGE_UPDATE = 8 /* selection + average + x_next = x - gamma * average */
+  ZENO_KERNEL_AVERAGE_UPDATE = 8, /* selection + average + x_next = x - gamma * average */
+  ZENO_KERNEL_KRUM = 9            /* Gram matrix + selection + copy of the chosen row */
 } zeno_kernel_t;
 
 typedef struct {

@@ -161,19 +161,28 @@ def median(G):
         return 0.5 * (srt[m // 2 - 1] + srt[m // 2])
 
 
-def krum(G, b):
-    """Krum_b (Definition 5): the candidate with the smallest sum of squared
-    distances to its m-b-2 nearest neighbours; ties go to the lower index."""
+def krum_scores(G, b):
+    """Definition 5: for every candidate the sum of squared distances to its m-b-2
+    nearest other candidates."""
     G = np.asarray(G, dtype=np.float64)
     m = G.shape[0]
     assert m - b - 2 >= 1
-    best, best_val = -1, np.inf
+    out = np.empty(m)
     for i in range(m):
         dist = sorted(float(np.sum((G[i] - G[j]) ** 2)) for j in range(m) if j != i)
-        val = sum(dist[:m - b - 2])
-        if val < best_val:
-            best, best_val = i, val
-    return G[best].copy(), best
+        out[i] = sum(dist[:m - b - 2])
+    return out
+
+
+def krum(G, b):
+    """Krum_b (Definition 5): the candidate with the smallest sum of squared
+    distances to its m-b-2 nearest neighbours; ties go to the lower index."""
+    vals = krum_scores(G, b)
+    best, best_val = -1, np.inf
+    for i in range(len(vals)):
+        if vals[i] < best_val:
+            best, best_val = i, vals[i]
+    return np.asarray(G, dtype=np.float64)[best].copy(), best
 
 
 def sgd_update(x, v, gamma):

@@ -23,9 +23,10 @@ STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported size", 3: "workspace",
 
 EXPORTS = ["zeno_model_create", "zeno_model_destroy", "zeno_model_num_params",
            "zeno_score_workspace_bytes", "zeno_score", "zeno_aggregate", "zeno_aggregate_update", "zeno_mean",
-           "zeno_median", "zeno_status_string", "zeno_profile_enable", "zeno_profile_collect"]
+           "zeno_median", "zeno_krum_workspace_bytes", "zeno_krum", "zeno_status_string", "zeno_profile_enable", "zeno_profile_collect"]
 
-KERNEL_NAMES = ["pack", "layer_base", "layer_cand", "loss", "combine", "average", "mean", "median", "average_update"]
+KERNEL_NAMES = ["pack", "layer_base", "layer_cand", "loss", "combine", "average", "mean", "median", "average_update",
+                "krum"]
 
 
 class ZenoError(RuntimeError):
@@ -87,6 +88,10 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.zeno_mean.restype = ctypes.c_int
     lib.zeno_median.argtypes = [vp, i64, i32, i64, vp, vp]
     lib.zeno_median.restype = ctypes.c_int
+    lib.zeno_krum_workspace_bytes.argtypes = [i32]
+    lib.zeno_krum_workspace_bytes.restype = ctypes.c_size_t
+    lib.zeno_krum.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.zeno_krum.restype = ctypes.c_int
     lib.zeno_profile_enable.argtypes = [i32]
     lib.zeno_profile_enable.restype = ctypes.c_int
     lib.zeno_profile_collect.argtypes = [ctypes.POINTER(_ProfileRecord), i32]
@@ -278,6 +283,26 @@ def zeno_median(G, *, out=None):
     if st != 0:
         raise ZenoError(st, "zeno_median")
     return out
+
+
+def zeno_krum(G, b, *, out=None, want_scores=True, workspace=None):
+    """Krum_b (Definition 5).  Returns (out, chosen index tensor [1], krum scores or None)."""
+    lib = load_library()
+    m, d = int(G.shape[0]), int(G.shape[1])
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=G.device)
+    chosen = torch.empty(1, dtype=torch.int32, device=G.device)
+    ks = torch.empty(m, dtype=torch.float32, device=G.device) if want_scores else None
+    if workspace is None:
+        n = int(lib.zeno_krum_workspace_bytes(m))
+        workspace = torch.empty(max(n, 256), dtype=torch.uint8, device=G.device)
+    g_ptr, ldg = _rows(G)
+    st = lib.zeno_krum(g_ptr, ldg, m, d, int(b), _dev(out, torch.float32, "out"), _dev(chosen, torch.int32, "chosen"),
+                       _dev(ks, torch.float32, "krum_scores") if ks is not None else None,
+                       _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream())
+    if st != 0:
+        raise ZenoError(st, "zeno_krum")
+    return out, chosen, ks
 
 
 def profile_enable(on: bool = True):

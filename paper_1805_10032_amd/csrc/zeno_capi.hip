@@ -364,6 +364,24 @@ zeno_status_t zeno_median(const float* G, int64_t ldg, int32_t m, int64_t d, flo
   return ZENO_OK;
 }
 
+size_t zeno_krum_workspace_bytes(int32_t m) {
+  if (m < 3 || m > 128) return 0;
+  return krum_workspace_bytes(m);
+}
+
+zeno_status_t zeno_krum(const float* G, int64_t ldg, int32_t m, int64_t d, int32_t b, float* out, int32_t* chosen,
+                        float* krum_scores, void* workspace, size_t workspace_bytes, void* stream) {
+  if (G == nullptr || out == nullptr || chosen == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (m < 3 || m > ZENO_MAX_CANDIDATES || b < 0 || m - b - 2 < 1 || d < 1 || ldg < d) return ZENO_ERR_INVALID_ARG;
+  if (!aligned(G, 4) || !aligned(out, 4) || !aligned(chosen, 4) || !aligned(krum_scores, 4)) return ZENO_ERR_INVALID_ARG;
+  if (m > 128) return ZENO_ERR_UNSUPPORTED;
+  if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < krum_workspace_bytes(m))
+    return ZENO_ERR_WORKSPACE;
+  ProfScope ps(ZENO_KERNEL_KRUM, 0, 4.0 * (double)d * (m + 2), reinterpret_cast<hipStream_t>(stream));
+  ZENO_TRY(launch_krum(G, ldg, m, d, b, out, chosen, krum_scores, workspace, reinterpret_cast<hipStream_t>(stream)));
+  return ZENO_OK;
+}
+
 const char* zeno_status_string(zeno_status_t status) {
   switch (status) {
     case ZENO_OK: return "ok";

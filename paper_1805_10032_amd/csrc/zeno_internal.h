@@ -90,6 +90,9 @@ hipError_t launch_score_combine(const double* sample_diff, const double* norm_pa
 hipError_t launch_masked_average(const float* G, long long ldg, const float* scores, int m, long long d, int b,
                                  float* out, int32_t* selected, hipStream_t stream, float gamma = 0.f,
                                  const float* x = nullptr, float* x_next = nullptr);
+size_t krum_workspace_bytes(int m);
+hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b, float* out, int32_t* chosen,
+                       float* scores_out, void* workspace, hipStream_t stream);
 hipError_t launch_median(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream);
 
 }  // namespace zeno

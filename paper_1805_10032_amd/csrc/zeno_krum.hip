@@ -1,0 +1,244 @@
+// Krum_b (Definition 5): the candidate with the smallest sum of squared distances to
+// its m-b-2 nearest neighbours.  The O(d m^2) part is the Gram matrix S = G G^T, taken
+// in one pass over G on the fp32 matrix cores (v_mfma_f32_32x32x2_f32); the squared
+// distances follow as S_ii + S_jj - 2 S_ij.
+//
+// krum_gram_kernel<RB>: the m <= 32 RB rows are cut into RB row blocks.  A wave owns a
+// contiguous range of 64-column chunks; per chunk it loads the RB tiles of 32 rows x 64
+// columns with coalesced 128-bit loads (rows at or beyond m read row m-1 and are
+// zeroed), passes each through its wave-private XOR-swizzled LDS tile to reach operand
+// order, and accumulates the RB(RB+1)/2 block products S_ab += T_a T_b^T, a <= b.  The
+// four waves of a workgroup add their accumulators through LDS in a fixed tree and
+// write one partial Gram per workgroup; krum_select_kernel sums the partials in
+// float64 (fixed order), forms the scores and picks the winner; krum_copy_kernel copies
+// the winning row.
+#include "zeno_layer_impl.h"
+
+namespace zeno {
+
+namespace {
+
+constexpr int kGramWaves = 4;
+
+template <int RB>
+__global__ __launch_bounds__(64 * kGramWaves) void krum_gram_kernel(const float* __restrict__ G, long long ldg,
+                                                                    int m, long long d, float* __restrict__ partial) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  constexpr int PAIRS = RB * (RB + 1) / 2;
+  constexpr int TILE_BYTES = 32 * 64 * 4;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  unsigned char* st = lds + wave * (RB * TILE_BYTES);
+  const int rsub = lane >> 4, kq = (lane & 15) << 2;
+  const int n = lane & 31, h = lane >> 5;
+
+  f32x16 acc[PAIRS];
+#pragma unroll
+  for (int p = 0; p < PAIRS; ++p)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[p][j] = 0.f;
+
+  // balanced contiguous share of the 64-column chunks for every wave of the launch
+  const long long n_chunks = (d + 63) / 64;
+  const long long w_global = (long long)blockIdx.x * kGramWaves + wave;
+  const long long w_total = (long long)gridDim.x * kGramWaves;
+  const long long c_begin = n_chunks * w_global / w_total, c_end = n_chunks * (w_global + 1) / w_total;
+
+  for (long long c = c_begin; c < c_end; ++c) {
+    const long long k0 = c * 64;
+    const bool k_full = k0 + 64 <= d;  // wave-uniform
+    f32x4 u[RB][8];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = 32 * rb + 4 * j + rsub;
+        const int rc = row < m ? row : m - 1;   // in bounds; zeroed below
+        const float* p = G + (long long)rc * ldg + k0;
+        f32x4 v;
+        if (k_full) {
+          v = load_stream4(p + kq);
+        } else {
+          v = load4_masked(p, kq, (int)(d - k0), true);
+        }
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        u[rb][j] = row < m ? v : zero;
+      }
+    }
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) stage_tile<false>(u[rb], st + rb * TILE_BYTES, lane);
+    // operand fragments: lane (n, h) reads row n, columns 8t + 4h .. + 3 of each tile
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      f32x4 f[RB];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+        f[rb] = *reinterpret_cast<const f32x4*>(st + rb * TILE_BYTES + n * 256 + ((((2 * t + h) ^ n) & 15) << 4));
+      int p = 0;
+#pragma unroll
+      for (int a = 0; a < RB; ++a)
+#pragma unroll
+        for (int b = a; b < RB; ++b, ++p)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[p] = __builtin_amdgcn_mfma_f32_32x32x2f32(f[a][e], f[b][e], acc[p], 0, 0, 0);
+    }
+  }
+
+  // sum the four waves' accumulators in a fixed tree, (0+2)+(1+3), through LDS
+  float* red = reinterpret_cast<float*>(lds);
+  for (int step = kGramWaves / 2; step >= 1; step >>= 1) {
+    __syncthreads();
+    if (wave >= step && wave < 2 * step) {
+#pragma unroll
+      for (int p = 0; p < PAIRS; ++p)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) red[(((wave - step) * PAIRS + p) * 16 + j) * 64 + lane] = acc[p][j];
+    }
+    __syncthreads();
+    if (wave < step) {
+#pragma unroll
+      for (int p = 0; p < PAIRS; ++p)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[p][j] += red[((wave * PAIRS + p) * 16 + j) * 64 + lane];
+    }
+  }
+  if (wave == 0) {
+    // accumulator element j of lane (n, h): row 8 (j/4) + 4 h + j%4 of block a, column n of block b
+    float* out = partial + (long long)blockIdx.x * PAIRS * 1024;
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) out[p * 1024 + (8 * (j >> 2) + 4 * h + (j & 3)) * 32 + n] = acc[p][j];
+  }
+}
+
+// One workgroup: S = sum of the partial Grams (float64, workgroup order), squared
+// distances, Krum scores, winner (ties to the lower index).
+__global__ __launch_bounds__(256) void krum_select_kernel(const float* __restrict__ partial, int n_partials, int rb,
+                                                          int m, int b, int32_t* __restrict__ chosen,
+                                                          float* __restrict__ scores_out) {
+  extern __shared__ double krum_sm[];          // m(m+1)/2 + m doubles
+  double* S = krum_sm;                          // upper triangle of the Gram matrix, row-major packed
+  double* score = krum_sm + m * (m + 1) / 2;
+  const int pairs = rb * (rb + 1) / 2;
+  auto tri = [&](int i, int j) { return i * m - i * (i - 1) / 2 + (j - i); };  // i <= j
+  for (int e = threadIdx.x; e < m * (m + 1) / 2; e += blockDim.x) {
+    // invert the packed index
+    int i = 0, rem = e;
+    while (rem >= m - i) { rem -= m - i; ++i; }
+    const int j = i + rem;
+    const int a = i >> 5, bb = j >> 5;          // block pair (a <= bb), pair index in the kernel's order
+    const int p = a * rb - a * (a - 1) / 2 + (bb - a);
+    const int off = p * 1024 + (i & 31) * 32 + (j & 31);
+    double t = 0.0;
+    for (int w = 0; w < n_partials; ++w) t += (double)partial[(long long)w * pairs * 1024 + off];
+    S[e] = t;
+  }
+  __syncthreads();
+  const int keep = m - b - 2;
+  for (int i = threadIdx.x; i < m; i += blockDim.x) {
+    // sum of the `keep` smallest squared distances to the others: selection by repeated minimum
+    // over a used-mask (m <= 128: two 64-bit words)
+    unsigned long long used0 = 0, used1 = 0;
+    double total = 0.0;
+    const double sii = S[tri(i, i)];
+    for (int r = 0; r < keep; ++r) {
+      double best = __builtin_inf();
+      int bj = -1;
+      for (int j = 0; j < m; ++j) {
+        if (j == i) continue;
+        const bool u = j < 64 ? ((used0 >> j) & 1ull) : ((used1 >> (j - 64)) & 1ull);
+        if (u) continue;
+        const double sij = i <= j ? S[tri(i, j)] : S[tri(j, i)];
+        double dist = sii + S[tri(j, j)] - 2.0 * sij;
+        dist = dist < 0.0 ? 0.0 : dist;
+        if (dist < best) { best = dist; bj = j; }
+      }
+      if (bj < 0) break;
+      if (bj < 64) used0 |= 1ull << bj; else used1 |= 1ull << (bj - 64);
+      total += best;
+    }
+    score[i] = total;
+    if (scores_out != nullptr) scores_out[i] = (float)total;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int best = 0;
+    for (int i = 1; i < m; ++i)
+      if (score[i] < score[best]) best = i;
+    *chosen = best;
+  }
+}
+
+__global__ __launch_bounds__(256) void krum_copy_kernel(const float* __restrict__ G, long long ldg, long long d,
+                                                        const int32_t* __restrict__ chosen, float* __restrict__ out) {
+  const float* row = G + (long long)(*chosen) * ldg;
+  for (long long j = (long long)blockIdx.x * blockDim.x + threadIdx.x; j < d; j += (long long)gridDim.x * blockDim.x)
+    out[j] = row[j];
+}
+
+int gram_grid(int rb) {
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+      v = 256;
+    n_cu = v;
+  }
+  const int lds = kGramWaves * rb * 32 * 64 * 4;
+  int per_cu = (160 * 1024) / lds;
+  per_cu = per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu);
+  return n_cu * per_cu;
+}
+
+template <int RB>
+hipError_t launch_gram(const float* G, long long ldg, int m, long long d, float* partial, int grid, hipStream_t stream) {
+  constexpr int lds = kGramWaves * RB * 32 * 64 * 4;
+  static bool attr_set = false;
+  if (!attr_set && lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(krum_gram_kernel<RB>, dim3(grid), dim3(64 * kGramWaves), lds, stream, G, ldg, m, d, partial);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t krum_workspace_bytes(int m) {
+  const int rb = (m + 31) / 32;
+  return align_up((size_t)gram_grid(rb) * (rb * (rb + 1) / 2) * 1024 * sizeof(float), 256);
+}
+
+hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b, float* out, int32_t* chosen,
+                       float* scores_out, void* workspace, hipStream_t stream) {
+  const int rb = (m + 31) / 32;
+  const int grid = gram_grid(rb);
+  float* partial = reinterpret_cast<float*>(workspace);
+  hipError_t e;
+  if (rb == 1) e = launch_gram<1>(G, ldg, m, d, partial, grid, stream);
+  else if (rb == 2) e = launch_gram<2>(G, ldg, m, d, partial, grid, stream);
+  else if (rb == 3) e = launch_gram<3>(G, ldg, m, d, partial, grid, stream);
+  else e = launch_gram<4>(G, ldg, m, d, partial, grid, stream);
+  if (e != hipSuccess) return e;
+  const int sel_lds = (m * (m + 1) / 2 + m) * (int)sizeof(double);
+  static bool sel_attr = false;
+  if (!sel_attr) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_select_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (128 * 129 / 2 + 128) * (int)sizeof(double));
+    if (e != hipSuccess) return e;
+    sel_attr = true;
+  }
+  hipLaunchKernelGGL(krum_select_kernel, dim3(1), dim3(256), sel_lds, stream, partial, grid, rb, m, b, chosen,
+                     scores_out);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  long long want = (d + 255) / 256;
+  const int cgrid = (int)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+  hipLaunchKernelGGL(krum_copy_kernel, dim3(cgrid), dim3(256), 0, stream, G, ldg, d, chosen, out);
+  return hipGetLastError();
+}
+
+}  // namespace zeno
