@@ -44,16 +44,16 @@ __global__ __launch_bounds__(64 * kGramWaves) void krum_gram_kernel(const float*
   const long long w_total = (long long)gridDim.x * kGramWaves;
   const long long c_begin = n_chunks * w_global / w_total, c_end = n_chunks * (w_global + 1) / w_total;
 
-  for (long long c = c_begin; c < c_end; ++c) {
+  // tile loads of chunk c into registers (rows at or beyond m read row m-1 and are zeroed)
+  auto load_chunk = [&](f32x4 (&u)[RB][8], long long c) __attribute__((always_inline)) {
     const long long k0 = c * 64;
     const bool k_full = k0 + 64 <= d;  // wave-uniform
-    f32x4 u[RB][8];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int row = 32 * rb + 4 * j + rsub;
-        const int rc = row < m ? row : m - 1;   // in bounds; zeroed below
+        const int rc = row < m ? row : m - 1;
         const float* p = G + (long long)rc * ldg + k0;
         f32x4 v;
         if (k_full) {
@@ -65,6 +65,9 @@ __global__ __launch_bounds__(64 * kGramWaves) void krum_gram_kernel(const float*
         u[rb][j] = row < m ? v : zero;
       }
     }
+  };
+  // stage the tiles and accumulate the block products of one chunk
+  auto products = [&](const f32x4 (&u)[RB][8]) __attribute__((always_inline)) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) stage_tile<false>(u[rb], st + rb * TILE_BYTES, lane);
     // operand fragments: lane (n, h) reads row n, columns 8t + 4h .. + 3 of each tile
@@ -81,6 +84,32 @@ __global__ __launch_bounds__(64 * kGramWaves) void krum_gram_kernel(const float*
         for (int b = a; b < RB; ++b, ++p)
 #pragma unroll
           for (int e = 0; e < 4; ++e) acc[p] = __builtin_amdgcn_mfma_f32_32x32x2f32(f[a][e], f[b][e], acc[p], 0, 0, 0);
+    }
+  };
+
+  if (RB <= 2) {
+    // one chunk ahead in registers: the loads of chunk c+1 fly while chunk c is multiplied
+    if (c_begin < c_end) {
+      f32x4 u0[RB][8], u1[RB][8];
+      load_chunk(u0, c_begin);
+      long long c = c_begin;
+      for (; c + 2 < c_end; c += 2) {
+        load_chunk(u1, c + 1);
+        products(u0);
+        load_chunk(u0, c + 2);
+        products(u1);
+      }
+      products(u0);
+      if (c + 1 < c_end) {
+        load_chunk(u1, c + 1);
+        products(u1);
+      }
+    }
+  } else {
+    for (long long c = c_begin; c < c_end; ++c) {
+      f32x4 u[RB][8];
+      load_chunk(u, c);
+      products(u);
     }
   }
 
@@ -177,18 +206,28 @@ __global__ __launch_bounds__(256) void krum_copy_kernel(const float* __restrict_
     out[j] = row[j];
 }
 
-int gram_grid(int rb) {
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
-      v = 256;
-    n_cu = v;
+template <int RB>
+int gram_resident() {
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0, n_cu = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+      n_cu = 256;
+    constexpr int lds = kGramWaves * RB * 32 * 64 * 4;
+    if (lds > 48 * 1024)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&krum_gram_kernel<RB>),
+                                                     64 * kGramWaves, lds) != hipSuccess || per_cu < 1)
+      per_cu = 1;
+    cached = n_cu * per_cu;
   }
-  const int lds = kGramWaves * rb * 32 * 64 * 4;
-  int per_cu = (160 * 1024) / lds;
-  per_cu = per_cu < 1 ? 1 : (per_cu > 2 ? 2 : per_cu);
-  return n_cu * per_cu;
+  return cached;
+}
+
+// workgroups of the Gram launch: as many as the chip holds at once
+int gram_grid(int rb) {
+  return rb == 1 ? gram_resident<1>() : rb == 2 ? gram_resident<2>() : rb == 3 ? gram_resident<3>() : gram_resident<4>();
 }
 
 template <int RB>
