@@ -9,9 +9,9 @@
 // zeroed), passes each through its wave-private XOR-swizzled LDS tile to reach operand
 // order, and accumulates the RB(RB+1)/2 block products S_ab += T_a T_b^T, a <= b.  The
 // four waves of a workgroup add their accumulators through LDS in a fixed tree and
-// write one partial Gram per workgroup; krum_select_kernel sums the partials in
-// float64 (fixed order), forms the scores and picks the winner; krum_copy_kernel copies
-// the winning row.
+// write one partial Gram per workgroup; krum_reduce_kernel sums the partials in
+// float64 (fixed order), krum_select_kernel forms the scores and picks the winner,
+// krum_copy_kernel copies the winning row.
 #include "zeno_layer_impl.h"
 
 namespace zeno {
@@ -141,15 +141,32 @@ __global__ __launch_bounds__(64 * kGramWaves) void krum_gram_kernel(const float*
   }
 }
 
-// One workgroup: S = sum of the partial Grams (float64, workgroup order), squared
-// distances, Krum scores, winner (ties to the lower index).
-__global__ __launch_bounds__(256) void krum_select_kernel(const float* __restrict__ partial, int n_partials, int rb,
+// Sum of the per-workgroup partial Grams in float64, in workgroup order: one thread per entry.
+__global__ __launch_bounds__(256) void krum_reduce_kernel(const float* __restrict__ partial, int n_partials,
+                                                          int entries, double* __restrict__ gram) {
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= entries) return;
+  double t = 0.0;
+  int w = 0;
+  for (; w + 8 <= n_partials; w += 8) {   // eight loads in flight, added in workgroup order
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = partial[(long long)(w + q) * entries + e];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t += (double)v[q];
+  }
+  for (; w < n_partials; ++w) t += (double)partial[(long long)w * entries + e];
+  gram[e] = t;
+}
+
+// One workgroup: squared distances from the summed Gram blocks, Krum scores, winner
+// (ties to the lower index).
+__global__ __launch_bounds__(256) void krum_select_kernel(const double* __restrict__ gram, int rb,
                                                           int m, int b, int32_t* __restrict__ chosen,
                                                           float* __restrict__ scores_out) {
   extern __shared__ double krum_sm[];          // m(m+1)/2 + m doubles
   double* S = krum_sm;                          // upper triangle of the Gram matrix, row-major packed
   double* score = krum_sm + m * (m + 1) / 2;
-  const int pairs = rb * (rb + 1) / 2;
   auto tri = [&](int i, int j) { return i * m - i * (i - 1) / 2 + (j - i); };  // i <= j
   for (int e = threadIdx.x; e < m * (m + 1) / 2; e += blockDim.x) {
     // invert the packed index
@@ -158,10 +175,7 @@ __global__ __launch_bounds__(256) void krum_select_kernel(const float* __restric
     const int j = i + rem;
     const int a = i >> 5, bb = j >> 5;          // block pair (a <= bb), pair index in the kernel's order
     const int p = a * rb - a * (a - 1) / 2 + (bb - a);
-    const int off = p * 1024 + (i & 31) * 32 + (j & 31);
-    double t = 0.0;
-    for (int w = 0; w < n_partials; ++w) t += (double)partial[(long long)w * pairs * 1024 + off];
-    S[e] = t;
+    S[e] = gram[p * 1024 + (i & 31) * 32 + (j & 31)];
   }
   __syncthreads();
   const int keep = m - b - 2;
@@ -248,7 +262,8 @@ hipError_t launch_gram(const float* G, long long ldg, int m, long long d, float*
 
 size_t krum_workspace_bytes(int m) {
   const int rb = (m + 31) / 32;
-  return align_up((size_t)gram_grid(rb) * (rb * (rb + 1) / 2) * 1024 * sizeof(float), 256);
+  const size_t entries = (size_t)(rb * (rb + 1) / 2) * 1024;
+  return align_up((size_t)gram_grid(rb) * entries * sizeof(float), 256) + align_up(entries * sizeof(double), 256);
 }
 
 hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b, float* out, int32_t* chosen,
@@ -270,8 +285,13 @@ hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b,
     if (e != hipSuccess) return e;
     sel_attr = true;
   }
-  hipLaunchKernelGGL(krum_select_kernel, dim3(1), dim3(256), sel_lds, stream, partial, grid, rb, m, b, chosen,
-                     scores_out);
+  const int entries = (rb * (rb + 1) / 2) * 1024;
+  double* gram = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(workspace) +
+                                           align_up((size_t)grid * entries * sizeof(float), 256));
+  hipLaunchKernelGGL(krum_reduce_kernel, dim3((entries + 255) / 256), dim3(256), 0, stream, partial, grid, entries, gram);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(krum_select_kernel, dim3(1), dim3(256), sel_lds, stream, gram, rb, m, b, chosen, scores_out);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   long long want = (d + 255) / 256;
