@@ -216,10 +216,12 @@ def zeno_step(x, G, b, gamma, rho, dims, has_bias, loss, features, labels=None, 
 #     h0_0 = the batch;
 #   * candidate u is propagated as the CHANGE of the pre-activations,
 #       dz_l = -gamma ( rb(h_{l-1}) rb(U_l)^T + rb(D_{l-1}) rb(W_l)^T + ub_l ),
-#       h_l = relu(z0_l + dz_l),  D_l = (relu(z0_l + dz_l) - relu(z0_l)) (-1/gamma),
-#     with D_0 = 0 and h_0 = the batch.  In exact arithmetic z0_l + dz_l equals the
-#     pre-activation of the model at x - gamma u, so without rounding this is
-#     Definition 2 unchanged;
+#       D_l = (relu(z0_l + dz_l) - relu(z0_l)) (-1/gamma),  D_0 = 0,  h_0 = the batch,
+#     and only D_l is carried from layer to layer: the candidate's activations are
+#     rebuilt as  h_l = fl32( rb(h0_l) - gamma rb(D_l) )  (one float32 rounding, a
+#     fused multiply-add) from the operands as they are stored.  In exact arithmetic
+#     h_l = relu(z0_l + dz_l) and z0_l + dz_l equals the pre-activation of the model
+#     at x - gamma u, so without rounding this is Definition 2 unchanged;
 #   * loss difference per sample and the final combine as in the exact oracle.
 #
 # Pinned by: exact equality with the float64 oracle when every operand is
@@ -277,7 +279,7 @@ def scores_bf16(x, G, gamma, rho, dims, has_bias, loss, features, labels=None, t
                     h_new = np.where(zs <= 0.0, 0.0, zs)
                     delta = np.where(z0[l] > 0.0, np.where(dz < -z0[l], -z0[l], dz), h_new)
                     dprime = _f32(delta * neg_inv_gamma)
-                    h = h_new
+                    h = _f32(rb(h0[l + 1]) - np.float64(np.float32(gamma)) * rb(dprime))
             diff = sample_losses(z0[-1] + dz, loss, labels, targets) - base_losses
             out.append(-float(np.mean(diff)) - rho * float(np.dot(u, u)))
     return np.array(out, dtype=np.float64)

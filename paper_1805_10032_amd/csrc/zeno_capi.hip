@@ -32,7 +32,7 @@ struct Plan {
   int L, pass_rows, MB, n_pad, esize, P;
   size_t off_feat, off_hbase[ZENO_MAX_LAYERS], off_z0[ZENO_MAX_LAYERS];
   size_t off_wt[ZENO_MAX_LAYERS];  // W_l in operand order, layers after the first
-  size_t off_hc[2], off_dc[2], cand_stride, off_dz, off_norm, off_diff, total;
+  size_t off_dc[2], cand_stride, off_dz, off_norm, off_diff, total;
 };
 
 Plan make_plan(const zeno_model* mdl, int m, int n_r) {
@@ -67,7 +67,6 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
   }
   p.cand_stride = align_up((size_t)p.n_pad * max_np * p.esize, 256);
   if (p.L > 1) {
-    for (int i = 0; i < 2; ++i) p.off_hc[i] = take(p.cand_stride * m);
     for (int i = 0; i < 2; ++i) p.off_dc[i] = take(p.cand_stride * m);
   }
   p.off_dz = take((size_t)m * p.pass_rows * D.dims[p.L] * sizeof(float));
@@ -284,10 +283,8 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
         a.bj = make_job(0);
         bytes += layer_bytes(0);
       } else {
-        a.A_cand = l == 0 ? nullptr : ws + p.off_hc[(l - 1) & 1];
         a.D_cand = l == 0 ? nullptr : ws + p.off_dc[(l - 1) & 1];
         a.A_stride = (long long)p.cand_stride;
-        a.H_cand = ws + p.off_hc[l & 1];
         a.Dl_cand = ws + p.off_dc[l & 1];
         a.H_stride = (long long)p.cand_stride;
         if (l + 1 < L) {

@@ -60,13 +60,11 @@ struct LayerArgs {
   int base_blocks;      // leading block indices reserved for the pass at x (multiple of 8)
   int n_r;              // valid samples (rows) in this pass
   LayerJob cj, bj;
-  const void* A_cand;   // tiled activations of candidate 0 (NULL: all candidates read cj.A_base, first layer)
   const void* D_cand;   // tiled scaled activation differences of candidate 0 (delta launches only)
-  long long A_stride;   // bytes between consecutive candidates in A_cand / D_cand
+  long long A_stride;   // bytes between consecutive candidates in D_cand
   float* dZ;            // [m x n_r x N] change of the output layer's pre-activations (last layer)
-  void* H_cand;         // tiled output activations of candidate 0 (hidden layers)
   void* Dl_cand;        // tiled scaled output differences of candidate 0 (hidden layers)
-  long long H_stride;   // bytes between consecutive candidates in H_cand / Dl_cand
+  long long H_stride;   // bytes between consecutive candidates in Dl_cand
   float gamma;
   float neg_inv_gamma;  // -1/gamma, or 0 when gamma == 0
   double* norm_partials;  // [m x P] partial sums of squares, or NULL in passes after the first

@@ -10,7 +10,9 @@
 //
 // where H_s are candidate s's input activations, U_s / ub_s its weight / bias
 // block, and D_s = (H_s - H0) * (-1/gamma) the scaled change of the input
-// activations (absent at the first layer, where H_s = H0 = the batch).  dZ_s is
+// activations (absent at the first layer, where H_s = H0 = the batch).  Only D_s
+// is stored per candidate: H_s = H0 - gamma D_s is rebuilt in LDS, once per chunk
+// and workgroup, from the shared H0 (which stays in the caches) and D_s.  dZ_s is
 // the change of the pre-activations caused by moving x to x - gamma u_s, so the
 // perturbed parameters are never formed and f_r(x) - f_r(x - gamma u) is later
 // obtained without subtracting two nearly equal losses.  ||u_s||^2 is
@@ -321,7 +323,6 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   const bool full_rows = row0 + 32 <= N;
 
   const unsigned char* Ag = reinterpret_cast<const unsigned char*>(J.A_base);
-  if (!is_base && a.A_cand != nullptr) Ag = reinterpret_cast<const unsigned char*>(a.A_cand) + (long long)s * a.A_stride;
   // The pass at x has no second product: its D operand is a harmless alias of H
   // and its products are skipped.
   const bool has_delta = DELTA && !is_base;
@@ -372,6 +373,31 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
         unsigned char* dst = lds + buf * AD_BYTES + q * 1024;
         lds_dma16(src, dst);
       }
+    }
+  };
+  // Rebuild the candidate's activations in LDS buffer `buf`: the H half holds H0 (copied
+  // from the pass at x), the D half the candidate's D; H0 - gamma D replaces H0 in place
+  // (fp32 fused multiply-add per element, then the operand rounding).  All threads of the
+  // workgroup share the work; the caller brackets this with barriers.
+  const float neg_gamma = -a.gamma;
+  auto rebuild_H = [&](int buf) __attribute__((always_inline)) {
+    unsigned char* bh = lds + buf * AD_BYTES;
+    const unsigned char* bd = bh + A_BYTES;
+    for (int i = tid; i < A_BYTES / 16; i += 64 * NW) {
+      const f32x4 hraw = *reinterpret_cast<const f32x4*>(bh + i * 16);
+      const f32x4 draw = *reinterpret_cast<const f32x4*>(bd + i * 16);
+      f32x4 out;
+      if (BF16) {
+        const bf16x8 hv = __builtin_bit_cast(bf16x8, hraw), dv = __builtin_bit_cast(bf16x8, draw);
+        bf16x8 r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = (__bf16)__builtin_fmaf(neg_gamma, (float)dv[e], (float)hv[e]);
+        out = __builtin_bit_cast(f32x4, r);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = __builtin_fmaf(neg_gamma, draw[e], hraw[e]);
+      }
+      *reinterpret_cast<f32x4*>(bh + i * 16) = out;
     }
   };
   auto load_W = [&](f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
@@ -433,6 +459,10 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       __syncthreads();
     }
     if (STEADY || c + 2 < c_end) load_tile<MODE, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
+    if (SECOND) {
+      rebuild_H(buf);   // behind the tile requests, so that it does not delay them
+      __syncthreads();
+    }
 
     // Matrix products of this chunk in groups of MB products that share one B
     // operand (k-step t, operand H or D).  The scheduler is fenced so that the LDS
@@ -624,17 +654,15 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
           if (last) {
             if (row_ok) *reinterpret_cast<f32x4_a4*>(a.dZ + ((long long)s * a.n_r + r) * N + f0) = dz;
           } else {
-            f32x4 hv, dv;
+            f32x4 dv;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const float z0 = z0v[mb][q][i];
               const float hr = relu_nan(z0 + dz[i]);
               // relu(z0 + dz) - relu(z0) without cancellation
               const float dd = (z0 > 0.f) ? ((dz[i] < -z0) ? -z0 : dz[i]) : hr;
-              hv[i] = row_ok ? hr : 0.f;
               dv[i] = row_ok ? dd * a.neg_inv_gamma : 0.f;
             }
-            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.H_cand) + (long long)s * a.H_stride, r, f0, Np, hv);
             store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.Dl_cand) + (long long)s * a.H_stride, r, f0, Np, dv);
           }
         }
@@ -668,17 +696,15 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
             if (row_ok) store4_masked(a.dZ + ((long long)s * a.n_r + r) * N, f0, N, dz);
           } else if (f0 < Np) {
             const f32x4 z0 = load4_masked(J.Z0 + (long long)r * N, f0, N, row_ok);
-            f32x4 hv, dv;
+            f32x4 dv;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const bool ok = row_ok && f0 + i < N;
               const float hr = relu_nan(z0[i] + dz[i]);
               // relu(z0 + dz) - relu(z0) without cancellation
               const float dd = (z0[i] > 0.f) ? ((dz[i] < -z0[i]) ? -z0[i] : dz[i]) : hr;
-              hv[i] = ok ? hr : 0.f;
               dv[i] = ok ? dd * a.neg_inv_gamma : 0.f;
             }
-            store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.H_cand) + (long long)s * a.H_stride, r, f0, Np, hv);
             store_tiled4<BF16>(reinterpret_cast<unsigned char*>(a.Dl_cand) + (long long)s * a.H_stride, r, f0, Np, dv);
           }
         }
