@@ -383,21 +383,34 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   auto rebuild_H = [&](int buf) __attribute__((always_inline)) {
     unsigned char* bh = lds + buf * AD_BYTES;
     const unsigned char* bd = bh + A_BYTES;
-    for (int i = tid; i < A_BYTES / 16; i += 64 * NW) {
-      const f32x4 hraw = *reinterpret_cast<const f32x4*>(bh + i * 16);
-      const f32x4 draw = *reinterpret_cast<const f32x4*>(bd + i * 16);
-      f32x4 out;
-      if (BF16) {
-        const bf16x8 hv = __builtin_bit_cast(bf16x8, hraw), dv = __builtin_bit_cast(bf16x8, draw);
-        bf16x8 r;
+    constexpr int PIECES = A_BYTES / 16;
+    constexpr int PER = (PIECES + 64 * NW - 1) / (64 * NW);   // 16-byte pieces per thread
+    f32x4 hraw[PER], draw[PER];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) r[e] = (__bf16)__builtin_fmaf(neg_gamma, (float)dv[e], (float)hv[e]);
-        out = __builtin_bit_cast(f32x4, r);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) out[e] = __builtin_fmaf(neg_gamma, draw[e], hraw[e]);
+    for (int q = 0; q < PER; ++q) {
+      const int i = tid + q * 64 * NW;
+      if (PIECES % (64 * NW) == 0 || i < PIECES) {
+        hraw[q] = *reinterpret_cast<const f32x4*>(bh + i * 16);
+        draw[q] = *reinterpret_cast<const f32x4*>(bd + i * 16);
       }
-      *reinterpret_cast<f32x4*>(bh + i * 16) = out;
+    }
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int i = tid + q * 64 * NW;
+      if (PIECES % (64 * NW) == 0 || i < PIECES) {
+        f32x4 out;
+        if (BF16) {
+          const bf16x8 hv = __builtin_bit_cast(bf16x8, hraw[q]), dv = __builtin_bit_cast(bf16x8, draw[q]);
+          bf16x8 r;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) r[e] = (__bf16)__builtin_fmaf(neg_gamma, (float)dv[e], (float)hv[e]);
+          out = __builtin_bit_cast(f32x4, r);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) out[e] = __builtin_fmaf(neg_gamma, draw[q][e], hraw[q][e]);
+        }
+        *reinterpret_cast<f32x4*>(bh + i * 16) = out;
+      }
     }
   };
   auto load_W = [&](f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
