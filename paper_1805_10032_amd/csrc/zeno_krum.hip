@@ -10,8 +10,8 @@
 // order, and accumulates the RB(RB+1)/2 block products S_ab += T_a T_b^T, a <= b.  The
 // four waves of a workgroup add their accumulators through LDS in a fixed tree and
 // write one partial Gram per workgroup; krum_reduce_kernel sums the partials in
-// float64 (fixed order), krum_select_kernel forms the scores and picks the winner,
-// krum_copy_kernel copies the winning row.
+// float64 (fixed order), krum_score_kernel forms the score of one row per workgroup,
+// krum_argmin_kernel picks the winner, krum_copy_kernel copies the winning row.
 #include "zeno_layer_impl.h"
 
 namespace zeno {
@@ -159,56 +159,50 @@ __global__ __launch_bounds__(256) void krum_reduce_kernel(const float* __restric
   gram[e] = t;
 }
 
-// One workgroup: squared distances from the summed Gram blocks, Krum scores, winner
-// (ties to the lower index).
-__global__ __launch_bounds__(256) void krum_select_kernel(const double* __restrict__ gram, int rb,
-                                                          int m, int b, int32_t* __restrict__ chosen,
-                                                          float* __restrict__ scores_out) {
-  extern __shared__ double krum_sm[];          // m(m+1)/2 + m doubles
-  double* S = krum_sm;                          // upper triangle of the Gram matrix, row-major packed
-  double* score = krum_sm + m * (m + 1) / 2;
-  auto tri = [&](int i, int j) { return i * m - i * (i - 1) / 2 + (j - i); };  // i <= j
-  for (int e = threadIdx.x; e < m * (m + 1) / 2; e += blockDim.x) {
-    // invert the packed index
-    int i = 0, rem = e;
-    while (rem >= m - i) { rem -= m - i; ++i; }
-    const int j = i + rem;
-    const int a = i >> 5, bb = j >> 5;          // block pair (a <= bb), pair index in the kernel's order
+// Krum score of row i = blockIdx.x: squared distances to the other rows from the summed Gram
+// blocks, ranked by counting (ties to the lower index), the m-b-2 smallest summed in
+// ascending order.
+__global__ __launch_bounds__(128) void krum_score_kernel(const double* __restrict__ gram, int rb, int m, int b,
+                                                         double* __restrict__ score64, float* __restrict__ scores_out) {
+  __shared__ double dist[128];
+  __shared__ double sorted[128];
+  const int i = blockIdx.x, j = threadIdx.x;
+  auto S = [&](int r, int c) {   // Gram entry (r, c), stored for block pairs a <= b only
+    if (r > c) { const int t = r; r = c; c = t; }
+    const int a = r >> 5, bb = c >> 5;
     const int p = a * rb - a * (a - 1) / 2 + (bb - a);
-    S[e] = gram[p * 1024 + (i & 31) * 32 + (j & 31)];
+    return gram[p * 1024 + (r & 31) * 32 + (c & 31)];
+  };
+  if (j < m) {
+    double dd = S(i, i) + S(j, j) - 2.0 * S(i, j);
+    dd = dd < 0.0 ? 0.0 : dd;
+    dist[j] = (j == i) ? __builtin_inf() : dd;   // the row itself is never a neighbour
   }
   __syncthreads();
-  const int keep = m - b - 2;
-  for (int i = threadIdx.x; i < m; i += blockDim.x) {
-    // sum of the `keep` smallest squared distances to the others: selection by repeated minimum
-    // over a used-mask (m <= 128: two 64-bit words)
-    unsigned long long used0 = 0, used1 = 0;
-    double total = 0.0;
-    const double sii = S[tri(i, i)];
-    for (int r = 0; r < keep; ++r) {
-      double best = __builtin_inf();
-      int bj = -1;
-      for (int j = 0; j < m; ++j) {
-        if (j == i) continue;
-        const bool u = j < 64 ? ((used0 >> j) & 1ull) : ((used1 >> (j - 64)) & 1ull);
-        if (u) continue;
-        const double sij = i <= j ? S[tri(i, j)] : S[tri(j, i)];
-        double dist = sii + S[tri(j, j)] - 2.0 * sij;
-        dist = dist < 0.0 ? 0.0 : dist;
-        if (dist < best) { best = dist; bj = j; }
-      }
-      if (bj < 0) break;
-      if (bj < 64) used0 |= 1ull << bj; else used1 |= 1ull << (bj - 64);
-      total += best;
+  if (j < m) {
+    const double dj = dist[j];
+    int rank = 0;
+    for (int k = 0; k < m; ++k) {
+      const double dk = dist[k];
+      rank += (dk < dj) || (dk == dj && k < j);
     }
-    score[i] = total;
+    sorted[rank] = dj;
+  }
+  __syncthreads();
+  if (j == 0) {
+    double total = 0.0;
+    for (int r = 0; r < m - b - 2; ++r) total += sorted[r];
+    score64[i] = total;
     if (scores_out != nullptr) scores_out[i] = (float)total;
   }
-  __syncthreads();
-  if (threadIdx.x == 0) {
+}
+
+// Winner: smallest score, ties to the lower index.
+__global__ void krum_argmin_kernel(const double* __restrict__ score64, int m, int32_t* __restrict__ chosen) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
     int best = 0;
     for (int i = 1; i < m; ++i)
-      if (score[i] < score[best]) best = i;
+      if (score64[i] < score64[best]) best = i;
     *chosen = best;
   }
 }
@@ -263,7 +257,8 @@ hipError_t launch_gram(const float* G, long long ldg, int m, long long d, float*
 size_t krum_workspace_bytes(int m) {
   const int rb = (m + 31) / 32;
   const size_t entries = (size_t)(rb * (rb + 1) / 2) * 1024;
-  return align_up((size_t)gram_grid(rb) * entries * sizeof(float), 256) + align_up(entries * sizeof(double), 256);
+  return align_up((size_t)gram_grid(rb) * entries * sizeof(float), 256) + align_up(entries * sizeof(double), 256) +
+         align_up(128 * sizeof(double), 256);
 }
 
 hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b, float* out, int32_t* chosen,
@@ -277,21 +272,17 @@ hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b,
   else if (rb == 3) e = launch_gram<3>(G, ldg, m, d, partial, grid, stream);
   else e = launch_gram<4>(G, ldg, m, d, partial, grid, stream);
   if (e != hipSuccess) return e;
-  const int sel_lds = (m * (m + 1) / 2 + m) * (int)sizeof(double);
-  static bool sel_attr = false;
-  if (!sel_attr) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_select_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (128 * 129 / 2 + 128) * (int)sizeof(double));
-    if (e != hipSuccess) return e;
-    sel_attr = true;
-  }
   const int entries = (rb * (rb + 1) / 2) * 1024;
   double* gram = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(workspace) +
                                            align_up((size_t)grid * entries * sizeof(float), 256));
   hipLaunchKernelGGL(krum_reduce_kernel, dim3((entries + 255) / 256), dim3(256), 0, stream, partial, grid, entries, gram);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(krum_select_kernel, dim3(1), dim3(256), sel_lds, stream, gram, rb, m, b, chosen, scores_out);
+  double* score64 = gram + align_up((size_t)entries * sizeof(double), 256) / sizeof(double);
+  hipLaunchKernelGGL(krum_score_kernel, dim3(m), dim3(128), 0, stream, gram, rb, m, b, score64, scores_out);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(krum_argmin_kernel, dim3(1), dim3(64), 0, stream, score64, m, chosen);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   long long want = (d + 255) / 256;
