@@ -413,6 +413,40 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       }
     }
   };
+  // The same for the 1 KB pieces this wave copied itself.  When the H pieces and the D
+  // pieces of a chunk fall to the same waves (A_KB a multiple of NW: piece q and piece
+  // q + A_KB are both copied by wave q % NW), a wave can rebuild its pieces as soon as
+  // its own copies have landed, before the barrier that publishes the buffer, and the
+  // chunk needs one barrier instead of two.
+  constexpr bool OWN_PIECES = (A_KB % NW) == 0;
+  auto rebuild_own = [&](int buf) __attribute__((always_inline)) {
+    unsigned char* bh = lds + buf * AD_BYTES;
+    const unsigned char* bd = bh + A_BYTES;
+    constexpr int PER = A_KB / NW > 0 ? A_KB / NW : 1;
+    f32x4 hraw[PER], draw[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int off = (wave + q * NW) * 1024 + lane * 16;
+      hraw[q] = *reinterpret_cast<const f32x4*>(bh + off);
+      draw[q] = *reinterpret_cast<const f32x4*>(bd + off);
+    }
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int off = (wave + q * NW) * 1024 + lane * 16;
+      f32x4 out;
+      if (BF16) {
+        const bf16x8 hv = __builtin_bit_cast(bf16x8, hraw[q]), dv = __builtin_bit_cast(bf16x8, draw[q]);
+        bf16x8 r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = (__bf16)__builtin_fmaf(neg_gamma, (float)dv[e], (float)hv[e]);
+        out = __builtin_bit_cast(f32x4, r);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = __builtin_fmaf(neg_gamma, draw[q][e], hraw[q][e]);
+      }
+      *reinterpret_cast<f32x4*>(bh + off) = out;
+    }
+  };
   auto load_W = [&](f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < WREGS; ++r)
@@ -458,6 +492,10 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       } else {
         wait_vmcnt<0>();
       }
+      if (SECOND && OWN_PIECES) {
+        asm volatile("" ::: "memory");  // the compiler must not move these LDS reads above the wait
+        rebuild_own(buf);               // this wave's own pieces have landed
+      }
       if (KS == 1) {
         __syncthreads();  // copies of every wave have landed; everyone is done with buffer buf^1
       } else {
@@ -472,7 +510,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       __syncthreads();
     }
     if (STEADY || c + 2 < c_end) load_tile<MODE, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
-    if (SECOND) {
+    if (SECOND && !(DBUF && OWN_PIECES)) {
       rebuild_H(buf);   // behind the tile requests, so that it does not delay them
       __syncthreads();
     }
