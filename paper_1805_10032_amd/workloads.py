@@ -14,7 +14,10 @@ no longer fits in cache.  They stand in for CIFAR-10, which is not used.
 
 Fault injectors (Section 3, Definition 1; Section 6.4): a large negative multiple
 of the honest mean copied over all faulty rows ("sign flip"), and independent
-large-variance Gaussian rows ("noise").
+large-variance Gaussian rows ("noise").  worker_gradients() produces one
+iteration's candidates of a training loop under the failures of Section 6:
+label flipping (6.3), bit flipping (6.4), a scaled sign flip, and workers that
+draw from disjoint shards of the data (6.5).
 """
 from __future__ import annotations
 
@@ -111,6 +114,55 @@ def minibatch_gradient(x, dims, has_bias, loss, features, labels=None, targets=N
         val = 0.5 * torch.mean((h[:, 0] - targets) ** 2)
     val.backward()
     return p.grad.detach()
+
+
+ATTACKS = ("none", "sign_flip", "bit_flip", "label_flip")
+
+
+def class_sorted_shards(labels, m):
+    """Disjoint local datasets (Section 6.5): sample indices sorted by label and cut into m
+    equal shards, so each worker sees only a few classes.  Returns an [m x shard] index tensor."""
+    order = torch.argsort(labels.long(), stable=True)
+    shard = order.numel() // m
+    return order[: m * shard].view(m, shard)
+
+
+def worker_gradients(G, x, dims, has_bias, features, labels, faulty, attack, gen, *, batch=32, scale=4.0,
+                     shards=None):
+    """Fill G[i] with worker i's candidate for one iteration of Algorithm 1 (worker side).
+
+    Every worker takes the softmax-CE minibatch gradient at x on `batch` samples drawn with
+    replacement from the whole data set, or from its own row of `shards` when given.  Workers
+    listed in `faulty` fail as `attack` says:
+      label_flip  labels replaced by C-1-label before the gradient is taken (Section 6.3);
+      bit_flip    the negated gradient, and the first faulty worker's value overwrites the
+                  other faulty rows, so all faulty rows are identical (Section 6.4);
+      sign_flip   -scale times the worker's own gradient (the enlarged-magnitude case the
+                  discussion in Section 6.7 points to);
+      none        no failure.
+    """
+    if attack not in ATTACKS:
+        raise ValueError(f"attack must be one of {ATTACKS}")
+    faulty = list(faulty)
+    bad = set(faulty)
+    n, C, dev = features.shape[0], dims[-1], features.device
+    for i in range(G.shape[0]):
+        if shards is not None:
+            idx = shards[i][torch.randint(0, shards.shape[1], (batch,), generator=gen, device=dev)]
+        else:
+            idx = torch.randint(0, n, (batch,), generator=gen, device=dev)
+        lab = labels[idx]
+        if i in bad and attack == "label_flip":
+            lab = (C - 1 - lab).to(lab.dtype)
+        gi = minibatch_gradient(x, dims, has_bias, "softmax_ce", features[idx], lab)
+        if i in bad and attack == "sign_flip":
+            gi = -scale * gi
+        elif i in bad and attack == "bit_flip":
+            gi = -gi
+        G[i] = gi
+    if attack == "bit_flip":
+        for i in faulty[1:]:
+            G[i] = G[faulty[0]]
 
 
 def _draw_batch(dims, loss, n, gen, device, feat="normal"):

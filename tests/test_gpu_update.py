@@ -131,3 +131,62 @@ def test_training_loop_zeno_descends_where_mean_and_median_ascend(B):
           f"median {final['median']:.3f}")
     assert final["zeno"] < 0.7 * start
     assert not (final["mean"] < start) and not (final["median"] < start)     # risen, or overflowed to inf/NaN
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("attack,disjoint", [("bit_flip", False), ("label_flip", False), ("label_flip", True)])
+def test_training_loop_under_the_failures_of_section_6(B, attack, disjoint):
+    """Algorithm 1 with q = 12 of m = 20 workers failing as Sections 6.3-6.5 describe, every
+    server-side rule in the HIP library (Zeno with b = 12, Mean, Median, Krum with b = 12).
+    What is asserted is what those sections claim and what the oracle's run of this recipe
+    shows over several seeds (start 3.14; Zeno 1.46-1.55 i.i.d. and 1.83-1.93 on disjoint data):
+      bit flipping            Zeno descends, the three baselines end above where they started;
+      label flipping          Zeno descends and ends below Mean and Median;
+      label flipping on       Zeno descends and ends below Median and Krum (Mean is within
+      disjoint data           noise of Zeno there and is only printed).
+    Teacher-labelled synthetic data stands in for CIFAR-10."""
+    dev = torch.device("cuda")
+    dims, m, q, b, n_r, gamma, rho, T = [48, 64, 10], 20, 12, 12, 32, 0.1, 5e-4, 80
+    feats, labels = _teacher_task(7, dims, 8192, dev)
+    shards = WL.class_sorted_shards(labels, m) if disjoint else None
+    mdl = B.ZenoModel(dims, True, "softmax_ce", "fp32")
+    d = mdl.num_params
+
+    def full_loss(x):
+        h = feats
+        layers = WL._views(x, dims, True)
+        for l, (W, bias) in enumerate(layers):
+            h = torch.nn.functional.linear(h, W, bias)
+            if l + 1 < len(layers):
+                h = torch.relu(h)
+        return float(torch.nn.functional.cross_entropy(h, labels.long()))
+
+    x0 = WL.init_params(dims, True, torch.Generator().manual_seed(1), torch.device("cpu"), "he").to(dev)
+    start = full_loss(x0)
+    final = {}
+    for rule in ("zeno", "mean", "median", "krum"):
+        gen = torch.Generator(device=dev).manual_seed(3)
+        x = x0.clone()
+        G = B.alloc_candidates(m, d, dev)
+        ws = B.alloc_workspace(mdl, m, n_r, dev)
+        for t in range(T):
+            faulty = torch.randperm(m, generator=gen, device=dev)[:q].tolist()
+            WL.worker_gradients(G, x, dims, True, feats, labels, faulty, attack, gen, shards=shards)
+            if rule == "zeno":
+                idx = torch.randint(0, feats.shape[0], (n_r,), generator=gen, device=dev)
+                s = B.zeno_score(mdl, x, G, feats[idx].contiguous(), gamma, rho, labels=labels[idx].contiguous(),
+                                 workspace=ws)
+                B.zeno_aggregate_update(G, s, b, gamma, x, x_next=x, want_out=False, want_selected=False)
+            else:
+                v = B.zeno_mean(G) if rule == "mean" else B.zeno_median(G) if rule == "median" else B.zeno_krum(G, b)[0]
+                x = x - gamma * v
+        final[rule] = full_loss(x)
+    print(f"{attack}{' disjoint' if disjoint else ''}: start {start:.3f}  " +
+          "  ".join(f"{k} {v:.3f}" for k, v in final.items()))
+    assert final["zeno"] < 0.7 * start
+    if attack == "bit_flip":
+        assert all(not (final[r] < start) for r in ("mean", "median", "krum"))
+    elif not disjoint:
+        assert final["zeno"] < final["mean"] - 0.1 and final["zeno"] < final["median"] - 0.1
+    else:
+        assert final["zeno"] < final["median"] - 0.1 and final["zeno"] < final["krum"] - 0.1
