@@ -3,12 +3,21 @@
 // keeps its values in registers as order-preserving integer keys.
 //
 // Only the middle of the order is needed, so no full sort is done: the m keys
-// are padded to a compile-time width P with equally many -inf and +inf keys
-// (one more +inf when P-m is odd), which pins the median to positions P/2-1 (m
-// odd) or P/2-1 and P/2 (m even) of the sorted order.  The two halves are sorted
-// by bitonic networks; one half-cleaner step min/max(a_i, b_{P/2-1-i}) then
-// separates the P/2 smallest from the P/2 largest keys, and the two middle
-// elements are the maximum of the former and the minimum of the latter.
+// are padded to a power of two P with equally many -inf and +inf keys (one more
+// +inf when P-m is odd), which pins the median to positions P/2-1 (m odd) or
+// P/2-1 and P/2 (m even) of the sorted order.  The two halves are sorted by
+// Batcher's odd-even merge sort (every compare-exchange ascending); one
+// half-cleaner step min/max(a_i, b_{P/2-1-i}) then separates the P/2 smallest
+// from the P/2 largest keys, and the two middle elements are the maximum of the
+// former and the minimum of the latter.
+//
+// Most of the padding sits at positions fixed at compile time: the kernel is
+// instantiated for Q real slots (m rounded up to a multiple of 8), the lowest
+// (P-Q)/2 positions of the first half hold the constant -inf key and the
+// highest (P-Q)/2 of the second half the constant +inf key.  An ascending
+// compare-exchange never moves those, so after unrolling the compiler deletes
+// every compare-exchange that touches one: the network that runs is the one for
+// Q keys, not for P.  The Q-m slots left over are padded at run time.
 #include <limits.h>
 
 #include "zeno_internal.h"
@@ -30,54 +39,62 @@ __device__ inline float key_float(int k) {
   return __int_as_float(k ^ ((k >> 31) & 0x7fffffff));
 }
 
-// Ascending bitonic sort of v[0..H), fully unrolled (H is a power of two).
+// Ascending odd-even merge sort of v[0..H), fully unrolled (H is a power of two).
 template <int H>
 __device__ inline void sort_regs(int (&v)[H]) {
 #pragma unroll
-  for (int k = 2; k <= H; k <<= 1) {
+  for (int p = 1; p < H; p <<= 1) {
 #pragma unroll
-    for (int s = k >> 1; s > 0; s >>= 1) {
+    for (int k = p; k >= 1; k >>= 1) {
 #pragma unroll
-      for (int i = 0; i < H; ++i) {
-        const int l = i ^ s;
-        if (l > i) {
-          const int a = v[i], c = v[l];
-          const int mn = a < c ? a : c, mx = a < c ? c : a;
-          const bool up = (i & k) == 0;
-          v[i] = up ? mn : mx;
-          v[l] = up ? mx : mn;
+      for (int j = k % p; j + k < H; j += 2 * k) {
+#pragma unroll
+        for (int i = 0; i < k; ++i) {
+          const int lo = i + j, hi = i + j + k;
+          if (hi < H && lo / (2 * p) == hi / (2 * p)) {
+            const int a = v[lo], c = v[hi];
+            v[lo] = a < c ? a : c;
+            v[hi] = a < c ? c : a;
+          }
         }
       }
     }
   }
 }
 
-template <int P>
+template <int P, int Q>
 __global__ __launch_bounds__(kThreads) void median_kernel(const float* __restrict__ G, int m, long long d,
                                                           long long ldg, float* __restrict__ out) {
   constexpr int H = P / 2;
+  constexpr int C = (P - Q) / 2;  // constant keys per half
+  static_assert(P == Q || (Q % 8 == 0 && Q < P && Q > P / 2), "Q real slots, more than half of P");
   const long long stride = (long long)gridDim.x * kThreads;
-  const int f = (P - m) / 2;  // -inf keys in front; the rest of the padding is +inf keys behind
+  const int f = (Q - m) / 2;  // run-time -inf keys; the rest of the run-time padding is +inf keys
   for (long long j = (long long)blockIdx.x * kThreads + threadIdx.x; j < d; j += stride) {
     int a[H], b[H];
-    // All P loads are issued back to back without branches: slot i reads row
+    // All Q loads are issued back to back without branches: slot i reads row
     // min(i, m-1); the slots beyond m re-read the last row (cached) and are
     // overwritten by padding keys.  The address is kept as a per-lane pointer that
     // is stepped row by row (the empty asm keeps it in vector registers; a table
-    // of P wave-uniform row addresses would not fit the scalar register file).
+    // of wave-uniform row addresses would not fit the scalar register file).
     const float* p = G + j;
-    float val[P];
+    float val[Q];
 #pragma unroll
-    for (int i = 0; i < P; ++i) {
+    for (int i = 0; i < Q; ++i) {
       val[i] = *p;
       p += (i + 1 < m) ? ldg : 0;
       asm volatile("" : "+v"(p));
     }
 #pragma unroll
-    for (int i = 0; i < P; ++i) {
-      // padding: the first f padding slots sort below everything, the rest above
+    for (int i = 0; i < C; ++i) {
+      a[i] = INT_MIN;
+      b[H - 1 - i] = INT_MAX;
+    }
+#pragma unroll
+    for (int i = 0; i < Q; ++i) {
+      // run-time padding: the first f padding slots sort below everything, the rest above
       const int key = (i < m) ? float_key(val[i]) : (i - m < f ? INT_MIN : INT_MAX);
-      if (i < H) a[i] = key; else b[i - H] = key;
+      if (i < H - C) a[C + i] = key; else b[i - (H - C)] = key;
     }
     sort_regs<H>(a);
     sort_regs<H>(b);
@@ -94,12 +111,35 @@ __global__ __launch_bounds__(kThreads) void median_kernel(const float* __restric
   }
 }
 
-template <int P>
-hipError_t launch_p(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream) {
+template <int P, int Q>
+hipError_t launch_pq(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream) {
   long long want = (d + kThreads - 1) / kThreads;
   int grid = (int)(want < 1 ? 1 : (want > 256 * 32 ? 256 * 32 : want));
-  hipLaunchKernelGGL(median_kernel<P>, dim3(grid), dim3(kThreads), 0, stream, G, m, d, ldg, out);
+  hipLaunchKernelGGL((median_kernel<P, Q>), dim3(grid), dim3(kThreads), 0, stream, G, m, d, ldg, out);
   return hipGetLastError();
+}
+
+// Q = m rounded up to a multiple of 8 inside (P/2, P].
+template <int P>
+hipError_t launch_p(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream) {
+  if constexpr (P >= 64) {
+    switch ((m + 7) / 8 * 8 - P / 2) {
+      case 8: return launch_pq<P, P / 2 + 8>(G, ldg, m, d, out, stream);
+      case 16: return launch_pq<P, P / 2 + 16>(G, ldg, m, d, out, stream);
+      case 24: return launch_pq<P, P / 2 + 24>(G, ldg, m, d, out, stream);
+      case 32: return launch_pq<P, P / 2 + 32>(G, ldg, m, d, out, stream);
+      default: break;
+    }
+    if constexpr (P >= 128) {
+      switch ((m + 7) / 8 * 8 - P / 2) {
+        case 40: return launch_pq<P, P / 2 + 40>(G, ldg, m, d, out, stream);
+        case 48: return launch_pq<P, P / 2 + 48>(G, ldg, m, d, out, stream);
+        case 56: return launch_pq<P, P / 2 + 56>(G, ldg, m, d, out, stream);
+        default: break;
+      }
+    }
+  }
+  return launch_pq<P, P>(G, ldg, m, d, out, stream);
 }
 
 }  // namespace
