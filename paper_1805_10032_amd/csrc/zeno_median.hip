@@ -12,7 +12,7 @@
 // former and the minimum of the latter.
 //
 // Most of the padding sits at positions fixed at compile time: the kernel is
-// instantiated for Q real slots (m rounded up to a multiple of 8), the lowest
+// instantiated for Q real slots (m rounded up to a multiple of 4, of 8 above 64), the lowest
 // (P-Q)/2 positions of the first half hold the constant -inf key and the
 // highest (P-Q)/2 of the second half the constant +inf key.  An ascending
 // compare-exchange never moves those, so after unrolling the compiler deletes
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kThreads) void median_kernel(const float* __restric
                                                           long long ldg, float* __restrict__ out) {
   constexpr int H = P / 2;
   constexpr int C = (P - Q) / 2;  // constant keys per half
-  static_assert(P == Q || (Q % 8 == 0 && Q < P && Q > P / 2), "Q real slots, more than half of P");
+  static_assert(P == Q || (Q % 4 == 0 && Q < P && Q > P / 2), "Q real slots, more than half of P");
   const long long stride = (long long)gridDim.x * kThreads;
   const int f = (Q - m) / 2;  // run-time -inf keys; the rest of the run-time padding is +inf keys
   for (long long j = (long long)blockIdx.x * kThreads + threadIdx.x; j < d; j += stride) {
@@ -85,18 +85,22 @@ __global__ __launch_bounds__(kThreads) void median_kernel(const float* __restric
       p += (i + 1 < m) ? ldg : 0;
       asm volatile("" : "+v"(p));
     }
-#pragma unroll
-    for (int i = 0; i < C; ++i) {
-      a[i] = INT_MIN;
-      b[H - 1 - i] = INT_MAX;
-    }
-#pragma unroll
-    for (int i = 0; i < Q; ++i) {
+    // First half: its keys are ready when the first Q/2 loads have landed, so
+    // its sort overlaps the rest of the loads (the fence keeps that order).
+    auto slot_key = [&](int i) {
       // run-time padding: the first f padding slots sort below everything, the rest above
-      const int key = (i < m) ? float_key(val[i]) : (i - m < f ? INT_MIN : INT_MAX);
-      if (i < H - C) a[C + i] = key; else b[i - (H - C)] = key;
-    }
+      return (i < m) ? float_key(val[i]) : (i - m < f ? INT_MIN : INT_MAX);
+    };
+#pragma unroll
+    for (int i = 0; i < C; ++i) a[i] = INT_MIN;
+#pragma unroll
+    for (int i = 0; i < H - C; ++i) a[C + i] = slot_key(i);
     sort_regs<H>(a);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < C; ++i) b[H - 1 - i] = INT_MAX;
+#pragma unroll
+    for (int i = H - C; i < Q; ++i) b[i - (H - C)] = slot_key(i);
     sort_regs<H>(b);
     int lo = INT_MIN, hi = INT_MAX;
 #pragma unroll
@@ -119,27 +123,25 @@ hipError_t launch_pq(const float* G, long long ldg, int m, long long d, float* o
   return hipGetLastError();
 }
 
-// Q = m rounded up to a multiple of 8 inside (P/2, P].
+// Q = m rounded up to a multiple of kStep inside (P/2, P]: 4 up to P = 64, 8 for P = 128.
+template <int P, int Q>
+hipError_t launch_q(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream) {
+  constexpr int kStep = P > 64 ? 8 : 4;
+  if constexpr (Q >= P) {
+    return launch_pq<P, P>(G, ldg, m, d, out, stream);
+  } else {
+    if (m <= Q) return launch_pq<P, Q>(G, ldg, m, d, out, stream);
+    return launch_q<P, Q + kStep>(G, ldg, m, d, out, stream);
+  }
+}
+
 template <int P>
 hipError_t launch_p(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream) {
-  if constexpr (P >= 64) {
-    switch ((m + 7) / 8 * 8 - P / 2) {
-      case 8: return launch_pq<P, P / 2 + 8>(G, ldg, m, d, out, stream);
-      case 16: return launch_pq<P, P / 2 + 16>(G, ldg, m, d, out, stream);
-      case 24: return launch_pq<P, P / 2 + 24>(G, ldg, m, d, out, stream);
-      case 32: return launch_pq<P, P / 2 + 32>(G, ldg, m, d, out, stream);
-      default: break;
-    }
-    if constexpr (P >= 128) {
-      switch ((m + 7) / 8 * 8 - P / 2) {
-        case 40: return launch_pq<P, P / 2 + 40>(G, ldg, m, d, out, stream);
-        case 48: return launch_pq<P, P / 2 + 48>(G, ldg, m, d, out, stream);
-        case 56: return launch_pq<P, P / 2 + 56>(G, ldg, m, d, out, stream);
-        default: break;
-      }
-    }
+  if constexpr (P >= 16) {
+    return launch_q<P, P / 2 + (P > 64 ? 8 : 4)>(G, ldg, m, d, out, stream);
+  } else {
+    return launch_pq<P, P>(G, ldg, m, d, out, stream);
   }
-  return launch_pq<P, P>(G, ldg, m, d, out, stream);
 }
 
 }  // namespace
