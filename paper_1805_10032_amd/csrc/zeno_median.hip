@@ -19,6 +19,7 @@
 // every compare-exchange that touches one: the network that runs is the one for
 // Q keys, not for P.  The Q-m slots left over are padded at run time.
 #include <limits.h>
+#include <stdint.h>
 
 #include "zeno_internal.h"
 
@@ -62,65 +63,106 @@ __device__ inline void sort_regs(int (&v)[H]) {
   }
 }
 
-template <int P, int Q>
+template <int P, int Q, int VEC, bool NT>
 __global__ __launch_bounds__(kThreads) void median_kernel(const float* __restrict__ G, int m, long long d,
                                                           long long ldg, float* __restrict__ out) {
+  typedef float vf __attribute__((ext_vector_type(VEC)));
   constexpr int H = P / 2;
   constexpr int C = (P - Q) / 2;  // constant keys per half
   static_assert(P == Q || (Q % 4 == 0 && Q < P && Q > P / 2), "Q real slots, more than half of P");
   const long long stride = (long long)gridDim.x * kThreads;
-  const int f = (Q - m) / 2;  // run-time -inf keys; the rest of the run-time padding is +inf keys
-  for (long long j = (long long)blockIdx.x * kThreads + threadIdx.x; j < d; j += stride) {
-    int a[H], b[H];
+  const long long n_vec = d / VEC;  // the launcher sends the d % VEC columns left over to the VEC = 1 kernel
+  const int f = (Q - m) / 2;        // run-time -inf keys; the rest of the run-time padding is +inf keys
+  for (long long j = (long long)blockIdx.x * kThreads + threadIdx.x; j < n_vec; j += stride) {
+    // Each lane owns VEC adjacent columns and reads them with one load per row.
     // All Q loads are issued back to back without branches: slot i reads row
     // min(i, m-1); the slots beyond m re-read the last row (cached) and are
     // overwritten by padding keys.  The address is kept as a per-lane pointer that
     // is stepped row by row (the empty asm keeps it in vector registers; a table
     // of wave-uniform row addresses would not fit the scalar register file).
-    const float* p = G + j;
-    float val[Q];
+    const float* p = G + j * VEC;
+    vf val[Q];
 #pragma unroll
     for (int i = 0; i < Q; ++i) {
-      val[i] = *p;
+      if constexpr (NT) {
+        val[i] = __builtin_nontemporal_load(reinterpret_cast<const vf*>(p));
+      } else {
+        val[i] = *reinterpret_cast<const vf*>(p);
+      }
       p += (i + 1 < m) ? ldg : 0;
       asm volatile("" : "+v"(p));
     }
-    // First half: its keys are ready when the first Q/2 loads have landed, so
-    // its sort overlaps the rest of the loads (the fence keeps that order).
-    auto slot_key = [&](int i) {
-      // run-time padding: the first f padding slots sort below everything, the rest above
-      return (i < m) ? float_key(val[i]) : (i - m < f ? INT_MIN : INT_MAX);
-    };
+    vf res;
 #pragma unroll
-    for (int i = 0; i < C; ++i) a[i] = INT_MIN;
+    for (int v = 0; v < VEC; ++v) {
+      int a[H], b[H];
+      auto slot_key = [&](int i) {
+        // run-time padding: the first f padding slots sort below everything, the rest above
+        return (i < m) ? float_key(val[i][v]) : (i - m < f ? INT_MIN : INT_MAX);
+      };
 #pragma unroll
-    for (int i = 0; i < H - C; ++i) a[C + i] = slot_key(i);
-    sort_regs<H>(a);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int i = 0; i < C; ++i) a[i] = INT_MIN;
 #pragma unroll
-    for (int i = 0; i < C; ++i) b[H - 1 - i] = INT_MAX;
+      for (int i = 0; i < H - C; ++i) a[C + i] = slot_key(i);
 #pragma unroll
-    for (int i = H - C; i < Q; ++i) b[i - (H - C)] = slot_key(i);
-    sort_regs<H>(b);
-    int lo = INT_MIN, hi = INT_MAX;
+      for (int i = 0; i < C; ++i) b[H - 1 - i] = INT_MAX;
 #pragma unroll
-    for (int i = 0; i < H; ++i) {
-      const int x = a[i], y = b[H - 1 - i];
-      const int mn = x < y ? x : y, mx = x < y ? y : x;
-      lo = lo > mn ? lo : mn;
-      hi = hi < mx ? hi : mx;
+      for (int i = H - C; i < Q; ++i) b[i - (H - C)] = slot_key(i);
+      sort_regs<H>(a);
+      sort_regs<H>(b);
+      int lo = INT_MIN, hi = INT_MAX;
+#pragma unroll
+      for (int i = 0; i < H; ++i) {
+        const int x = a[i], y = b[H - 1 - i];
+        const int mn = x < y ? x : y, mx = x < y ? y : x;
+        lo = lo > mn ? lo : mn;
+        hi = hi < mx ? hi : mx;
+      }
+      const float fa = key_float(lo), fb = key_float(hi);
+      const float r = (m & 1) ? fa : (float)(0.5 * ((double)fa + (double)fb));
+      res[v] = r;
     }
-    const float fa = key_float(lo), fb = key_float(hi);
-    out[j] = (m & 1) ? fa : (float)(0.5 * ((double)fa + (double)fb));
+    *reinterpret_cast<vf*>(out + j * VEC) = res;
   }
 }
 
+// Rows that start on cache-line boundaries are read with streaming (nontemporal)
+// loads when m is small: every line is used once by one wave, and at small m the
+// kernel is bound by the loads alone.  Rows that straddle lines keep ordinary loads,
+// which let the neighbouring wave find the shared line in cache.
+template <int P, int Q, int VEC>
+hipError_t launch_vec(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream) {
+  long long want = (d / VEC + kThreads - 1) / kThreads;
+  int grid = (int)(want < 1 ? 1 : (want > 256 * 32 ? 256 * 32 : want));
+  if constexpr (Q <= 48) {
+    if (ldg % 32 == 0 && reinterpret_cast<uintptr_t>(G) % 128 == 0) {
+      hipLaunchKernelGGL((median_kernel<P, Q, VEC, true>), dim3(grid), dim3(kThreads), 0, stream, G, m, d, ldg, out);
+      return hipGetLastError();
+    }
+  }
+  hipLaunchKernelGGL((median_kernel<P, Q, VEC, false>), dim3(grid), dim3(kThreads), 0, stream, G, m, d, ldg, out);
+  return hipGetLastError();
+}
+
+// Lanes take kVec<Q> columns each when every row and the output are aligned for
+// that load width; the d % VEC columns left over go to the one-column kernel.
+template <int Q>
+constexpr int kVecFor = Q <= 32 ? 4 : 1;
+
 template <int P, int Q>
 hipError_t launch_pq(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream) {
-  long long want = (d + kThreads - 1) / kThreads;
-  int grid = (int)(want < 1 ? 1 : (want > 256 * 32 ? 256 * 32 : want));
-  hipLaunchKernelGGL((median_kernel<P, Q>), dim3(grid), dim3(kThreads), 0, stream, G, m, d, ldg, out);
-  return hipGetLastError();
+  constexpr int VEC = kVecFor<Q>;
+  if constexpr (VEC > 1) {
+    const bool aligned = ldg % VEC == 0 && reinterpret_cast<uintptr_t>(G) % (4 * VEC) == 0 &&
+                         reinterpret_cast<uintptr_t>(out) % (4 * VEC) == 0;
+    if (aligned && d >= VEC) {
+      hipError_t e = launch_vec<P, Q, VEC>(G, ldg, m, d, out, stream);
+      const long long done = d / VEC * VEC;
+      if (e != hipSuccess || done == d) return e;
+      return launch_vec<P, Q, 1>(G + done, ldg, m, d - done, out + done, stream);
+    }
+  }
+  return launch_vec<P, Q, 1>(G, ldg, m, d, out, stream);
 }
 
 // Q = m rounded up to a multiple of kStep inside (P/2, P]: 4 up to P = 64, 8 for P = 128.
