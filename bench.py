@@ -172,9 +172,9 @@ def main():
         e[2] += nbytes
     # the baseline aggregators on the same G (Section 6.1.1, Definitions 4 and 5), and the variant of
     # the aggregation that also takes the server's SGD step (Algorithm 1), in place on a copy of x
-    B.profile_enable(True)
     x_step = w.x.clone()
-    for i in range(3):
+    for i in range(-1, 3):                             # the first pass is an unrecorded warm-up
+        B.profile_enable(i >= 0)
         B.zeno_mean(Gs[i % n_buf], out=out)
         B.zeno_median(Gs[i % n_buf], out=out)
         B.zeno_aggregate_update(Gs[i % n_buf], scores, b, w.gamma, x_step, x_next=x_step, want_out=False,
