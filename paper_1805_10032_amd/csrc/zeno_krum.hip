@@ -1,7 +1,13 @@
 // Krum_b (Definition 5): the candidate with the smallest sum of squared distances to
 // its m-b-2 nearest neighbours.  The O(d m^2) part is the Gram matrix S = G G^T, taken
-// in one pass over G on the fp32 matrix cores (v_mfma_f32_32x32x2_f32); the squared
-// distances follow as S_ii + S_jj - 2 S_ij.
+// in one pass over G on the bf16 matrix cores at float32 accuracy: every float is split
+// into three bf16 pieces x = h + m + l (round to nearest each, |m| <= 2^-8 |x|,
+// |l| <= 2^-17 |x|) and the six piece products down to 2^-17 of the leading one
+// (hh, hm, mh, mm, hl, lh) are accumulated in float32 (v_mfma_f32_32x32x16_bf16); what is
+// dropped (ml, lm, ll and the split's remainder) is about 2^-24 of |x||y| per product,
+// the size of one float32 rounding.  Six of these instructions cover 16
+// columns in 192 cycles where the fp32 instruction (v_mfma_f32_32x32x2_f32) needs 512.
+// The squared distances follow as S_ii + S_jj - 2 S_ij.
 //
 // krum_gram_kernel<RB>: the m <= 32 RB rows are cut into RB row blocks.  A wave owns a
 // contiguous range of 64-column chunks; per chunk it loads the RB tiles of 32 rows x 64
@@ -20,8 +26,22 @@ namespace {
 
 constexpr int kGramWaves = 4;
 
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+
+// Three-way split of eight floats into bf16 pieces, x = h + m + l + (at most 2^-25 |x|):
+// h = bf16(x), m = bf16(x - h), l = bf16(x - h - m), round to nearest even each time;
+// both subtractions are exact.
+__device__ inline void split3(const f32x4& v0, const f32x4& v1, bf16x8& h, bf16x8& m, bf16x8& l) {
+  const f32x8 x = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+  h = __builtin_convertvector(x, bf16x8);
+  const f32x8 r1 = x - __builtin_convertvector(h, f32x8);
+  m = __builtin_convertvector(r1, bf16x8);
+  const f32x8 r2 = r1 - __builtin_convertvector(m, f32x8);
+  l = __builtin_convertvector(r2, bf16x8);
+}
+
 template <int RB>
-__global__ __launch_bounds__(64 * kGramWaves) void krum_gram_kernel(const float* __restrict__ G, long long ldg,
+__global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) void krum_gram_kernel(const float* __restrict__ G, long long ldg,
                                                                     int m, long long d, float* __restrict__ partial) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   constexpr int PAIRS = RB * (RB + 1) / 2;
@@ -70,20 +90,31 @@ __global__ __launch_bounds__(64 * kGramWaves) void krum_gram_kernel(const float*
   auto products = [&](const f32x4 (&u)[RB][8]) __attribute__((always_inline)) {
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) stage_tile<false>(u[rb], st + rb * TILE_BYTES, lane);
-    // operand fragments: lane (n, h) reads row n, columns 8t + 4h .. + 3 of each tile
+    // operand fragments: per 16-column step s, lane (n, h) reads row n, columns
+    // 16 s + 8 h .. + 7 of each tile and splits them into three bf16 pieces
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      f32x4 f[RB];
+    for (int s = 0; s < 4; ++s) {
+      bf16x8 fh[RB], fm[RB], fl[RB];
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        f[rb] = *reinterpret_cast<const f32x4*>(st + rb * TILE_BYTES + n * 256 + ((((2 * t + h) ^ n) & 15) << 4));
+      for (int rb = 0; rb < RB; ++rb) {
+        const unsigned char* row = st + rb * TILE_BYTES + n * 256;
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(row + ((((4 * s + 2 * h) ^ n) & 15) << 4));
+        const f32x4 v1 = *reinterpret_cast<const f32x4*>(row + ((((4 * s + 2 * h + 1) ^ n) & 15) << 4));
+        split3(v0, v1, fh[rb], fm[rb], fl[rb]);
+      }
       int p = 0;
 #pragma unroll
       for (int a = 0; a < RB; ++a)
 #pragma unroll
-        for (int b = a; b < RB; ++b, ++p)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) acc[p] = __builtin_amdgcn_mfma_f32_32x32x2f32(f[a][e], f[b][e], acc[p], 0, 0, 0);
+        for (int b = a; b < RB; ++b, ++p) {
+          const bf16x8 ah = fh[a], am = fm[a], al = fl[a], bh = fh[b], bm = fm[b], bl = fl[b];
+          acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc[p], 0, 0, 0);
+          acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc[p], 0, 0, 0);
+          acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bm, acc[p], 0, 0, 0);
+          acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bh, acc[p], 0, 0, 0);
+          acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bm, acc[p], 0, 0, 0);
+          acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc[p], 0, 0, 0);
+        }
     }
   };
 
