@@ -118,7 +118,7 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) voi
     }
   };
 
-  if (RB <= 2) {
+  if (RB <= 3) {
     // one chunk ahead in registers: the loads of chunk c+1 fly while chunk c is multiplied
     if (c_begin < c_end) {
       f32x4 u0[RB][8], u1[RB][8];

@@ -256,17 +256,20 @@ struct Lds {
   static constexpr int TOTAL = BIAS_OFF + NW * 32 * 4;
 };
 
-// KS > 1 (pass at x on its own, NW == 1): the KS waves of a workgroup own the SAME 32
-// features and split the K range between them, each with a private copy of the LDS
-// layout and no barrier inside the loop; the partial accumulators are summed through
-// LDS in a fixed tree order at the end and wave 0 writes the results.  A launch of
-// the pass at x has only N/32 feature tiles, far too few single waves to keep enough
-// loads in flight, and this multiplies them by KS.
+// KS > 1 (launches of one-wave tiles, NW == 1): the KS waves of a workgroup own the SAME
+// 32 features and split the K range between them, each with a private copy of the LDS
+// layout and no barrier inside the loop; the partial accumulators (and the partial
+// squared norms) are summed through LDS in a fixed order at the end and wave 0 writes
+// the results.  A launch of the pass at x has only N/32 feature tiles, and a narrow
+// layer (ten classes) only one tile per candidate: far too few single waves to keep
+// enough loads in flight, and each of them would walk all of K alone, one chunk's
+// latency after the other.  This multiplies the waves by KS and divides the walk.
 template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS>
 __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) {
   static_assert(KS == 1 || NW == 1, "K is only split in one-tile workgroups");
   using T = Tr<BF16>;
   using LD = Lds<BF16, DELTA, MB, NW>;
+  static_assert(KS == 1 || LD::DBUF, "the single-buffer loop has workgroup barriers, which waves with different K ranges cannot share");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
   constexpr int BN = 32 * NW;
   constexpr int A_BYTES = LD::A_BYTES;
@@ -641,6 +644,20 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
           for (int j = 0; j < 16; ++j) acc[mb][j] += red[((kw * MB + mb) * 16 + j) * 64 + lane];
       }
     }
+    if (do_norm) {
+      // the waves' partial squared norms: each wave sums its lanes, wave 0 adds the totals
+      // in wave order and carries the result in lane 0 into the reduction after the epilogue
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
+      double* nred = reinterpret_cast<double*>(lds_all + LD::TOTAL);  // wave 1's layout, idle by now and beyond `red`
+      if (kw != 0 && lane == 0) nred[kw] = nrm;
+      __syncthreads();
+      if (kw == 0) {
+        double t = nrm;
+        for (int w = 1; w < KS; ++w) t += nred[w];
+        nrm = lane == 0 ? t : 0.0;
+      }
+    }
     if (kw != 0) return;
   }
 
@@ -767,14 +784,19 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     // fixed-order reduction: lanes by xor-shuffle tree, then waves in order
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
-    __syncthreads();
-    double* red = reinterpret_cast<double*>(lds);
-    if (lane == 0) red[wave] = nrm;
-    __syncthreads();
-    if (tid == 0) {
-      double t = 0.0;
-      for (int wv = 0; wv < NW; ++wv) t += red[wv];
-      a.norm_partials[(long long)s * a.P + a.p_off + nt] = t;
+    if (KS > 1) {
+      // only wave 0 is left, and it holds the whole tile's sum
+      if (lane == 0) a.norm_partials[(long long)s * a.P + a.p_off + nt] = nrm;
+    } else {
+      __syncthreads();
+      double* red = reinterpret_cast<double*>(lds);
+      if (lane == 0) red[wave] = nrm;
+      __syncthreads();
+      if (tid == 0) {
+        double t = 0.0;
+        for (int wv = 0; wv < NW; ++wv) t += red[wv];
+        a.norm_partials[(long long)s * a.P + a.p_off + nt] = t;
+      }
     }
   }
 }
@@ -859,9 +881,12 @@ constexpr int kSplitK = 4;  // waves that share one feature tile of a lone pass 
 
 template <bool BF16, bool DELTA, int MB, int NW>
 hipError_t launch_nt(const LayerArgs& a, hipStream_t stream) {
-  // A pass at x on its own, one-tile workgroups, a K long enough to split, and LDS for kSplitK private layouts
-  if constexpr (NW == 1 && !DELTA && Lds<BF16, DELTA, MB, 1>::TOTAL * kSplitK <= 160 * 1024) {
-    if (a.n_cand == 0 && a.has_base && (a.bj.Kp >> 6) >= 2 * kSplitK) {
+  // One-tile workgroups, every K of the launch long enough to split, and LDS for kSplitK private
+  // double-buffered layouts
+  if constexpr (NW == 1 && Lds<BF16, DELTA, MB, 1>::DBUF && Lds<BF16, DELTA, MB, 1>::TOTAL * kSplitK <= 160 * 1024) {
+    const bool base_ok = !a.has_base || (a.bj.Kp >> 6) >= 2 * kSplitK;
+    const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * kSplitK;
+    if ((a.has_base || a.n_cand > 0) && base_ok && cand_ok) {
       if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, kSplitK>(a, stream);
       return launch_inst<BF16, DELTA, MB, NW, false, kSplitK>(a, stream);
     }
