@@ -158,7 +158,8 @@ zeno_status_t zeno_median(const float* G, int64_t ldg, int32_t m, int64_t d, flo
 
 /* Krum_b (Definition 5, the paper's main baseline): out = the row of G whose sum of squared
  * distances to its m-b-2 nearest other rows is smallest (ties: lower index).  The distances
- * come from the Gram matrix G G^T, taken in one pass over G on the fp32 matrix cores and
+ * come from the Gram matrix G G^T, taken in one pass over G on the bf16 matrix cores (every
+ * float split into three bf16 pieces, six piece products: float32 accuracy) and
  * summed in float64; they are therefore exact to about 1e-5 of ||G_i||^2 + ||G_j||^2, and two
  * rows whose Krum scores differ by less than that may be chosen either way.  Requires
  * m - b - 2 >= 1; UNSUPPORTED for m > 128; rows must be finite.
