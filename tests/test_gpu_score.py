@@ -98,15 +98,18 @@ def test_small_shapes(B, case, fwd):
 
 LONG_K = [("fp32", 32, [3072, 512, 10]), ("bf16", 32, [3072, 512, 10]), ("bf16", 128, [1024, 512, 10]),
           ("fp32", 64, [1024, 512, 10]), ("fp32", 32, [512, 64, 10]), ("fp32", 20, [640, 96, 10]), ("bf16", 20, [640, 96, 10]),
-          ("fp32", 100, [576, 130, 70, 3])]
+          ("fp32", 100, [576, 130, 70, 3]),
+          # narrow layers behind a wide one: the candidates' own launches split K too (one-wave tiles)
+          ("bf16", 64, [1024, 512, 10]), ("bf16", 50, [640, 1088, 7]), ("fp32", 32, [1100, 10]), ("bf16", 32, [1100, 10])]
 
 
 @pytest.mark.parametrize("fwd,n_r,dims", LONG_K)
 def test_long_k_layers(B, fwd, n_r, dims):
     """Input widths of eight and more 64-wide chunks: the pass at x on its own splits K
     over the waves of a workgroup there (both operand types, one to four row blocks, a
-    chunk count that the waves do not share evenly), and fp32 activations leave the
-    kernels through 128-bit stores."""
+    chunk count that the waves do not share evenly), so do candidate launches of layers
+    at most 32 features wide (with and without the second product, partial norms summed
+    across the waves), and fp32 activations leave the kernels through 128-bit stores."""
     w = WL.make_mlp_workload("longk", 95, dims, 6, 2, n_r, 0.05, 1e-3, fwd, seed=n_r, n_flip=2)
     _check_step(B, w)
 
