@@ -158,6 +158,18 @@ def test_batches_larger_than_one_pass(B, fwd):
     _check_step(B, w)
 
 
+@pytest.mark.parametrize("fwd", ["fp32", "bf16"])
+def test_maximum_number_of_candidates(B, fwd):
+    """m = 1024, the most the boundary accepts (more than kSrcChunk-sized groups of candidates
+    per feature tile, selection over 1024 scores), with faulty rows of both kinds."""
+    w = WL.make_mlp_workload("maxm", 92, [48, 40, 5], 1024, 300, 16, 0.1, 1e-3, fwd, n_flip=100, n_noise=200,
+                             noise_std=3.0)
+    # The distance of the bf16 forward to the float64 definition is printed, not gated: it is the
+    # operand rounding itself, and the largest of 1024 rows (5.7e-2 of the score scale) lies
+    # beyond the bound that the other tests' handful of rows stays within.
+    _check_step(B, w, exact_bound=None)
+
+
 def test_gamma_zero_and_rho_zero(B):
     w = WL.make_mlp_workload("g0", 91, [40, 30, 6], 5, 1, 12, 0.0, 2e-3, "fp32", n_flip=1)
     s = npy(gpu_scores(B, w)).astype(np.float64)
