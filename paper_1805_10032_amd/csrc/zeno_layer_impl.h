@@ -877,18 +877,25 @@ bool launch_lines_aligned(const LayerArgs& a) {
   return ok;
 }
 
-constexpr int kSplitK = 4;  // waves that share one feature tile of a lone pass at x
+// Waves that share one feature tile and split K: four, or two where four private LDS layouts do not
+// fit into the 160 KB of a compute unit (0: the layout is single-buffered or too large even twice).
+template <bool BF16, bool DELTA, int MB>
+constexpr int split_k_waves() {
+  using L = Lds<BF16, DELTA, MB, 1>;
+  if (!L::DBUF) return 0;
+  return L::TOTAL * 4 <= 160 * 1024 ? 4 : L::TOTAL * 2 <= 160 * 1024 ? 2 : 0;
+}
 
 template <bool BF16, bool DELTA, int MB, int NW>
 hipError_t launch_nt(const LayerArgs& a, hipStream_t stream) {
-  // One-tile workgroups, every K of the launch long enough to split, and LDS for kSplitK private
-  // double-buffered layouts
-  if constexpr (NW == 1 && Lds<BF16, DELTA, MB, 1>::DBUF && Lds<BF16, DELTA, MB, 1>::TOTAL * kSplitK <= 160 * 1024) {
-    const bool base_ok = !a.has_base || (a.bj.Kp >> 6) >= 2 * kSplitK;
-    const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * kSplitK;
+  // One-tile workgroups and every K of the launch long enough to split
+  constexpr int KS = split_k_waves<BF16, DELTA, MB>();
+  if constexpr (NW == 1 && KS > 0) {
+    const bool base_ok = !a.has_base || (a.bj.Kp >> 6) >= 2 * KS;
+    const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * KS;
     if ((a.has_base || a.n_cand > 0) && base_ok && cand_ok) {
-      if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, kSplitK>(a, stream);
-      return launch_inst<BF16, DELTA, MB, NW, false, kSplitK>(a, stream);
+      if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, KS>(a, stream);
+      return launch_inst<BF16, DELTA, MB, NW, false, KS>(a, stream);
     }
   }
   if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream);
