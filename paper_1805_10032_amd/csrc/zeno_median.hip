@@ -1,6 +1,7 @@
 // Marginal median (Definition 4): for every coordinate j the one-dimensional
-// median of the m values G[0][j] .. G[m-1][j].  Each lane owns one column and
-// keeps its values in registers as order-preserving integer keys.
+// median of the m values G[0][j] .. G[m-1][j].  Each lane owns one column (four
+// adjacent ones up to m = 32, read with one 128-bit load per row) and keeps its
+// values in registers as order-preserving integer keys.
 //
 // Only the middle of the order is needed, so no full sort is done: the m keys
 // are padded to a power of two P with equally many -inf and +inf keys (one more
@@ -12,8 +13,8 @@
 // former and the minimum of the latter.
 //
 // Most of the padding sits at positions fixed at compile time: the kernel is
-// instantiated for Q real slots (m rounded up to a multiple of 4, of 8 above 64), the lowest
-// (P-Q)/2 positions of the first half hold the constant -inf key and the
+// instantiated for Q real slots (m rounded up to a multiple of 4, of 8 above
+// 64), the lowest (P-Q)/2 positions of the first half hold the constant -inf key and the
 // highest (P-Q)/2 of the second half the constant +inf key.  An ascending
 // compare-exchange never moves those, so after unrolling the compiler deletes
 // every compare-exchange that touches one: the network that runs is the one for
