@@ -99,6 +99,25 @@ def test_mean_and_median_bit_exact(B, m, d):
     assert np.array_equal(med, O.median(G.numpy()).astype(np.float32))
 
 
+@pytest.mark.parametrize("row_align", [1, 32])
+def test_median_every_m(B, row_align):
+    """Every number of candidates the median accepts: each has its own count of compile-time and
+    run-time padding keys (and the small ones the four-column lanes when the rows are aligned);
+    d = 263 leaves a ragged tail behind the four-column part.  NaN and infinite entries included."""
+    from tests._util import rows_to_gpu
+    d = 263
+    for m in range(1, 129):
+        G = _rand_G(m, d, 5000 + m, scale=2.0)
+        G[m // 2, ::17] = float("inf")
+        G[0, 5::29] = float("nan")
+        G[m - 1, 3::31] = float("-inf")
+        med = B.zeno_median(rows_to_gpu(B, G, row_align)).cpu().numpy()
+        ref = O.median(G.numpy()).astype(np.float32)
+        assert np.array_equal(np.isnan(med), np.isnan(ref)), m
+        ok = ~np.isnan(ref)
+        assert np.array_equal(med[ok], ref[ok]), m
+
+
 def test_median_with_nonfinite_entries(B):
     m, d = 6, 200
     G = _rand_G(m, d, 9)
