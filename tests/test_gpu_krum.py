@@ -11,8 +11,9 @@ from tests._util import npy, rows_to_gpu
 
 pytestmark = pytest.mark.gpu
 
-# The squared distances come from a Gram matrix accumulated in fp32 on the matrix cores and summed in
-# float64 over workgroups: exact to about sqrt(columns per wave) * 2^-24 of ||G_i||^2 + ||G_j||^2.
+# The squared distances come from a Gram matrix accumulated in fp32 on the matrix cores (operands split
+# into three bf16 pieces each, six piece products: fp32-level products) and summed in float64 over
+# workgroups: exact to about sqrt(columns per wave) * 2^-24 of ||G_i||^2 + ||G_j||^2.
 # Gate: 2e-5 of that scale per distance, times the number of distances in a score.
 DIST_TOL = 2e-5
 
@@ -53,6 +54,19 @@ def test_krum_against_oracle(B, m, d, b, row_align):
     G[bad] = -4.0 * G[bad] + 3.0 * torch.randn(b, d, generator=g)
     idx = _check(B, G, b, row_align)
     assert idx not in set(bad.tolist())
+
+
+def test_krum_row_counts_around_the_block_sizes(B):
+    """Row counts on both sides of every 32-row block boundary and in between (one to four row
+    blocks, the last one from one live row to full), d with a ragged last chunk."""
+    d = 333
+    for m in (3, 4, 7, 12, 13, 20, 21, 31, 32, 33, 40, 63, 64, 65, 72, 90, 95, 96, 97, 100, 111, 127, 128):
+        g = torch.Generator().manual_seed(900 + m)
+        G = torch.randn(1, d, generator=g) + 0.5 * torch.randn(m, d, generator=g)
+        b = min(m // 4, m - 3)
+        bad = torch.randperm(m, generator=g)[:b]
+        G[bad] = -3.0 * G[bad]
+        _check(B, G, b, row_align=1 if m % 2 else 32)
 
 
 def test_krum_discussion_example(B):
