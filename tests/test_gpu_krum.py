@@ -69,6 +69,21 @@ def test_krum_row_counts_around_the_block_sizes(B):
         _check(B, G, b, row_align=1 if m % 2 else 32)
 
 
+def test_krum_full_mantissas_and_wide_exponents(B):
+    """Entries whose 24 mantissa bits are all in use (random, and the all-ones pattern) over 40 binades
+    and both signs: every one of the three bf16 pieces of a value carries weight, and the piece
+    products that the Gram kernel leaves out must stay below the stated tolerance."""
+    g = torch.Generator().manual_seed(77)
+    m, d = 40, 4099
+    mant = torch.randint(0, 1 << 23, (m, d), generator=g, dtype=torch.int32)
+    mant[:, ::5] = (1 << 23) - 1
+    expo = torch.randint(127 - 20, 127 + 20, (m, d), generator=g, dtype=torch.int32)
+    sign = torch.randint(0, 2, (m, d), generator=g, dtype=torch.int32)
+    G = ((sign << 31) | (expo << 23) | mant).view(torch.float32)
+    assert torch.isfinite(G).all()
+    _check(B, G, 9, row_align=32)
+
+
 def test_krum_discussion_example(B):
     """The one-dimensional example of the Discussion section: four honest gradients with mean 1,
     two colluding ones at -1, b = 2: Krum returns the faulty value."""
