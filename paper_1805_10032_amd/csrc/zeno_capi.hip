@@ -247,7 +247,7 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
     t.n_cand = m;
     t.cj = make_job(l);
     p_off[l] = P;
-    P += layer_tiles(t);
+    P += layer_tiles(t, bf16, l > 0, p.MB);
   }
 
   for (int begin = 0; begin < n_r; begin += p.pass_rows) {

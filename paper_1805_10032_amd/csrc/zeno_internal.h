@@ -78,7 +78,7 @@ hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, i
                                 void* tiled, hipStream_t stream);
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream);
 bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB);  // run a.bj inside the candidates' launch?
-int layer_tiles(const LayerArgs& a);  // partial-norm slots (feature tiles) of the candidate job of this launch
+int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB);  // partial-norm slots (feature tiles) of the candidate job of this launch
 hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, const float* targets,
                        int loss, int m, int n_r_total, int chunk_begin, int chunk_rows, int C,
                        double* sample_diff, hipStream_t stream);

@@ -15,14 +15,7 @@ int wgs_per_cu_bf16_first(int MB, int NW);
 int wgs_per_cu_f32_delta(int MB, int NW);
 int wgs_per_cu_f32_first(int MB, int NW);
 
-int layer_tiles(const LayerArgs& a) { return job_tiles(a.cj, 32 * launch_nw_for(a)); }
-
-// Should the pass at x (a.bj) ride in the candidates' launch?  Workgroups run in
-// rounds of (compute units x resident workgroups); the extra workgroups are free
-// when they fit into the last round and cost a whole extra round when the
-// candidates fill their rounds exactly, unless there are many rounds anyway.
-bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB) {
-  if (a.n_cand <= 0) return true;
+static int compute_units() {
   static int n_cu = 0;
   if (n_cu == 0) {
     int dev = 0, v = 0;
@@ -30,9 +23,42 @@ bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB) {
       v = 256;
     n_cu = v;
   }
-  const int NW = launch_nw_for(a);
-  const int per_cu = bf16 ? (delta ? wgs_per_cu_bf16_delta(MB, NW) : wgs_per_cu_bf16_first(MB, NW))
-                          : (delta ? wgs_per_cu_f32_delta(MB, NW) : wgs_per_cu_f32_first(MB, NW));
+  return n_cu;
+}
+
+static int wgs_per_cu(bool bf16, bool delta, int MB, int NW) {
+  return bf16 ? (delta ? wgs_per_cu_bf16_delta(MB, NW) : wgs_per_cu_bf16_first(MB, NW))
+              : (delta ? wgs_per_cu_f32_delta(MB, NW) : wgs_per_cu_f32_first(MB, NW));
+}
+
+// Waves per workgroup of a launch.  Where eight would be picked, four are taken instead if two
+// such workgroups fit on a compute unit and the eight-wave workgroups do not fill their rounds of
+// (compute units x resident workgroups) almost exactly: the eight waves of a workgroup that has a
+// compute unit to itself all wait at the same barrier once per chunk, while two four-wave
+// workgroups run out of step and fill each other's waits (workload 4: 800 eight-wave workgroups
+// are 3.1 rounds, four waves gain 2-4 % per layer; workload 5: 1024 are exactly four rounds and
+// eight waves, which copy the activations once per 256 features instead of once per 128, win).
+static int nw_for(const LayerArgs& a, bool bf16, bool delta, int MB) {
+  const int nw = launch_nw_for(a);
+  if (nw != 8 || a.n_cand <= 0) return nw;
+  if (wgs_per_cu(bf16, delta, MB, 4) < 2) return 8;
+  const long long slots = (long long)compute_units() * wgs_per_cu(bf16, delta, MB, 8);
+  const long long wgs = (long long)job_tiles(a.cj, 256) * a.n_cand;
+  const long long rounds = (wgs + slots - 1) / slots;
+  return 10 * wgs >= 9 * rounds * slots ? 8 : 4;
+}
+
+int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB) { return job_tiles(a.cj, 32 * nw_for(a, bf16, delta, MB)); }
+
+// Should the pass at x (a.bj) ride in the candidates' launch?  Workgroups run in
+// rounds of (compute units x resident workgroups); the extra workgroups are free
+// when they fit into the last round and cost a whole extra round when the
+// candidates fill their rounds exactly, unless there are many rounds anyway.
+bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB) {
+  if (a.n_cand <= 0) return true;
+  const int n_cu = compute_units();
+  const int NW = nw_for(a, bf16, delta, MB);
+  const int per_cu = wgs_per_cu(bf16, delta, MB, NW);
   const long long slots = (long long)n_cu * per_cu;
   const long long cand = (long long)job_tiles(a.cj, 32 * NW) * a.n_cand;
   const long long base = job_tiles(a.bj, 32 * NW);
@@ -54,7 +80,7 @@ hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, i
 }
 
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream) {
-  const int NW = launch_nw_for(a);
+  const int NW = nw_for(a, bf16, delta, MB);
   if (bf16) {
     return delta ? launch_layer_bf16_delta(a, MB, NW, stream) : launch_layer_bf16_first(a, MB, NW, stream);
   }
