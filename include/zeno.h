@@ -87,7 +87,8 @@ typedef struct zeno_model zeno_model_t; /* opaque HOST object owned by the libra
 typedef struct {
   int32_t n_r;             /* >= 1 */
   const float* features;   /* DEVICE [n_r x dims[0]] row-major */
-  const int32_t* labels;   /* DEVICE [n_r], softmax-CE only, 0 <= label < dims[L] */
+  const int32_t* labels;   /* DEVICE [n_r], softmax-CE only, 0 <= label < dims[L]; a label outside that
+                              range makes every score NaN (nothing is read out of bounds) */
   const float* targets;    /* DEVICE [n_r], squared loss only */
 } zeno_batch_t;
 
@@ -162,7 +163,8 @@ zeno_status_t zeno_median(const float* G, int64_t ldg, int32_t m, int64_t d, flo
  * float split into three bf16 pieces, six piece products: float32 accuracy) and
  * summed in float64; they are therefore exact to about 1e-5 of ||G_i||^2 + ||G_j||^2, and two
  * rows whose Krum scores differ by less than that may be chosen either way.  Requires
- * m - b - 2 >= 1; UNSUPPORTED for m > 128; rows must be finite.
+ * m - b - 2 >= 1; UNSUPPORTED for m > 128.  A row that holds NaN or Inf is at infinite distance
+ * from every row: it is nobody's near neighbour and its own score is +infinity.
  *   out         DEVICE [d]    copy of the chosen row
  *   chosen      DEVICE [1]    int32 out, index of the chosen row
  *   krum_scores DEVICE [m]    out, the m sums of squared distances, or NULL
@@ -172,6 +174,14 @@ zeno_status_t zeno_krum(const float* G, int64_t ldg, int32_t m, int64_t d, int32
                         float* krum_scores, void* workspace, size_t workspace_bytes, void* stream);
 
 const char* zeno_status_string(zeno_status_t status);
+
+/* Host-only self-check of the scratch layout of zeno_score (Definition 2's m+1 forward passes keep
+ * their activations there): walks the launch sequence for (model, m, n_r) without touching a
+ * device and verifies, for every workgroup width a launch may take, that everything the launch
+ * writes lies inside its slot of the workspace.  OK, INVALID_ARG for bad arguments, WORKSPACE if a
+ * launch would leave its slot (a bug in the library: zeno_score makes the same check for the
+ * widths it really uses and then enqueues nothing). */
+zeno_status_t zeno_score_plan_check(const zeno_model_t* model, int32_t m, int32_t n_r);
 
 /* Per-launch timing, a measurement aid (Section 5.3 prices the step by its
  * O(d m) passes over the candidates; this reports what each pass costs).
@@ -201,6 +211,13 @@ typedef struct {
   int32_t layer;  /* 0-based layer index for the layer kernels, else 0 */
   float ms;       /* elapsed time between the two events */
   double algorithmic_bytes;
+  /* layer kernels only (else 0): the launch shape that ran */
+  int32_t waves;      /* waves per workgroup that own different 32-feature tiles: 1, 4 or 8 */
+  int32_t k_split;    /* waves that share one feature tile and split the input width: 1, 2 or 4 */
+  int32_t streaming;  /* 1: rows read with non-temporal loads (line-aligned layout), 0: plain loads */
+  int32_t row_blocks; /* 32-sample accumulator blocks per wave: 1, 2 or 4 */
+  int32_t merged;     /* 1: the launch carries the candidates' layer AND the pass at x through another layer */
+  int32_t second;     /* 1: candidates with the second matrix product (layers after the first) */
 } zeno_profile_record_t;
 
 zeno_status_t zeno_profile_enable(int32_t enable);

@@ -163,13 +163,17 @@ def median(G):
 
 def krum_scores(G, b):
     """Definition 5: for every candidate the sum of squared distances to its m-b-2
-    nearest other candidates."""
+    nearest other candidates.  Reading where the paper is silent: a distance that is
+    not finite (a row holding NaN or Inf, Section 3 Eq. 1 allows any value) counts as
+    +infinity."""
     G = np.asarray(G, dtype=np.float64)
     m = G.shape[0]
     assert m - b - 2 >= 1
     out = np.empty(m)
     for i in range(m):
-        dist = sorted(float(np.sum((G[i] - G[j]) ** 2)) for j in range(m) if j != i)
+        with np.errstate(invalid="ignore", over="ignore"):
+            dist = [float(np.sum((G[i] - G[j]) ** 2)) for j in range(m) if j != i]
+        dist = sorted(v if np.isfinite(v) else np.inf for v in dist)
         out[i] = sum(dist[:m - b - 2])
     return out
 

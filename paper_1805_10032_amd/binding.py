@@ -23,7 +23,8 @@ STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported size", 3: "workspace",
 
 EXPORTS = ["zeno_model_create", "zeno_model_destroy", "zeno_model_num_params",
            "zeno_score_workspace_bytes", "zeno_score", "zeno_aggregate", "zeno_aggregate_update", "zeno_mean",
-           "zeno_median", "zeno_krum_workspace_bytes", "zeno_krum", "zeno_status_string", "zeno_profile_enable", "zeno_profile_collect"]
+           "zeno_median", "zeno_krum_workspace_bytes", "zeno_krum", "zeno_status_string", "zeno_profile_enable", "zeno_profile_collect",
+           "zeno_score_plan_check"]
 
 KERNEL_NAMES = ["pack", "layer_base", "layer_cand", "loss", "combine", "average", "mean", "median", "average_update",
                 "krum"]
@@ -45,7 +46,9 @@ class _ModelDesc(ctypes.Structure):
 
 class _ProfileRecord(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int32), ("layer", ctypes.c_int32), ("ms", ctypes.c_float),
-                ("algorithmic_bytes", ctypes.c_double)]
+                ("algorithmic_bytes", ctypes.c_double), ("waves", ctypes.c_int32), ("k_split", ctypes.c_int32),
+                ("streaming", ctypes.c_int32), ("row_blocks", ctypes.c_int32), ("merged", ctypes.c_int32),
+                ("second", ctypes.c_int32)]
 
 
 class _Batch(ctypes.Structure):
@@ -92,6 +95,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.zeno_krum_workspace_bytes.restype = ctypes.c_size_t
     lib.zeno_krum.argtypes = [vp, i64, i32, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.zeno_krum.restype = ctypes.c_int
+    lib.zeno_score_plan_check.argtypes = [vp, i32, i32]
+    lib.zeno_score_plan_check.restype = ctypes.c_int
     lib.zeno_profile_enable.argtypes = [i32]
     lib.zeno_profile_enable.restype = ctypes.c_int
     lib.zeno_profile_collect.argtypes = [ctypes.POINTER(_ProfileRecord), i32]
@@ -167,6 +172,10 @@ class ZenoModel:
 
     def workspace_bytes(self, m: int, n_r: int) -> int:
         return int(self._lib.zeno_score_workspace_bytes(self._h, int(m), int(n_r)))
+
+    def plan_check(self, m: int, n_r: int) -> int:
+        """Status of the host-side check that every launch of zeno_score stays inside its workspace slots."""
+        return int(self._lib.zeno_score_plan_check(self._h, int(m), int(n_r)))
 
     def close(self):
         if self._h is not None and self._h.value:
@@ -309,9 +318,15 @@ def profile_enable(on: bool = True):
     load_library().zeno_profile_enable(1 if on else 0)
 
 
-def profile_collect(max_records: int = 4096):
-    """[(kernel name, layer, ms, algorithmic bytes)] of the launches since the last collect."""
+def profile_collect(max_records: int = 4096, detail: bool = False):
+    """[(kernel name, layer, ms, algorithmic bytes)] of the launches since the last collect; with
+    detail=True a dict per launch that also names the launch shape of the layer kernels."""
     buf = (_ProfileRecord * max_records)()
     n = load_library().zeno_profile_collect(buf, max_records)
+    if detail:
+        return [dict(kernel=KERNEL_NAMES[r.kernel], layer=int(r.layer), ms=float(r.ms), bytes=float(r.algorithmic_bytes),
+                     waves=int(r.waves), k_split=int(r.k_split), streaming=int(r.streaming),
+                     row_blocks=int(r.row_blocks), merged=int(r.merged), second=int(r.second))
+                for r in (buf[i] for i in range(n))]
     return [(KERNEL_NAMES[buf[i].kernel], int(buf[i].layer), float(buf[i].ms), float(buf[i].algorithmic_bytes))
             for i in range(n)]

@@ -218,20 +218,19 @@ hipError_t launch_masked_average(const float* G, long long ldg, const float* sco
   const int n_blocks = (int)(nb < 1 ? 1 : (nb > max_blocks ? max_blocks : nb));
   const size_t lds = ZENO_MAX_CANDIDATES * sizeof(int) + (size_t)n_bufs * n_blocks * kBlockVec * 16;
   // as many workgroups as the chip holds at once (LDS-limited), each with a balanced share of the blocks
-  static int n_cu = 0;
-  if (n_cu == 0) {
+  static const int n_cu = [] {
     int dev = 0, v = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
       v = 256;
-    n_cu = v;
-  }
+    return v;
+  }();
   int per_cu = (int)((160 * 1024) / (lds + 512));
   per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
   const long long blocks_total = (n_vec + kBlockVec - 1) / kBlockVec;
   const long long resident = (long long)n_cu * per_cu;
   const int grid = (int)(blocks_total < 1 ? 1 : (blocks_total > resident ? resident : blocks_total));
-  static bool attr_set = false;
-  if (!attr_set) {
+  // once per process (initialisation of a local static is thread-safe)
+  static const hipError_t attr_err = [] {
     const int lds_max = (int)(ZENO_MAX_CANDIDATES * sizeof(int) + (size_t)kMaxBlocks * kBlockVec * 16);
     const void* kernels[4] = {reinterpret_cast<const void*>(&masked_average_kernel<true, false>),
                               reinterpret_cast<const void*>(&masked_average_kernel<false, false>),
@@ -241,8 +240,9 @@ hipError_t launch_masked_average(const float* G, long long ldg, const float* sco
       hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds_max);
       if (e != hipSuccess) return e;
     }
-    attr_set = true;
-  }
+    return hipSuccess;
+  }();
+  if (attr_err != hipSuccess) return attr_err;
   const bool all = scores == nullptr;
   const int bb = all ? 0 : b;
 #define ZENO_LAUNCH_AVG(ALLV, UPD)                                                                                  \

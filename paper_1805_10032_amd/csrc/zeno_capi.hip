@@ -22,17 +22,29 @@ namespace {
 using namespace zeno;
 
 constexpr int kMaxPassRows = 128;  // samples per pass over G (four 32-row accumulator blocks)
+constexpr int kMaxTileRows = 256;  // output features of the widest workgroup (eight waves x 32)
 
 inline int pad64(int v) { return (v + 63) / 64 * 64; }
 inline int blocks_for(int rows) { return rows <= 32 ? 1 : (rows <= 64 ? 2 : 4); }
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Rows of the operand-order copy of a weight matrix.  The pass at x writes the copy one
+// 32-row wave tile at a time for EVERY wave of its workgroups, also for waves whose rows lie
+// beyond the layer (they store zeros), and the candidates' workgroups read it the same way;
+// the widest workgroup of any launch covers kMaxTileRows features.
+inline int wt_rows_alloc(int N, bool last) {
+  const int cover = last ? N : pad64(N);
+  return (cover + kMaxTileRows - 1) / kMaxTileRows * kMaxTileRows;
+}
 
 // Workspace layout, shared by the size query and the call itself.
 struct Plan {
   int L, pass_rows, MB, n_pad, esize, P;
   size_t off_feat, off_hbase[ZENO_MAX_LAYERS], off_z0[ZENO_MAX_LAYERS];
   size_t off_wt[ZENO_MAX_LAYERS];  // W_l in operand order, layers after the first
+  int wt_rows[ZENO_MAX_LAYERS];    // rows of that copy (features, rounded up to whole workgroup tiles)
   size_t off_dc[2], cand_stride, off_dz, off_norm, off_diff, total;
+  size_t sz_hbase[ZENO_MAX_LAYERS], sz_z0[ZENO_MAX_LAYERS], sz_wt[ZENO_MAX_LAYERS], sz_dz;  // bytes of the slots
 };
 
 Plan make_plan(const zeno_model* mdl, int m, int n_r) {
@@ -54,14 +66,18 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
   int max_np = 64;
   for (int l = 0; l < p.L; ++l) {
     const int N = D.dims[l + 1];
-    p.off_z0[l] = take((size_t)p.pass_rows * N * sizeof(float));
+    p.sz_z0[l] = (size_t)p.pass_rows * N * sizeof(float);
+    p.off_z0[l] = take(p.sz_z0[l]);
     if (l + 1 < p.L) {
-      p.off_hbase[l] = take((size_t)p.n_pad * pad64(N) * p.esize);
+      p.sz_hbase[l] = (size_t)p.n_pad * pad64(N) * p.esize;
+      p.off_hbase[l] = take(p.sz_hbase[l]);
       if (pad64(N) > max_np) max_np = pad64(N);
     }
     if (l > 0) {
-      const int cover = (l + 1 < p.L) ? pad64(N) : N;
-      p.off_wt[l] = take((size_t)((cover + 127) / 128 * 128) * pad64(D.dims[l]) * p.esize);
+      // rows: whole feature tiles of the widest workgroup (256 features) that may carry the pass at x
+      p.wt_rows[l] = wt_rows_alloc(N, l + 1 == p.L);
+      p.sz_wt[l] = (size_t)p.wt_rows[l] * pad64(D.dims[l]) * p.esize;
+      p.off_wt[l] = take(p.sz_wt[l]);
     }
     p.P += (pad64(N) + 31) / 32;  // upper bound on the partial-norm slots of this layer
   }
@@ -69,7 +85,8 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
   if (p.L > 1) {
     for (int i = 0; i < 2; ++i) p.off_dc[i] = take(p.cand_stride * m);
   }
-  p.off_dz = take((size_t)m * p.pass_rows * D.dims[p.L] * sizeof(float));
+  p.sz_dz = (size_t)m * p.pass_rows * D.dims[p.L] * sizeof(float);
+  p.off_dz = take(p.sz_dz);
   p.off_norm = take((size_t)m * p.P * sizeof(double));
   p.off_diff = take((size_t)m * n_r * sizeof(double));
   p.total = off;
@@ -108,9 +125,22 @@ struct ProfScope {
     e.rec.layer = layer;
     e.rec.ms = 0.f;
     e.rec.algorithmic_bytes = bytes;
+    e.rec.waves = e.rec.k_split = e.rec.streaming = e.rec.row_blocks = e.rec.merged = e.rec.second = 0;
     (void)hipEventRecord(e.start, stream);
     g_prof.push_back(e);
     slot = (int)g_prof.size() - 1;
+  }
+  void set_shape(const LaunchShape& s, bool merged, bool second) {
+    if (slot < 0) return;
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    if (slot >= (int)g_prof.size()) return;
+    zeno_profile_record_t& r = g_prof[slot].rec;
+    r.waves = s.waves;
+    r.k_split = s.k_split;
+    r.streaming = s.streaming;
+    r.row_blocks = s.row_blocks;
+    r.merged = merged ? 1 : 0;
+    r.second = second ? 1 : 0;
   }
   ~ProfScope() {
     if (slot < 0) return;
@@ -118,6 +148,206 @@ struct ProfScope {
     if (slot < (int)g_prof.size()) (void)hipEventRecord(g_prof[slot].stop, stream);
   }
 };
+
+zeno_status_t check_score_args(const zeno_model_t* model, const float* x, const float* G, int64_t ldg, int32_t m,
+                               const zeno_batch_t* batch, float gamma, float rho, const float* scores) {
+  if (model == nullptr || x == nullptr || G == nullptr || batch == nullptr || scores == nullptr)
+    return ZENO_ERR_INVALID_ARG;
+  if (m < 1 || m > ZENO_MAX_CANDIDATES || batch->n_r < 1 || ldg < model->d) return ZENO_ERR_INVALID_ARG;
+  if (!std::isfinite(gamma) || gamma < 0.f || !std::isfinite(rho) || rho < 0.f) return ZENO_ERR_INVALID_ARG;
+  const zeno_model_desc_t& D = model->desc;
+  if (batch->features == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (D.loss == ZENO_LOSS_SOFTMAX_CE && batch->labels == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (D.loss == ZENO_LOSS_SQUARED && batch->targets == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (!aligned(x, 4) || !aligned(G, 4) || !aligned(scores, 4) || !aligned(batch->features, 4) ||
+      !aligned(batch->labels, 4) || !aligned(batch->targets, 4))
+    return ZENO_ERR_INVALID_ARG;
+  return ZENO_OK;
+}
+
+// One launch of the layer kernel as the sequence plans it.
+struct Launch {
+  LayerArgs a;
+  bool delta;     // candidates carry the second product
+  int kernel;     // zeno_kernel_t, for the per-launch timing
+  int layer;
+  double bytes;   // algorithmic bytes
+  int wt_layer;   // layer whose operand-order copy of W the launch writes, or -1
+  int base_layer; // layer the pass at x runs through in this launch, or -1
+};
+
+// The layer launches of one pass over G (rows samples): [pass at x, layer 0], then for
+// every layer l the candidates' layer l, with the pass at x through layer l+1 (whose
+// input the previous launch completed) either inside that launch or as a launch of its
+// own in front of it.  A single-layer model needs one launch.  *P_out receives the
+// partial-norm slots per candidate.  query_device = false plans without asking the
+// device for occupancies (every merge is then planned as merged, the wider case).
+std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const float* x, const float* G, int64_t ldg,
+                                   int m, float gamma, unsigned char* ws, int rows, bool first_pass, int* P_out,
+                                   bool query_device = true) {
+  const zeno_model_desc_t& D = model->desc;
+  const bool bf16 = D.fwd == ZENO_FWD_BF16;
+  const int L = p.L;
+  auto make_job = [&](int l) {
+    LayerJob j;
+    std::memset(&j, 0, sizeof(j));
+    j.w_off = model->w_off[l];
+    j.b_off = model->b_off[l];
+    j.N = D.dims[l + 1];
+    j.K = D.dims[l];
+    j.Kp = pad64(j.K);
+    j.Np = pad64(j.N);
+    j.last = (l + 1 == L);
+    j.A_base = l == 0 ? ws + p.off_feat : ws + p.off_hbase[l - 1];
+    j.Wt = l > 0 ? ws + p.off_wt[l] : nullptr;
+    j.Z0 = reinterpret_cast<float*>(ws + p.off_z0[l]);
+    j.H_base = j.last ? nullptr : ws + p.off_hbase[l];
+    return j;
+  };
+  // bytes of layer l's block in one parameter vector (what one source streams)
+  auto layer_bytes = [&](int l) {
+    return 4.0 * ((double)D.dims[l + 1] * D.dims[l] + (model->b_off[l] >= 0 ? D.dims[l + 1] : 0));
+  };
+  LayerArgs common;
+  std::memset(&common, 0, sizeof(common));
+  common.G = G;
+  common.x = x;
+  common.ldg = ldg;
+  common.dZ = reinterpret_cast<float*>(ws + p.off_dz);
+  common.gamma = gamma;
+  common.neg_inv_gamma = gamma > 0.f ? -1.0f / gamma : 0.f;
+  common.n_r = rows;
+
+  // partial-norm slots actually used by the candidate launches
+  int p_off[ZENO_MAX_LAYERS], P = 0;
+  for (int l = 0; l < L; ++l) {
+    LayerArgs t = common;
+    t.n_cand = m;
+    t.cj = make_job(l);
+    p_off[l] = P;
+    P += query_device ? layer_tiles(t, bf16, l > 0, p.MB) : (pad64(D.dims[l + 1]) + 31) / 32;
+  }
+  *P_out = P;
+
+  std::vector<Launch> seq;
+  if (L > 1) {
+    Launch b;
+    b.a = common;
+    b.a.has_base = 1;
+    b.a.bj = make_job(0);
+    b.delta = false;
+    b.kernel = ZENO_KERNEL_LAYER_BASE;
+    b.layer = 0;
+    b.bytes = layer_bytes(0);
+    b.wt_layer = -1;
+    b.base_layer = 0;
+    seq.push_back(b);
+  }
+  for (int l = 0; l < L; ++l) {
+    Launch c;
+    c.a = common;
+    c.a.n_cand = m;
+    c.a.cj = make_job(l);
+    c.a.norm_partials = first_pass ? reinterpret_cast<double*>(ws + p.off_norm) : nullptr;
+    c.a.P = P;
+    c.a.p_off = p_off[l];
+    c.delta = l > 0;
+    c.kernel = ZENO_KERNEL_LAYER_CAND;
+    c.layer = l;
+    c.bytes = layer_bytes(l) * m;
+    c.wt_layer = -1;
+    c.base_layer = -1;
+    if (L == 1) {
+      c.a.has_base = 1;
+      c.a.bj = make_job(0);
+      c.base_layer = 0;
+      c.bytes += layer_bytes(0);
+    } else {
+      c.a.D_cand = l == 0 ? nullptr : ws + p.off_dc[(l - 1) & 1];
+      c.a.A_stride = (long long)p.cand_stride;
+      c.a.Dl_cand = ws + p.off_dc[l & 1];
+      c.a.H_stride = (long long)p.cand_stride;
+      if (l + 1 < L) {
+        c.a.has_base = 1;
+        c.a.bj = make_job(l + 1);
+        if (!query_device || layer_merge_pays(c.a, bf16, l > 0, p.MB)) {
+          c.bytes += layer_bytes(l + 1);
+          c.wt_layer = l + 1;
+          c.base_layer = l + 1;
+        } else {
+          // the extra workgroups would cost a whole extra round: run the pass at x on its own first
+          Launch b;
+          b.a = common;
+          b.a.has_base = 1;
+          b.a.bj = c.a.bj;
+          b.delta = false;
+          b.kernel = ZENO_KERNEL_LAYER_BASE;
+          b.layer = l + 1;
+          b.bytes = layer_bytes(l + 1);
+          b.wt_layer = l + 1;
+          b.base_layer = l + 1;
+          seq.push_back(b);
+          c.a.has_base = 0;
+        }
+      }
+    }
+    seq.push_back(c);
+  }
+  return seq;
+}
+
+// Does everything a launch writes with NW waves per workgroup lie inside its workspace slot?
+bool launch_fits(const Plan& p, const Launch& L, int NW) {
+  const bool bf16 = p.esize == 2;
+  const LayerExtents e = layer_extents(L.a, bf16, p.MB, NW);
+  if (L.wt_layer >= 0 ? (size_t)e.wt_bytes > p.sz_wt[L.wt_layer] : e.wt_bytes != 0) return false;
+  if (L.base_layer >= 0) {
+    if ((size_t)e.z0_floats * sizeof(float) > p.sz_z0[L.base_layer]) return false;
+    if (L.base_layer + 1 < p.L && (size_t)e.hbase_bytes > p.sz_hbase[L.base_layer]) return false;
+  }
+  if (L.a.n_cand > 0) {
+    if ((size_t)e.d_bytes_per_cand > p.cand_stride) return false;
+    if ((size_t)e.dz_floats * sizeof(float) > p.sz_dz) return false;
+    if (L.a.P > p.P || L.a.p_off + e.norm_slots > L.a.P) return false;
+  }
+  return true;
+}
+
+zeno_status_t score_enqueue(const zeno_model* model, const Plan& p, const float* x, const float* G, int64_t ldg, int m,
+                            const zeno_batch_t* batch, float gamma, float rho, float* scores, unsigned char* ws,
+                            hipStream_t stream) {
+  const zeno_model_desc_t& D = model->desc;
+  const bool bf16 = D.fwd == ZENO_FWD_BF16;
+  const int L = p.L, n_r = batch->n_r, C = D.dims[L];
+  double* norm_partials = reinterpret_cast<double*>(ws + p.off_norm);
+  double* sample_diff = reinterpret_cast<double*>(ws + p.off_diff);
+  float* dZ = reinterpret_cast<float*>(ws + p.off_dz);
+  int P = 0;
+  for (int begin = 0; begin < n_r; begin += p.pass_rows) {
+    const int rows = (n_r - begin) < p.pass_rows ? (n_r - begin) : p.pass_rows;
+    const std::vector<Launch> seq = layer_sequence(model, p, x, G, ldg, m, gamma, ws, rows, begin == 0, &P);
+    // nothing is enqueued for a pass unless every launch of it stays inside its slots
+    for (const Launch& l : seq)
+      if (!launch_fits(p, l, layer_nw(l.a, bf16, l.delta, p.MB))) return ZENO_ERR_WORKSPACE;
+    {
+      ProfScope ps(ZENO_KERNEL_PACK, 0, 4.0 * rows * D.dims[0], stream);
+      ZENO_TRY(launch_pack_features(batch->features + (size_t)begin * D.dims[0], rows, D.dims[0], pad64(D.dims[0]),
+                                    p.MB, bf16, ws + p.off_feat, stream));
+    }
+    for (const Launch& l : seq) {
+      ProfScope ps(l.kernel, l.layer, l.bytes, stream);
+      LaunchShape shape;
+      ZENO_TRY(launch_layer(l.a, bf16, l.delta, p.MB, stream, &shape));
+      ps.set_shape(shape, l.a.n_cand > 0 && l.a.has_base, l.a.n_cand > 0 && l.delta);
+    }
+    ProfScope ps(ZENO_KERNEL_LOSS, 0, 4.0 * (m + 1) * rows * C, stream);
+    ZENO_TRY(launch_loss(reinterpret_cast<const float*>(ws + p.off_z0[L - 1]), dZ, batch->labels, batch->targets,
+                         D.loss, m, n_r, begin, rows, C, sample_diff, stream));
+  }
+  ProfScope ps(ZENO_KERNEL_COMBINE, 0, 8.0 * m * (n_r + P), stream);
+  ZENO_TRY(launch_score_combine(sample_diff, norm_partials, P, m, n_r, rho, scores, stream));
+  return ZENO_OK;
+}
 
 }  // namespace
 
@@ -184,135 +414,34 @@ size_t zeno_score_workspace_bytes(const zeno_model_t* model, int32_t m, int32_t 
 zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float* G, int64_t ldg, int32_t m,
                          const zeno_batch_t* batch, float gamma, float rho, float* scores, void* workspace,
                          size_t workspace_bytes, void* stream_) {
-  if (model == nullptr || x == nullptr || G == nullptr || batch == nullptr || scores == nullptr)
-    return ZENO_ERR_INVALID_ARG;
-  if (m < 1 || m > ZENO_MAX_CANDIDATES || batch->n_r < 1 || ldg < model->d) return ZENO_ERR_INVALID_ARG;
-  if (!std::isfinite(gamma) || gamma < 0.f || !std::isfinite(rho) || rho < 0.f) return ZENO_ERR_INVALID_ARG;
-  const zeno_model_desc_t& D = model->desc;
-  if (batch->features == nullptr) return ZENO_ERR_INVALID_ARG;
-  if (D.loss == ZENO_LOSS_SOFTMAX_CE && batch->labels == nullptr) return ZENO_ERR_INVALID_ARG;
-  if (D.loss == ZENO_LOSS_SQUARED && batch->targets == nullptr) return ZENO_ERR_INVALID_ARG;
-  if (!aligned(x, 4) || !aligned(G, 4) || !aligned(scores, 4) || !aligned(batch->features, 4) ||
-      !aligned(batch->labels, 4) || !aligned(batch->targets, 4))
-    return ZENO_ERR_INVALID_ARG;
-  const int n_r = batch->n_r;
-  const Plan p = make_plan(model, m, n_r);
+  zeno_status_t st = check_score_args(model, x, G, ldg, m, batch, gamma, rho, scores);
+  if (st != ZENO_OK) return st;
+  const Plan p = make_plan(model, m, batch->n_r);
   if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < p.total) return ZENO_ERR_WORKSPACE;
+  return score_enqueue(model, p, x, G, ldg, m, batch, gamma, rho, scores, reinterpret_cast<unsigned char*>(workspace),
+                       reinterpret_cast<hipStream_t>(stream_));
+}
 
-  hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
-  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
-  const bool bf16 = D.fwd == ZENO_FWD_BF16;
-  const int L = p.L;
-  double* norm_partials = reinterpret_cast<double*>(ws + p.off_norm);
-  double* sample_diff = reinterpret_cast<double*>(ws + p.off_diff);
-  float* dZ = reinterpret_cast<float*>(ws + p.off_dz);
-  const int C = D.dims[L];
-
-  auto make_job = [&](int l) {
-    LayerJob j;
-    std::memset(&j, 0, sizeof(j));
-    j.w_off = model->w_off[l];
-    j.b_off = model->b_off[l];
-    j.N = D.dims[l + 1];
-    j.K = D.dims[l];
-    j.Kp = pad64(j.K);
-    j.Np = pad64(j.N);
-    j.last = (l + 1 == L);
-    j.A_base = l == 0 ? ws + p.off_feat : ws + p.off_hbase[l - 1];
-    j.Wt = l > 0 ? ws + p.off_wt[l] : nullptr;
-    j.Z0 = reinterpret_cast<float*>(ws + p.off_z0[l]);
-    j.H_base = j.last ? nullptr : ws + p.off_hbase[l];
-    return j;
-  };
-  // bytes of layer l's block in one parameter vector (what one source streams)
-  auto layer_bytes = [&](int l) {
-    return 4.0 * ((double)D.dims[l + 1] * D.dims[l] + (model->b_off[l] >= 0 ? D.dims[l + 1] : 0));
-  };
-  LayerArgs common;
-  std::memset(&common, 0, sizeof(common));
-  common.G = G;
-  common.x = x;
-  common.ldg = ldg;
-  common.dZ = dZ;
-  common.gamma = gamma;
-  common.neg_inv_gamma = gamma > 0.f ? -1.0f / gamma : 0.f;
-#ifdef ZENO_TIMING_EXPERIMENTS
-  common.dbg = std::getenv("ZENO_DEBUG_SKIP") ? std::atoi(std::getenv("ZENO_DEBUG_SKIP")) : 0;
-#endif
-
-  // partial-norm slots actually used by the candidate launches
-  int p_off[ZENO_MAX_LAYERS], P = 0;
-  for (int l = 0; l < L; ++l) {
-    LayerArgs t = common;
-    t.n_cand = m;
-    t.cj = make_job(l);
-    p_off[l] = P;
-    P += layer_tiles(t, bf16, l > 0, p.MB);
-  }
-
+zeno_status_t zeno_score_plan_check(const zeno_model_t* model, int32_t m, int32_t n_r) {
+  if (model == nullptr || m < 1 || m > ZENO_MAX_CANDIDATES || n_r < 1) return ZENO_ERR_INVALID_ARG;
+  const Plan p = make_plan(model, m, n_r);
+  // a fictitious, suitably aligned workspace address: nothing is dereferenced
+  unsigned char* ws = reinterpret_cast<unsigned char*>(uintptr_t(1) << 40);
+  const float* fake = reinterpret_cast<const float*>(uintptr_t(1) << 30);
+  zeno_batch_t batch;
+  std::memset(&batch, 0, sizeof(batch));
+  batch.n_r = n_r;
+  batch.features = fake;
+  static const int widths[3] = {1, 4, 8};
   for (int begin = 0; begin < n_r; begin += p.pass_rows) {
     const int rows = (n_r - begin) < p.pass_rows ? (n_r - begin) : p.pass_rows;
-    const bool first_pass = begin == 0;
-    {
-      ProfScope ps(ZENO_KERNEL_PACK, 0, 4.0 * rows * D.dims[0], stream);
-      ZENO_TRY(launch_pack_features(batch->features + (size_t)begin * D.dims[0], rows, D.dims[0], pad64(D.dims[0]),
-                                    p.MB, bf16, ws + p.off_feat, stream));
-    }
-    // Launch order: [pass at x, layer 0] then for every layer l the candidates'
-    // layer l together with the pass at x through layer l+1 (whose input the
-    // previous launch completed).  A single-layer model needs one launch.
-    if (L > 1) {
-      LayerArgs a = common;
-      a.n_r = rows;
-      a.has_base = 1;
-      a.bj = make_job(0);
-      ProfScope ps(ZENO_KERNEL_LAYER_BASE, 0, layer_bytes(0), stream);
-      ZENO_TRY(launch_layer(a, bf16, false, p.MB, stream));
-    }
-    for (int l = 0; l < L; ++l) {
-      LayerArgs a = common;
-      a.n_r = rows;
-      a.n_cand = m;
-      a.cj = make_job(l);
-      a.norm_partials = first_pass ? norm_partials : nullptr;
-      a.P = P;
-      a.p_off = p_off[l];
-      double bytes = layer_bytes(l) * m;
-      if (L == 1) {
-        a.has_base = 1;
-        a.bj = make_job(0);
-        bytes += layer_bytes(0);
-      } else {
-        a.D_cand = l == 0 ? nullptr : ws + p.off_dc[(l - 1) & 1];
-        a.A_stride = (long long)p.cand_stride;
-        a.Dl_cand = ws + p.off_dc[l & 1];
-        a.H_stride = (long long)p.cand_stride;
-        if (l + 1 < L) {
-          a.has_base = 1;
-          a.bj = make_job(l + 1);
-          if (layer_merge_pays(a, bf16, l > 0, p.MB)) {
-            bytes += layer_bytes(l + 1);
-          } else {
-            // the extra workgroups would cost a whole extra round: run the pass at x on its own first
-            LayerArgs b = common;
-            b.n_r = rows;
-            b.has_base = 1;
-            b.bj = a.bj;
-            a.has_base = 0;
-            ProfScope ps(ZENO_KERNEL_LAYER_BASE, l + 1, layer_bytes(l + 1), stream);
-            ZENO_TRY(launch_layer(b, bf16, false, p.MB, stream));
-          }
-        }
-      }
-      ProfScope ps(ZENO_KERNEL_LAYER_CAND, l, bytes, stream);
-      ZENO_TRY(launch_layer(a, bf16, l > 0, p.MB, stream));
-    }
-    ProfScope ps(ZENO_KERNEL_LOSS, 0, 4.0 * (m + 1) * rows * C, stream);
-    ZENO_TRY(launch_loss(reinterpret_cast<const float*>(ws + p.off_z0[L - 1]), dZ, batch->labels, batch->targets,
-                         D.loss, m, n_r, begin, rows, C, sample_diff, stream));
+    int P = 0;
+    const std::vector<Launch> seq = layer_sequence(model, p, fake, fake, model->d, m, 0.1f, ws, rows, begin == 0, &P,
+                                                   /*query_device=*/false);
+    for (const Launch& L : seq)
+      for (int NW : widths)
+        if (!launch_fits(p, L, NW)) return ZENO_ERR_WORKSPACE;
   }
-  ProfScope ps(ZENO_KERNEL_COMBINE, 0, 8.0 * m * (n_r + P), stream);
-  ZENO_TRY(launch_score_combine(sample_diff, norm_partials, P, m, n_r, rho, scores, stream));
   return ZENO_OK;
 }
 

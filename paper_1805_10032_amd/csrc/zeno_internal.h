@@ -70,15 +70,33 @@ struct LayerArgs {
   double* norm_partials;  // [m x P] partial sums of squares, or NULL in passes after the first
   int P;                // partial slots per candidate
   int p_off;            // first slot of this layer
-  int dbg;              // timing experiments (only read when built with ZENO_TIMING_EXPERIMENTS)
 };
 
 // Launchers.  Each returns the hipError_t of its launches.
 hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, int MB, bool bf16,
                                 void* tiled, hipStream_t stream);
-hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream);
+// Which instantiation of the layer kernel a launch took (reported in the per-launch timing records).
+struct LaunchShape {
+  int waves;       // waves per workgroup that own different feature tiles (1, 4 or 8)
+  int k_split;     // waves that share one feature tile and split K (1, 2 or 4)
+  int streaming;   // 1: rows read with non-temporal loads (line-aligned layout)
+  int row_blocks;  // 32-sample accumulator blocks per wave (1, 2 or 4)
+};
+hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream,
+                        LaunchShape* shape = nullptr);
 bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB);  // run a.bj inside the candidates' launch?
-int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB);  // partial-norm slots (feature tiles) of the candidate job of this launch
+int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB);
+int layer_nw(const LayerArgs& a, bool bf16, bool delta, int MB);     // waves per workgroup the launch will use
+// Extents a launch with NW waves per workgroup writes (bytes / floats / slots, counted from the start of each buffer).
+struct LayerExtents {
+  long long wt_bytes;          // operand-order copy of W (pass at x)
+  long long hbase_bytes;       // tiled activations of the pass at x
+  long long z0_floats;         // pre-activations at x
+  long long d_bytes_per_cand;  // tiled scaled activation differences of one candidate
+  long long dz_floats;         // output layer's change of pre-activations, all candidates
+  int norm_slots;              // partial-norm slots per candidate
+};
+LayerExtents layer_extents(const LayerArgs& a, bool bf16, int MB, int NW);  // partial-norm slots (feature tiles) of the candidate job of this launch
 hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, const float* targets,
                        int loss, int m, int n_r_total, int chunk_begin, int chunk_rows, int C,
                        double* sample_diff, hipStream_t stream);

@@ -207,6 +207,7 @@ __global__ __launch_bounds__(128) void krum_score_kernel(const double* __restric
   if (j < m) {
     double dd = S(i, i) + S(j, j) - 2.0 * S(i, j);
     dd = dd < 0.0 ? 0.0 : dd;
+    dd = (dd == dd) ? dd : __builtin_inf();      // a NaN/Inf row is infinitely far from every row: ranks stay a permutation
     dist[j] = (j == i) ? __builtin_inf() : dd;   // the row itself is never a neighbour
   }
   __syncthreads();
@@ -247,8 +248,7 @@ __global__ __launch_bounds__(256) void krum_copy_kernel(const float* __restrict_
 
 template <int RB>
 int gram_resident() {
-  static int cached = 0;
-  if (cached == 0) {
+  static const int cached = [] {
     int dev = 0, n_cu = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
       n_cu = 256;
@@ -259,8 +259,8 @@ int gram_resident() {
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&krum_gram_kernel<RB>),
                                                      64 * kGramWaves, lds) != hipSuccess || per_cu < 1)
       per_cu = 1;
-    cached = n_cu * per_cu;
-  }
+    return n_cu * per_cu;
+  }();
   return cached;
 }
 
@@ -272,13 +272,11 @@ int gram_grid(int rb) {
 template <int RB>
 hipError_t launch_gram(const float* G, long long ldg, int m, long long d, float* partial, int grid, hipStream_t stream) {
   constexpr int lds = kGramWaves * RB * 32 * 64 * 4;
-  static bool attr_set = false;
-  if (!attr_set && lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static const hipError_t attr_err =
+      lds > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds)
+                      : hipSuccess;
+  if (attr_err != hipSuccess) return attr_err;
   hipLaunchKernelGGL(krum_gram_kernel<RB>, dim3(grid), dim3(64 * kGramWaves), lds, stream, G, ldg, m, d, partial);
   return hipGetLastError();
 }

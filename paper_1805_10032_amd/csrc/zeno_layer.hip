@@ -2,27 +2,28 @@
 // and separate launches of the pass at x, and the packing of the batch.  The kernel
 // itself lives in zeno_layer_impl.h and is compiled in four translation units
 // (zeno_layer_{bf16,f32}_{first,delta}.hip).
+#include <cstring>
+
 #include "zeno_layer_impl.h"
 
 namespace zeno {
 
-hipError_t launch_layer_bf16_delta(const LayerArgs& a, int MB, int NW, hipStream_t stream);
-hipError_t launch_layer_bf16_first(const LayerArgs& a, int MB, int NW, hipStream_t stream);
-hipError_t launch_layer_f32_delta(const LayerArgs& a, int MB, int NW, hipStream_t stream);
-hipError_t launch_layer_f32_first(const LayerArgs& a, int MB, int NW, hipStream_t stream);
+hipError_t launch_layer_bf16_delta(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
+hipError_t launch_layer_bf16_first(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
+hipError_t launch_layer_f32_delta(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
+hipError_t launch_layer_f32_first(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
 int wgs_per_cu_bf16_delta(int MB, int NW);
 int wgs_per_cu_bf16_first(int MB, int NW);
 int wgs_per_cu_f32_delta(int MB, int NW);
 int wgs_per_cu_f32_first(int MB, int NW);
 
 static int compute_units() {
-  static int n_cu = 0;
-  if (n_cu == 0) {
+  static const int n_cu = [] {
     int dev = 0, v = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
       v = 256;
-    n_cu = v;
-  }
+    return v;
+  }();
   return n_cu;
 }
 
@@ -46,6 +47,34 @@ static int nw_for(const LayerArgs& a, bool bf16, bool delta, int MB) {
   const long long wgs = (long long)job_tiles(a.cj, 256) * a.n_cand;
   const long long rounds = (wgs + slots - 1) / slots;
   return 10 * wgs >= 9 * rounds * slots ? 8 : 4;
+}
+
+int layer_nw(const LayerArgs& a, bool bf16, bool delta, int MB) { return nw_for(a, bf16, delta, MB); }
+
+// What a launch of workgroup width NW writes, from the kernel's own index formulas: the
+// host checks these against the workspace slots before anything is enqueued.
+LayerExtents layer_extents(const LayerArgs& a, bool bf16, int MB, int NW) {
+  LayerExtents e;
+  std::memset(&e, 0, sizeof(e));
+  const int esize = bf16 ? 2 : 4, wregs = bf16 ? 4 : 8, n_pad = 32 * MB;
+  auto tiled_bytes = [&](int Np) {
+    const long long last = bf16 ? tiled_index<true>(n_pad - 1, Np - 1, Np) : tiled_index<false>(n_pad - 1, Np - 1, Np);
+    return (last + 1) * esize;
+  };
+  if (a.has_base) {
+    const LayerJob& j = a.bj;
+    // every wave of every workgroup of the pass at x stores its 32-row tile of W, chunk by chunk
+    if (j.Wt != nullptr) e.wt_bytes = (long long)job_tiles(j, 32 * NW) * NW * (j.Kp >> 6) * wregs * 1024;
+    e.z0_floats = (long long)a.n_r * j.N;
+    if (!j.last) e.hbase_bytes = tiled_bytes(j.Np);
+  }
+  if (a.n_cand > 0) {
+    const LayerJob& j = a.cj;
+    if (j.last) e.dz_floats = (long long)a.n_cand * a.n_r * j.N;
+    else e.d_bytes_per_cand = tiled_bytes(j.Np);
+    e.norm_slots = job_tiles(j, 32 * NW);
+  }
+  return e;
 }
 
 int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB) { return job_tiles(a.cj, 32 * nw_for(a, bf16, delta, MB)); }
@@ -79,12 +108,12 @@ hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, i
   return hipGetLastError();
 }
 
-hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream) {
+hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream, LaunchShape* shape) {
   const int NW = nw_for(a, bf16, delta, MB);
   if (bf16) {
-    return delta ? launch_layer_bf16_delta(a, MB, NW, stream) : launch_layer_bf16_first(a, MB, NW, stream);
+    return delta ? launch_layer_bf16_delta(a, MB, NW, stream, shape) : launch_layer_bf16_first(a, MB, NW, stream, shape);
   }
-  return delta ? launch_layer_f32_delta(a, MB, NW, stream) : launch_layer_f32_first(a, MB, NW, stream);
+  return delta ? launch_layer_f32_delta(a, MB, NW, stream, shape) : launch_layer_f32_first(a, MB, NW, stream, shape);
 }
 
 }  // namespace zeno

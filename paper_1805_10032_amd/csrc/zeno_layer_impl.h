@@ -232,12 +232,15 @@ __device__ inline void wait_vmcnt() {
 // kernel waits for it explicitly (wait_vmcnt, loads complete in order) before the
 // workgroup barrier that publishes the buffer.  Hidden loads only make the
 // compiler's own counts for its ordinary loads stricter than needed, never laxer.
-// m0 (the LDS base of the copy) is written inside the statement and is not on the
-// clobber list: the compiler reserves it and uses it for nothing else in this file.
+// m0 (the LDS base of the copy) cannot be declared clobbered: the compiler treats it as a
+// reserved register and ignores such a declaration (with a warning).  The statement
+// therefore saves m0 in a scalar register of its own and restores it behind the copy, so
+// whatever the compiler keeps in m0 survives.
 __device__ inline void lds_dma16(const unsigned char* src, unsigned char* dst) {
   const unsigned lds_off = (unsigned)(uintptr_t)(lptr_t)dst;  // byte offset inside the workgroup's LDS
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :
+  unsigned saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
                : "v"(src), "s"(lds_off)
                : "memory");
 }
@@ -348,15 +351,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[mb][j] = 0.f;
 
-#ifdef ZENO_TIMING_EXPERIMENTS
-  // Timing experiments only (results are wrong): bit 0 skips the matrix products
-  // and their LDS reads, bit 1 the activation copies, bit 2 the staging writes,
-  // bit 3 the epilogue, bit 4 the norm.
-  const int dbg = a.dbg;
-#else
-  constexpr int dbg = 0;
-#endif
-  const bool do_norm = (a.norm_partials != nullptr) && !is_base && !(dbg & 16);
+  const bool do_norm = (a.norm_partials != nullptr) && !is_base;
   double nrm = 0.0;
 
   f32x4 u0[8], u1[8];
@@ -484,7 +479,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       for (int j = 0; j < 8; ++j) q += (u[j][0] * u[j][0] + u[j][1] * u[j][1]) + (u[j][2] * u[j][2] + u[j][3] * u[j][3]);
       nrm += (double)q;
     }
-    if (!(dbg & 4)) stage_tile<BF16>(u, stU, lane);
+    stage_tile<BF16>(u, stU, lane);
     if (DBUF) {
       // copies(c) were issued before U(c+1) [8 loads] and W(c+1) [WREGS loads]; the
       // last chunk has no such loads behind its copies and waits for everything
@@ -504,7 +499,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       } else {
         asm volatile("" ::: "memory");  // private buffers: only the compiler must not move LDS reads above the wait
       }
-      if ((STEADY || c + 1 < c_end) && !(dbg & 2)) copy_AD(c + 1, buf ^ 1);
+      if (STEADY || c + 1 < c_end) copy_AD(c + 1, buf ^ 1);
       __builtin_amdgcn_sched_barrier(0);  // the wait above counts on the copies being issued before the next loads
     } else {
       __syncthreads();  // single buffer: everyone is done with the previous chunk
@@ -539,7 +534,6 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     };
     f32x4 fr[NG][MB];
     f32x4 bq[KSTEPS];
-    if (dbg & 1) return;
     bq[0] = read_b(0);
     read_group(fr[0], 0);
 #pragma unroll
@@ -667,10 +661,6 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // row0 + 8 (j/4) + 4 h + j%4.  Four consecutive features of one sample are
   // adjacent in the tiled operand of the next layer, so a lane stores them as one
   // piece and a wave's store instruction covers one contiguous 512 B / 1 KB run.
-  if (dbg & 8) {
-    if (acc[0][0] == 12345.f) a.dZ[0] = 1.f;
-    return;
-  }
   const int n = lane & 31, h = lane >> 5;
   f32x4 bias[4];
 #pragma unroll
@@ -815,16 +805,21 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
 int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
 
 template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1>
-hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
+hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
   constexpr int BN = 32 * NW;
-  constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL * KS;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT, KS>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
+  if (shape != nullptr) {
+    shape->waves = NW;
+    shape->k_split = KS;
+    shape->streaming = NT ? 1 : 0;
+    shape->row_blocks = MB;
   }
+  constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL * KS;
+  // once per process and instantiation (initialisation of a local static is thread-safe)
+  static const hipError_t attr_err =
+      lds_bytes > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT, KS>),
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)
+                            : hipSuccess;
+  if (attr_err != hipSuccess) return attr_err;
   a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) + 7) / 8 * 8 : 0;
   int cand_blocks = 0;
   if (a.n_cand > 0) {
@@ -840,15 +835,14 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream) {
 // Workgroups of this instantiation that fit on one compute unit (cached).
 template <bool BF16, bool DELTA, int MB, int NW>
 int wgs_per_cu_inst() {
-  static int cached = 0;
-  if (cached == 0) {
+  static const int cached = [] {
     constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL;
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, false, 1>),
                                                      64 * NW, lds_bytes) != hipSuccess || n < 1)
       n = 1;
-    cached = n;
-  }
+    return n;
+  }();
   return cached;
 }
 
@@ -887,33 +881,33 @@ constexpr int split_k_waves() {
 }
 
 template <bool BF16, bool DELTA, int MB, int NW>
-hipError_t launch_nt(const LayerArgs& a, hipStream_t stream) {
+hipError_t launch_nt(const LayerArgs& a, hipStream_t stream, LaunchShape* shape) {
   // One-tile workgroups and every K of the launch long enough to split
   constexpr int KS = split_k_waves<BF16, DELTA, MB>();
   if constexpr (NW == 1 && KS > 0) {
     const bool base_ok = !a.has_base || (a.bj.Kp >> 6) >= 2 * KS;
     const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * KS;
     if ((a.has_base || a.n_cand > 0) && base_ok && cand_ok) {
-      if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, KS>(a, stream);
-      return launch_inst<BF16, DELTA, MB, NW, false, KS>(a, stream);
+      if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, KS>(a, stream, shape);
+      return launch_inst<BF16, DELTA, MB, NW, false, KS>(a, stream, shape);
     }
   }
-  if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream);
-  return launch_inst<BF16, DELTA, MB, NW, false>(a, stream);
+  if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream, shape);
+  return launch_inst<BF16, DELTA, MB, NW, false>(a, stream, shape);
 }
 
 template <bool BF16, bool DELTA, int MB>
-hipError_t launch_nw(const LayerArgs& a, int NW, hipStream_t stream) {
-  if (NW == 8) return launch_nt<BF16, DELTA, MB, 8>(a, stream);
-  if (NW == 4) return launch_nt<BF16, DELTA, MB, 4>(a, stream);
-  return launch_nt<BF16, DELTA, MB, 1>(a, stream);
+hipError_t launch_nw(const LayerArgs& a, int NW, hipStream_t stream, LaunchShape* shape) {
+  if (NW == 8) return launch_nt<BF16, DELTA, MB, 8>(a, stream, shape);
+  if (NW == 4) return launch_nt<BF16, DELTA, MB, 4>(a, stream, shape);
+  return launch_nt<BF16, DELTA, MB, 1>(a, stream, shape);
 }
 
 template <bool BF16, bool DELTA>
-hipError_t launch_mb(const LayerArgs& a, int MB, int NW, hipStream_t stream) {
-  if (MB == 1) return launch_nw<BF16, DELTA, 1>(a, NW, stream);
-  if (MB == 2) return launch_nw<BF16, DELTA, 2>(a, NW, stream);
-  return launch_nw<BF16, DELTA, 4>(a, NW, stream);
+hipError_t launch_mb(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape) {
+  if (MB == 1) return launch_nw<BF16, DELTA, 1>(a, NW, stream, shape);
+  if (MB == 2) return launch_nw<BF16, DELTA, 2>(a, NW, stream, shape);
+  return launch_nw<BF16, DELTA, 4>(a, NW, stream, shape);
 }
 
 // Waves per workgroup (32 output features each): the widest workgroup that still
@@ -941,8 +935,9 @@ int launch_nw_for(const LayerArgs& a) {
 // entry points the dispatcher in zeno_layer.hip calls.
 #define ZENO_LAYER_INSTANCE(NAME, BF16, DELTA)                                                    \
   namespace zeno {                                                                                \
-  hipError_t launch_layer_##NAME(const LayerArgs& a, int MB, int NW, hipStream_t stream) {        \
-    return launch_mb<BF16, DELTA>(a, MB, NW, stream);                                             \
+  hipError_t launch_layer_##NAME(const LayerArgs& a, int MB, int NW, hipStream_t stream,          \
+                                 LaunchShape* shape) {                                            \
+    return launch_mb<BF16, DELTA>(a, MB, NW, stream, shape);                                      \
   }                                                                                               \
   int wgs_per_cu_##NAME(int MB, int NW) { return wgs_per_cu_mb<BF16, DELTA>(MB, NW); }            \
   }

@@ -56,8 +56,11 @@ __global__ __launch_bounds__(64) void loss_diff_kernel(const float* __restrict__
     }
     s0 = wave_sum(s0);
     s1 = wave_sum(s1);
+    // a label outside [0, C) has no logit: the sample's loss difference becomes NaN (and with it
+    // every score) instead of reading past the row
     const int y = labels[chunk_begin + kk];
-    diff = ((m1 + log(s1)) - (m0 + log(s0))) - (double)dz[y];
+    const double dzy = (y >= 0 && y < C) ? (double)dz[y] : __builtin_nan("");
+    diff = ((m1 + log(s1)) - (m0 + log(s0))) - dzy;
   }
   if (lane == 0) sample_diff[(long long)i * n_r_total + chunk_begin + kk] = diff;
 }

@@ -31,13 +31,13 @@ def oracle_terms(w, rows=None):
     return s_exact, scale
 
 
-def exact_terms(w, rows=None):
-    """(scores, scale) from the float64 oracle."""
+def exact_terms(w, rows=None, with_losses=False):
+    """(scores, scale) from the float64 oracle; with_losses: also |f_r(x)| + |f_r(x - gamma u)| per row."""
     x = npy(w.x).astype(np.float64)
     args = (w.dims, w.has_bias, w.loss, npy(w.features), npy(w.labels), npy(w.targets))
     f0 = O.f_r(x, *args)
     idx = list(range(w.m)) if rows is None else list(rows)
-    s, scale = np.empty(len(idx)), np.empty(len(idx))
+    s, scale, mag = np.empty(len(idx)), np.empty(len(idx)), np.empty(len(idx))
     for n, i in enumerate(idx):
         u = npy(w.G[i]).astype(np.float64)
         with np.errstate(invalid="ignore", over="ignore"):
@@ -45,6 +45,9 @@ def exact_terms(w, rows=None):
             pen = w.rho * float(u @ u)
             s[n] = f0 - fi - pen
             scale[n] = abs(f0 - fi) + pen
+            mag[n] = abs(f0) + abs(fi)
+    if with_losses:
+        return s, scale, mag
     return s, scale
 
 
@@ -80,22 +83,34 @@ def score_error(s_gpu, s_ref, scale):
     return err
 
 
-def check_selection(sel_gpu, s_ref, b, tol_abs):
-    """Exact set equality when the oracle's gap at the cut exceeds tol_abs;
-    otherwise every chosen row must be within tol_abs of the cut."""
+def check_selection(sel_gpu, s_ref, b, tol, scale=None):
+    """Definition 3 against reference scores s_ref: exact set equality when the reference's gap at
+    the cut exceeds the tolerance; otherwise every chosen row must lie within the tolerance of the
+    cut.  The tolerance is relative (tol x scale[i], the error scale of each row's score) when
+    `scale` is given, so that one huge-penalty row elsewhere cannot slacken the rule at a cut between
+    two small-scale rows; without `scale`, tol is absolute."""
     m = len(s_ref)
     ref_sel = O.select(s_ref, b)
     sel_gpu = np.asarray(sel_gpu, dtype=np.int64)
     assert len(sel_gpu) == m - b and np.all(np.diff(sel_gpu) > 0)
     if b == 0:
         assert np.array_equal(sel_gpu, ref_sel)
-        return
-    key = np.where(np.isnan(s_ref), -np.inf, s_ref)
-    order = np.sort(key)[::-1]
-    lo_in, hi_out = order[m - b - 1], order[m - b]
-    if lo_in - hi_out > tol_abs:
-        assert np.array_equal(sel_gpu, ref_sel), (sel_gpu, ref_sel)
+        return "exact"
+    key = np.where(np.isnan(s_ref), -np.inf, np.asarray(s_ref, dtype=np.float64))
+    order = sorted(range(m), key=lambda i: (-key[i], i))
+    i_in, i_out = order[m - b - 1], order[m - b]          # last row kept, first row trimmed
+    lo_in, hi_out = key[i_in], key[i_out]
+    if scale is None:
+        tol_abs = np.full(m, float(tol))
     else:
-        chosen = np.zeros(m, dtype=bool)
-        chosen[sel_gpu] = True
-        assert np.all(key[chosen] >= hi_out - tol_abs) and np.all(key[~chosen] <= lo_in + tol_abs)
+        sc = np.asarray(scale, dtype=np.float64)
+        tol_abs = np.where(np.isfinite(sc), tol * sc, 0.0)
+    # both scores may be off by their own tolerance
+    if lo_in - hi_out > tol_abs[i_in] + tol_abs[i_out]:
+        assert np.array_equal(sel_gpu, ref_sel), (sel_gpu, ref_sel)
+        return "exact"
+    chosen = np.zeros(m, dtype=bool)
+    chosen[sel_gpu] = True
+    slack = tol_abs + max(tol_abs[i_in], tol_abs[i_out])
+    assert np.all(key[chosen] >= hi_out - slack[chosen]) and np.all(key[~chosen] <= lo_in + slack[~chosen])
+    return "near-tie"

@@ -1,0 +1,136 @@
+"""Every instantiation of the streaming layer kernel that a caller can reach at scale is executed
+here at sizes the float64 oracle scores in seconds, ALL rows compared: four- and eight-wave
+workgroups in fp32 and bf16, with and without the second matrix product, one, two and four
+32-sample row blocks, densely packed rows (plain loads) and rows on 128-byte lines (streaming
+loads), ragged widths, and the pass at x riding in an eight-wave candidate launch.  Which launch
+shapes really ran is read back from the library's per-launch records and asserted, so the
+coverage cannot silently move when the dispatch heuristics change."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1805_10032_amd import workloads as WL
+from tests._util import SCORE_TOL, check_selection, exact_terms, npy, oracle_terms, rows_to_gpu, score_error
+
+pytestmark = pytest.mark.gpu
+
+SEEN = set()     # (fwd, second product, waves, k_split, streaming, row_blocks, merged) of every layer launch
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1805_10032_amd import binding
+    binding.load_library()
+    return binding
+
+
+_CACHE = {}
+
+
+def _workload(key, dims, m, b, n_r, fwd, n_flip, n_noise):
+    """Workloads and their oracle scores are shared by the row-pitch variants of a case."""
+    if key not in _CACHE:
+        _CACHE.clear()           # one big case at a time in host memory
+        w = WL.make_mlp_workload(f"inst{key}", 60, dims, m, b, n_r, 0.05, 1e-3, fwd, seed=len(dims) + n_r,
+                                 n_flip=n_flip, n_noise=n_noise, noise_std=5.0, worker_batch=16)
+        s_ref, scale = oracle_terms(w)
+        s_exact = exact_terms(w)[0] if fwd == "bf16" else s_ref
+        _CACHE[key] = (w, s_ref, s_exact, scale)
+    return _CACHE[key]
+
+
+def _run(B, w, s_ref, s_exact, scale, row_align):
+    dev = torch.device("cuda", 0)
+    mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
+    G = rows_to_gpu(B, w.G, row_align, dev)
+    B.profile_enable(True)
+    try:
+        s = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
+        torch.cuda.synchronize()
+        recs = B.profile_collect(detail=True)
+    finally:
+        B.profile_enable(False)
+    shapes = []
+    for r in recs:
+        if r["kernel"] in ("layer_base", "layer_cand"):
+            shape = (w.fwd, r["second"], r["waves"], r["k_split"], r["streaming"], r["row_blocks"], r["merged"])
+            SEEN.add(shape)
+            shapes.append((r["kernel"], r["layer"]) + shape[1:])
+    tol = SCORE_TOL[w.fwd]
+    err = score_error(npy(s), s_ref, scale)
+    assert np.all(err <= tol), (w.name, row_align, float(err.max()), int(err.argmax()), shapes)
+    if w.fwd == "bf16":   # every layer is at least 512 wide on its input side: the float64 definition at 1e-2 too
+        err_exact = score_error(npy(s), s_exact, scale)
+        assert np.all(err_exact <= tol), (w.name, row_align, float(err_exact.max()), shapes)
+    out, sel = B.zeno_aggregate(G, s, w.b)
+    torch.cuda.synchronize()
+    check_selection(npy(sel), s_exact, w.b, tol, scale)
+    return shapes
+
+
+# dims, m, b, n_r: wide layers so that (feature tiles x candidates) reaches 256 workgroups
+WIDE = [1024, 2048, 1024, 10]
+
+
+@pytest.mark.parametrize("row_align", [1, 32])
+@pytest.mark.parametrize("n_r", [32, 64, 128])
+@pytest.mark.parametrize("fwd", ["fp32", "bf16"])
+def test_wide_layers_all_rows(B, fwd, n_r, row_align):
+    """2048- and 1024-wide layers with 64 candidates: eight- (or four-) wave workgroups in the first
+    layer and in the layer with the second product, a ten-class layer behind them; one, two and
+    four row blocks; d mod 4 = 2, so densely packed odd rows are only 8-byte aligned."""
+    w, s_ref, s_exact, scale = _workload(("wide", fwd, n_r), WIDE, 64, 20, n_r, fwd, 12, 8)
+    shapes = _run(B, w, s_ref, s_exact, scale, row_align)
+    print(f"\n  wide {fwd} n_r={n_r} align={row_align}: {shapes}")
+    cand = [s for s in shapes if s[0] == "layer_cand"]
+    assert all(s[5] == (row_align == 32) for s in cand)                         # streaming loads iff line-aligned
+    assert all(s[6] == {32: 1, 64: 2, 128: 4}[n_r] for s in cand)
+    assert all(s[3] >= 4 for s in cand if s[1] < 2), cand                       # the wide layers run in wide workgroups
+
+
+@pytest.mark.parametrize("row_align", [1, 32])
+@pytest.mark.parametrize("fwd", ["fp32", "bf16"])
+def test_ragged_widths_in_wide_workgroups(B, fwd, row_align):
+    """Input widths that are not multiples of 64 (element-wise guards in the last chunk) and output
+    widths that leave the last feature tile of a four- or eight-wave workgroup partly empty."""
+    w, s_ref, s_exact, scale = _workload(("ragged", fwd), [1000, 1100, 520, 10], 64, 20, 48, fwd, 12, 8)
+    shapes = _run(B, w, s_ref, s_exact, scale, row_align)
+    print(f"\n  ragged {fwd} align={row_align}: {shapes}")
+    cand = [s for s in shapes if s[0] == "layer_cand"]
+    assert all(s[3] >= 4 for s in cand if s[1] < 2), cand
+
+
+@pytest.mark.parametrize("fwd", ["bf16", "fp32"])
+def test_pass_at_x_rides_in_an_eight_wave_launch(B, fwd):
+    """A ten-class output layer behind a 2048-wide hidden layer with m = 60: the candidates' launch of
+    the hidden layer has 480 eight-wave workgroups, so the pass at x through the output layer rides in
+    it, and all eight waves of its one workgroup store their (mostly empty) tile of W in operand order.
+    Those stores must stay inside the slot of that copy: the candidates' D operand lies behind it."""
+    w, s_ref, s_exact, scale = _workload(("merge8", fwd), [1024, 2048, 2048, 10], 60, 20, 64, fwd, 12, 8)
+    shapes = _run(B, w, s_ref, s_exact, scale, 32)
+    print(f"\n  merge8 {fwd}: {shapes}")
+    merged = [s for s in shapes if s[0] == "layer_cand" and s[7] == 1]
+    assert any(s[3] == 8 for s in merged), shapes
+
+
+def test_zz_which_instantiations_ran(B):
+    """The cases above, between them, executed every (operand type, second product, workgroup width,
+    loads, row blocks) combination that the dispatch can pick for a large model."""
+    if not SEEN:
+        pytest.skip("runs after the cases of this file")
+    missing = []
+    for fwd in ("fp32", "bf16"):
+        for second in (0, 1):
+            for streaming in (0, 1):
+                for mb in (1, 2, 4):
+                    if not any(s[0] == fwd and s[1] == second and s[2] in (4, 8) and s[4] == streaming and s[5] == mb
+                               for s in SEEN):
+                        missing.append((fwd, second, "4|8 waves", streaming, mb))
+        for waves in (4, 8):
+            for second in (0, 1):
+                if not any(s[0] == fwd and s[1] == second and s[2] == waves for s in SEEN):
+                    missing.append((fwd, second, waves))
+        if not any(s[0] == fwd and s[3] > 1 for s in SEEN):
+            missing.append((fwd, "k_split"))
+    print("\n  launch shapes seen:", sorted(SEEN))
+    assert not missing, missing

@@ -118,3 +118,25 @@ def test_krum_error_codes(B):
     with pytest.raises(B.ZenoError) as e:
         B.zeno_krum(G, 1, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     assert e.value.status == 3
+
+
+def test_krum_non_finite_rows(B):
+    """'Arbitrary values' (Section 3, Eq. 1): a row that holds NaN or Inf is infinitely far from every
+    row.  It is nobody's near neighbour, its own score is +inf, and the scores of the other rows are
+    those of the matrix without it (with one neighbour more to sum)."""
+    g = torch.Generator().manual_seed(5)
+    m, d, b = 12, 515, 3
+    G = torch.randn(1, d, generator=g) + 0.5 * torch.randn(m, d, generator=g)
+    G[4, 100] = float("nan")
+    G[9, 7] = float("inf")
+    ref = O.krum_scores(npy(G), b)
+    assert ref[4] == np.inf and ref[9] == np.inf
+    out, chosen, ks = B.zeno_krum(G.cuda(), b)
+    torch.cuda.synchronize()
+    ks = npy(ks).astype(np.float64)
+    assert ks[4] == np.inf and ks[9] == np.inf
+    ok = [i for i in range(m) if i not in (4, 9)]
+    sq = (npy(G[ok]).astype(np.float64) ** 2).sum(1)
+    assert np.all(np.abs(ks[ok] - ref[ok]) <= DIST_TOL * (m - b - 2) * 4.0 * sq.max())
+    idx = int(chosen.item())
+    assert idx not in (4, 9) and np.array_equal(npy(out), npy(G[idx]))

@@ -19,22 +19,27 @@ def B():
     return binding
 
 
-def _check_step(B, w, tol=None, row_align=1, exact_bound=5e-2):
+def _check_step(B, w, tol=None, row_align=1, exact_bound=None):
+    """Scores against the oracle at `tol`, selection (Definition 3) against the oracle's scores, and
+    the aggregate.  bf16 forward: the reference at `tol` is the oracle's bf16-operand variant; the
+    distance to the float64 definition itself is gated too: at the same 1e-2 where every layer is
+    at least 512 wide on its input side (the operand rounding errors average out over K), else at
+    `exact_bound` (default 5e-2), a stated limit of the bf16 mode on narrow layers."""
     tol = SCORE_TOL[w.fwd] if tol is None else tol
     s_gpu = gpu_scores(B, w, row_align=row_align)
     s_ref, scale = oracle_terms(w)
     err = score_error(npy(s_gpu), s_ref, scale)
     assert np.all(err <= tol), (w.name, err.max(), int(err.argmax()))
     if w.fwd == "bf16":
-        # distance to the float64 definition: bounded by the forward error of bf16 operands
+        if exact_bound is None:
+            exact_bound = SCORE_TOL["bf16"] if min(w.dims[:-1]) >= 512 else 5e-2
         s_exact, _ = exact_terms(w)
         err_exact = score_error(npy(s_gpu), s_exact, scale)
         print(f"{w.name}: bf16 path vs contract {err.max():.2e}, vs float64 definition {err_exact.max():.2e}")
-        assert exact_bound is None or np.all(err_exact <= exact_bound), (w.name, err_exact.max())
+        assert np.all(err_exact <= exact_bound), (w.name, err_exact.max())
     out, sel = B.zeno_aggregate(rows_to_gpu(B, w.G, row_align), s_gpu, w.b)
     torch.cuda.synchronize()
-    finite = np.isfinite(scale)
-    check_selection(npy(sel), s_ref, w.b, tol * float(np.max(scale[finite])) if finite.any() else 0.0)
+    check_selection(npy(sel), s_ref, w.b, tol, scale)
     # the aggregate of the rows the GPU chose, against the oracle's average of the same rows
     ref = np.zeros(w.d)
     for i in npy(sel):
@@ -120,11 +125,26 @@ def test_small_server_batches(B, cfg, n_r):
     n_r = 1 suffices in theory.  Same kernels, one 32-row block of which n_r rows are live."""
     w = WL.make_config(cfg, n_r=n_r)
     assert w.n_r == n_r
-    # Workload 2's faulty rows are N(0, 200^2) noise: their logits move by ~1e4 and, with one or a
-    # few samples, lse(z0 + dz) - dz[y] cancels most of that, so the fp32 rounding of dz (6e-8
-    # relative to ~1e4) shows at a few 1e-5 of the score scale; nothing averages it away as the 32
-    # samples of the full workload do.  Those rows are gated at 1e-4, everything else at 1e-5.
-    _check_step(B, w, tol=1e-4 if cfg == 2 else None)
+    if (cfg, n_r) != (2, 1):
+        _check_step(B, w)
+        return
+    # One sample, softmax regression: every row is gated at 1e-5 of |f_r(x) - f_r(x - gamma u)| +
+    # rho ||u||^2 except honest rows whose loss hardly moves on that single sample although their
+    # logits do.  Row 13 of this workload: logits move by O(1), the loss by 2.3e-4 (its gradient is
+    # nearly orthogonal to the sample's), so lse(z0 + dz) - lse(z0) - dz[y] cancels four digits and
+    # the float32 accumulation error of dz (about 1e-7 |dz|) is 3e-5 .. 7e-5 of the 3.8e-3 scale.
+    # Against the magnitudes that enter the score, |f_r(x)| + |f_r(x - gamma u)| + rho ||u||^2
+    # (the other scale the tolerance was proposed on), the same row is right to 1e-7.
+    s_gpu = npy(gpu_scores(B, w)).astype(np.float64)
+    s_ref, scale, mag = exact_terms(w, with_losses=True)
+    err = score_error(s_gpu, s_ref, scale)
+    strict_ok = err <= 1e-5
+    mixed_err = np.abs(s_gpu - s_ref) / (mag + scale)
+    cancelling = scale <= 2e-3 * mag            # |f0 - fi| + penalty three digits below the losses themselves
+    assert np.all(strict_ok | (cancelling & (mixed_err <= 1e-6))), (err, mixed_err)
+    assert np.count_nonzero(~strict_ok) <= 1 and np.all(err <= 1e-4)
+    _, sel = B.zeno_aggregate(w.G.cuda(), torch.from_numpy(s_gpu.astype(np.float32)).cuda(), w.b)
+    check_selection(npy(sel), s_ref, w.b, 1e-5, np.where(strict_ok, scale, 10 * scale))
 
 
 @pytest.mark.parametrize("fwd", ["fp32", "bf16"])
@@ -132,8 +152,10 @@ def test_single_sample_deep_net(B, fwd):
     w = WL.make_mlp_workload("nr1", 96, [200, 130, 70, 33, 6], 9, 3, 1, 0.1, 1e-3, fwd, n_flip=2, n_noise=1,
                              worker_batch=16)
     # one sample through four small bf16 layers: the contract is met to 2e-7, but nothing averages the
-    # operand rounding, so the distance to the float64 definition (0.11 here) is reported, not bounded
-    _check_step(B, w, exact_bound=None)
+    # operand rounding (one sample, K = 33..200), so the distance to the float64 definition is the
+    # operand rounding itself: 0.11 of the score scale here, gated at 0.2 as a stated limit of the
+    # bf16 mode at n_r = 1 on narrow layers
+    _check_step(B, w, exact_bound=0.2)
 
 
 def test_workspace_contents_do_not_matter(B):
@@ -164,10 +186,10 @@ def test_maximum_number_of_candidates(B, fwd):
     per feature tile, selection over 1024 scores), with faulty rows of both kinds."""
     w = WL.make_mlp_workload("maxm", 92, [48, 40, 5], 1024, 300, 16, 0.1, 1e-3, fwd, n_flip=100, n_noise=200,
                              noise_std=3.0)
-    # The distance of the bf16 forward to the float64 definition is printed, not gated: it is the
-    # operand rounding itself, and the largest of 1024 rows (5.7e-2 of the score scale) lies
-    # beyond the bound that the other tests' handful of rows stays within.
-    _check_step(B, w, exact_bound=None)
+    # Distance of the bf16 forward to the float64 definition on 40/48-wide layers: the operand
+    # rounding itself; the largest of 1024 rows measures 5.7e-2 of the score scale and is gated at
+    # 0.1, a stated limit of the bf16 mode on layers this narrow.
+    _check_step(B, w, exact_bound=0.1)
 
 
 def test_gamma_zero_and_rho_zero(B):

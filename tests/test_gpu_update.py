@@ -137,7 +137,8 @@ def test_training_loop_zeno_descends_where_mean_and_median_ascend(B):
 @pytest.mark.parametrize("attack,disjoint", [("bit_flip", False), ("label_flip", False), ("label_flip", True)])
 def test_training_loop_under_the_failures_of_section_6(B, attack, disjoint):
     """Algorithm 1 with q = 12 of m = 20 workers failing as Sections 6.3-6.5 describe, every
-    server-side rule in the HIP library (Zeno with b = 12, Mean, Median, Krum with b = 12).
+    server-side rule in the HIP library (Zeno with b = 12, Mean, Median, and Krum with b = 8, the
+    largest value Definition 5's condition 2b + 2 < m admits at m = 20 and the paper's own choice).
     What is asserted is what those sections claim and what the oracle's run of this recipe
     shows over several seeds (start 3.14; Zeno 1.46-1.55 i.i.d. and 1.83-1.93 on disjoint data):
       bit flipping            Zeno descends, the three baselines end above where they started;
@@ -147,6 +148,8 @@ def test_training_loop_under_the_failures_of_section_6(B, attack, disjoint):
     Teacher-labelled synthetic data stands in for CIFAR-10."""
     dev = torch.device("cuda")
     dims, m, q, b, n_r, gamma, rho, T = [48, 64, 10], 20, 12, 12, 32, 0.1, 5e-4, 80
+    b_krum = 8
+    assert 2 * b_krum + 2 < m
     feats, labels = _teacher_task(7, dims, 8192, dev)
     shards = WL.class_sorted_shards(labels, m) if disjoint else None
     mdl = B.ZenoModel(dims, True, "softmax_ce", "fp32")
@@ -178,7 +181,7 @@ def test_training_loop_under_the_failures_of_section_6(B, attack, disjoint):
                                  workspace=ws)
                 B.zeno_aggregate_update(G, s, b, gamma, x, x_next=x, want_out=False, want_selected=False)
             else:
-                v = B.zeno_mean(G) if rule == "mean" else B.zeno_median(G) if rule == "median" else B.zeno_krum(G, b)[0]
+                v = B.zeno_mean(G) if rule == "mean" else B.zeno_median(G) if rule == "median" else B.zeno_krum(G, b_krum)[0]
                 x = x - gamma * v
         final[rule] = full_loss(x)
     print(f"{attack}{' disjoint' if disjoint else ''}: start {start:.3f}  " +

@@ -75,3 +75,32 @@ def test_missing_library_fails_loudly(B, tmp_path):
             B.load_library(str(tmp_path / "nope.so"))
     finally:
         B._lib = saved
+
+
+PLAN_SHAPES = [
+    # dims, fwd
+    ([3072, 2048, 2048, 10], "bf16"),          # a ten-class layer behind wide hidden layers
+    ([3072, 2048, 2048, 10], "fp32"),
+    ([4096, 4096, 4096, 4096, 1000], "bf16"),
+    ([3072, 2048, 2048, 2048, 10], "bf16"),
+    ([3072, 512, 10], "fp32"),
+    ([784, 10], "fp32"),
+    ([64, 1], "fp32"),
+    ([300, 129, 65, 33, 7], "bf16"),           # widths that are not multiples of 32/64/128/256
+    ([300, 129, 65, 33, 7], "fp32"),
+    ([1024, 257, 385, 3], "bf16"),
+    ([64, 128, 64, 32, 16, 8, 4, 3, 2], "fp32"),
+]
+
+
+@pytest.mark.parametrize("dims,fwd", PLAN_SHAPES)
+def test_every_launch_stays_inside_its_workspace_slot(B, dims, fwd):
+    """Host-only walk over the launch sequence of zeno_score: whatever workgroup width a launch takes
+    (one, four or eight waves), the rows of W it copies in operand order, the activations, the
+    pre-activations and the partial norms it writes lie inside their workspace slots."""
+    loss = "squared" if dims[-1] == 1 else "softmax_ce"
+    mdl = B.ZenoModel(dims, True, loss, fwd)
+    for m in (1, 7, 60, 64, 100, 1024):
+        for n_r in (1, 32, 33, 64, 128, 300):
+            assert mdl.plan_check(m, n_r) == 0, (dims, fwd, m, n_r)
+    assert mdl.plan_check(0, 4) == 1 and mdl.plan_check(4, 0) == 1

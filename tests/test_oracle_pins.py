@@ -286,9 +286,57 @@ def test_discussion_one_dimensional_example():
     G = np.array(vals["candidates"], dtype=np.float64)[:, None]
     b = int(vals["b"][0])
     chosen, idx = O.krum(G, b)
-    assert chosen[0] == vals["krum"][0] and idx in (0, 1)
+    assert chosen[0] == vals["krum"][0] and idx == 0          # ties go to the lower index
+    np.testing.assert_allclose(O.krum_scores(G, b), vals["krum_scores"], rtol=1e-14)
     assert abs(O.mean(G)[0] - vals["mean"][0]) < 1e-15
     assert abs(O.median(G)[0] - vals["median"][0]) < 1e-15
+
+
+def test_krum_two_dimensional_hand_example():
+    """Definition 5 with d = 2: hand-derived scores; the case separates the definition from its
+    usual slips (self as neighbour, m-b-1 neighbours, unsquared distances, one coordinate)."""
+    vals = {}
+    with open(os.path.join(GOLDEN, "krum_2d_example.txt")) as fh:
+        for line in fh:
+            if line.startswith("#") or ":" not in line:
+                continue
+            k, v = line.split(":")
+            vals[k.strip()] = [float(t) for t in v.split()]
+    G = np.array(vals["candidates"], dtype=np.float64).reshape(-1, 2)
+    b = int(vals["b"][0])
+    np.testing.assert_array_equal(O.krum_scores(G, b), vals["krum_scores"])
+    chosen, idx = O.krum(G, b)
+    assert idx == int(vals["chosen"][0]) and np.array_equal(chosen, G[idx])
+    # the same rows in another order: scores follow the rows
+    perm = [4, 0, 3, 1, 2]
+    np.testing.assert_array_equal(O.krum_scores(G[perm], b), np.array(vals["krum_scores"])[perm])
+
+
+def test_krum_against_pairwise_distances_from_scipy():
+    """Random rows: the oracle's sums equal the m-b-2 smallest off-diagonal entries of the squared
+    Euclidean distance matrix a library routine returns."""
+    from scipy.spatial.distance import cdist
+    rng = np.random.default_rng(8)
+    G = rng.normal(size=(9, 17))
+    D2 = cdist(G, G, "sqeuclidean")
+    for b in (0, 2, 5):
+        ref = [np.sort(np.delete(D2[i], i))[:9 - b - 2].sum() for i in range(9)]
+        np.testing.assert_allclose(O.krum_scores(G, b), ref, rtol=1e-12)
+
+
+def test_krum_non_finite_rows_are_infinitely_far():
+    """'Arbitrary values' (Section 3, Eq. 1) include NaN and Inf; Definition 5 is silent on them.
+    Reading: a row holding one is at infinite distance from every row, so it is nobody's near
+    neighbour and its own score is +inf."""
+    rng = np.random.default_rng(9)
+    G = rng.normal(size=(7, 5))
+    clean = O.krum_scores(np.delete(G, 2, axis=0), 1)      # b = 1 among the six finite rows: 3 neighbours
+    G[2, 3] = np.nan
+    s = O.krum_scores(G, 2)                                 # b = 2 among seven rows: also 3 neighbours
+    assert s[2] == np.inf
+    np.testing.assert_allclose(np.delete(s, 2), clean, rtol=1e-14)
+    G[2, 3] = np.inf
+    assert O.krum_scores(G, 2)[2] == np.inf and O.krum(G, 2)[1] != 2
 
 
 # ---------------------------------------------------------------- server update (Algorithm 1)
