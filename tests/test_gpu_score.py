@@ -32,7 +32,7 @@ def _check_step(B, w, tol=None, row_align=1, exact_bound=None):
     assert np.all(err <= tol), (w.name, err.max(), int(err.argmax()))
     if w.fwd == "bf16":
         if exact_bound is None:
-            exact_bound = SCORE_TOL["bf16"] if min(w.dims[:-1]) >= 512 else 5e-2
+            exact_bound = 2e-2 if min(w.dims[:-1]) >= 512 else 5e-2
         s_exact, _ = exact_terms(w)
         err_exact = score_error(npy(s_gpu), s_exact, scale)
         print(f"{w.name}: bf16 path vs contract {err.max():.2e}, vs float64 definition {err_exact.max():.2e}")
