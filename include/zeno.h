@@ -126,6 +126,22 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
                          const zeno_batch_t* batch, float gamma, float rho, float* scores,
                          void* workspace, size_t workspace_bytes, void* stream);
 
+/* zeno_score for callers that cannot allocate device memory and have no workspace to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as zeno_score, bit for bit, but the scratch is a static device
+ * array inside the library (ZENO_STATIC_SCRATCH_BYTES per GPU, held until the process ends), so
+ * the call allocates nothing, frees nothing and takes no workspace.
+ *   UNSUPPORTED if zeno_score_workspace_bytes(model, m, n_r) exceeds ZENO_STATIC_SCRATCH_BYTES
+ *     (32 MiB covers e.g. a 3072->512->10 model with m = 20, or the paper's m = 20, n_r = 4 on
+ *     far larger models; it does not cover hundreds of candidates on 2048-wide layers);
+ *   DEVICE if the array's address cannot be obtained on the current device.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race and give wrong scores; calls on one stream are ordered and safe.  The array
+ * keeps the previous call's contents; no call depends on them. */
+#define ZENO_STATIC_SCRATCH_BYTES (32u << 20)
+zeno_status_t zeno_score_static(const zeno_model_t* model, const float* x, const float* G, int64_t ldg, int32_t m,
+                                const zeno_batch_t* batch, float gamma, float rho, float* scores, void* stream);
+
 /* Definition 3: out = (1/(m-b)) * sum of the m-b rows of G with the highest
  * scores, 0 <= b < m (b = 0 is the Mean).  The selection runs on the device
  * from `scores` (no host round trip); rows are summed in ascending index order

@@ -22,7 +22,7 @@ FWD = {"fp32": 0, "bf16": 1}
 STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported size", 3: "workspace", 4: "device"}
 
 EXPORTS = ["zeno_model_create", "zeno_model_destroy", "zeno_model_num_params",
-           "zeno_score_workspace_bytes", "zeno_score", "zeno_aggregate", "zeno_aggregate_update", "zeno_mean",
+           "zeno_score_workspace_bytes", "zeno_score", "zeno_score_static", "zeno_aggregate", "zeno_aggregate_update", "zeno_mean",
            "zeno_median", "zeno_krum_workspace_bytes", "zeno_krum", "zeno_status_string", "zeno_profile_enable", "zeno_profile_collect",
            "zeno_score_plan_check"]
 
@@ -83,6 +83,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.zeno_score.argtypes = [vp, vp, vp, i64, i32, ctypes.POINTER(_Batch), f32, f32, vp, vp,
                                ctypes.c_size_t, vp]
     lib.zeno_score.restype = ctypes.c_int
+    lib.zeno_score_static.argtypes = [vp, vp, vp, i64, i32, ctypes.POINTER(_Batch), f32, f32, vp, vp]
+    lib.zeno_score_static.restype = ctypes.c_int
     lib.zeno_aggregate.argtypes = [vp, i64, vp, i32, i64, i32, vp, vp, vp]
     lib.zeno_aggregate.restype = ctypes.c_int
     lib.zeno_aggregate_update.argtypes = [vp, i64, vp, i32, i64, i32, f32, vp, vp, vp, vp, vp]
@@ -224,6 +226,33 @@ def zeno_score(model: ZenoModel, x, G, features, gamma, rho, *, labels=None, tar
                         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream())
     if st != 0:
         raise ZenoError(st, "zeno_score")
+    return scores
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def zeno_score_static(model: ZenoModel, x, G, features, gamma, rho, *, labels=None, targets=None, scores=None):
+    """zeno_score on the library's static scratch array: no workspace, nothing allocated by the call
+    (pass `scores` to keep the binding from allocating the output either)."""
+    lib = load_library()
+    m, d = int(G.shape[0]), int(G.shape[1])
+    if d != model.num_params or x.numel() != d:
+        raise ValueError("x / G do not match the model's parameter count")
+    if features.shape[1] != model.dims[0]:
+        raise ValueError("features do not match the model's input width")
+    batch = _Batch()
+    batch.n_r = int(features.shape[0])
+    batch.features = _dev(features, torch.float32, "features")
+    batch.labels = _dev(labels, torch.int32, "labels") if labels is not None else None
+    batch.targets = _dev(targets, torch.float32, "targets") if targets is not None else None
+    if scores is None:
+        scores = torch.empty(m, dtype=torch.float32, device=G.device)
+    g_ptr, ldg = _rows(G)
+    st = lib.zeno_score_static(model._h, _dev(x, torch.float32, "x"), g_ptr, ldg, m, ctypes.byref(batch),
+                               float(gamma), float(rho), _dev(scores, torch.float32, "scores"), _stream())
+    if st != 0:
+        raise ZenoError(st, "zeno_score_static")
     return scores
 
 

@@ -17,6 +17,11 @@ struct zeno_model {
   int64_t d;
 };
 
+// Scratch of zeno_score_static: a file-scope device array, one copy per GPU at that GPU's own
+// address, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress, never an address to pass to a kernel.
+static __device__ __align__(256) unsigned char scratch[ZENO_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace zeno;
@@ -349,6 +354,28 @@ zeno_status_t score_enqueue(const zeno_model* model, const Plan& p, const float*
   return ZENO_OK;
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t static_scratch(unsigned char** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = reinterpret_cast<unsigned char*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -420,6 +447,19 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
   if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < p.total) return ZENO_ERR_WORKSPACE;
   return score_enqueue(model, p, x, G, ldg, m, batch, gamma, rho, scores, reinterpret_cast<unsigned char*>(workspace),
                        reinterpret_cast<hipStream_t>(stream_));
+}
+
+zeno_status_t zeno_score_static(const zeno_model_t* model, const float* x, const float* G, int64_t ldg, int32_t m,
+                                const zeno_batch_t* batch, float gamma, float rho, float* scores, void* stream_) {
+  zeno_status_t st = check_score_args(model, x, G, ldg, m, batch, gamma, rho, scores);
+  if (st != ZENO_OK) return st;
+  const Plan p = make_plan(model, m, batch->n_r);
+  if (p.total > (size_t)ZENO_STATIC_SCRATCH_BYTES) return ZENO_ERR_UNSUPPORTED;
+  unsigned char* ws = nullptr;
+  if (static_scratch(&ws) != hipSuccess) return ZENO_ERR_DEVICE;
+  // Every slot of the layout is written by an earlier launch of the same call before a later one
+  // reads it, so nothing left behind by the previous call has to be cleared.
+  return score_enqueue(model, p, x, G, ldg, m, batch, gamma, rho, scores, ws, reinterpret_cast<hipStream_t>(stream_));
 }
 
 zeno_status_t zeno_score_plan_check(const zeno_model_t* model, int32_t m, int32_t n_r) {

@@ -104,3 +104,14 @@ def test_every_launch_stays_inside_its_workspace_slot(B, dims, fwd):
         for n_r in (1, 32, 33, 64, 128, 300):
             assert mdl.plan_check(m, n_r) == 0, (dims, fwd, m, n_r)
     assert mdl.plan_check(0, 4) == 1 and mdl.plan_check(4, 0) == 1
+
+
+def test_library_sources_never_allocate_device_memory():
+    """Every entry point runs on memory the caller hands over (or, for zeno_score_static, on the
+    library's static device array): no source of the library calls a HIP allocation routine."""
+    csrc = os.path.join(ROOT, "paper_1805_10032_amd", "csrc")
+    pat = re.compile(r"\bhip(Malloc\w*|Free\w*|HostMalloc|HostAlloc|ExtMallocWithFlags|MemPool\w*)\s*\(")
+    for name in sorted(os.listdir(csrc)):
+        text = open(os.path.join(csrc, name)).read()
+        text = re.sub(r"//[^\n]*|/\*.*?\*/", "", text, flags=re.S)
+        assert not pat.search(text), name
