@@ -3,10 +3,14 @@
 
 One step = one whole aggregation: zeno_score over the m candidates followed by
 zeno_aggregate (selection + average), on seeded synthetic inputs that are
-already resident in HBM.  Prints ONE JSON line: aggregations/s, the roofline
-figures of the dominant kernel (the candidate layer kernel that streams G),
-measured with HIP events around every launch, and the CPU oracle timed on a
-bounded sample of the same workload as a baseline.
+already resident in HBM.  Prints ONE JSON line: aggregations/s on the headline
+workload (config 5, rows of G on 128-byte lines), the roofline figures of the
+dominant kernel (the candidate layer kernel that streams G), measured with HIP
+events around every launch, and the CPU oracle timed on a bounded sample of the
+same workload as a baseline.  The same line carries, under "also", the same
+measurement for the densely packed layout G[m x d] of the headline workload,
+for workload 4, and for workloads 3, 2 and 1 (buffers rotated so that G comes
+from HBM, eager launches and a replayed HIP graph).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
 """
@@ -30,16 +34,29 @@ def parse_args():
     ap.add_argument("--buffers", type=int, default=0,
                     help="distinct copies of G to rotate over (0 = automatic: enough to defeat the 256 MB cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline workload (no 'also' section)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise copy-like kernel (torch.ceil, 4 GiB in, 4 GiB out) so that rocprofv3 "
                          "byte counters collected over this command can be scaled")
     ap.add_argument("--row-align", type=int, default=32,
-                    help="alignment of the rows of G in floats (32 = 128-byte lines, the layout the library "
-                         "recommends; 1 = densely packed rows)")
+                    help="alignment of the rows of G in floats (32 = 128-byte lines, an odd number of them per row: "
+                         "the layout the library recommends; 1 = densely packed rows, ld = d)")
     ap.add_argument("--n-r", type=int, default=0,
                     help="override the size of the server's batch (0 = the workload's own; the paper's runs use 4)")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget of the CPU oracle sample")
     return ap.parse_args()
+
+
+def blas_threads():
+    """Threads of the BLAS library NumPy's matrix products run on (what the oracle really uses)."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p.get("num_threads", 0) for p in threadpool_info() if p.get("user_api") == "blas"]
+        if n:
+            return int(max(n))
+    except Exception:
+        pass
+    return int(os.environ.get("OMP_NUM_THREADS", 0)) or os.cpu_count()
 
 
 def cpu_baseline(w, budget_s):
@@ -47,7 +64,6 @@ def cpu_baseline(w, budget_s):
     m candidates, and the selection + average on the first d_s coordinates; the
     parts are scaled to the full step."""
     import numpy as np
-    import torch
     from oracle import zeno_oracle as O
 
     npy = lambda t: None if t is None else t.detach().cpu().numpy()
@@ -71,10 +87,11 @@ def cpu_baseline(w, budget_s):
     O.zeno_aggregate(Gs, s, w.b)
     t_agg = (time.perf_counter() - t0) * (w.d / d_s)
     total = t_f0 + t_cand * (w.m / k) + t_agg
-    return {"value": 1.0 / total, "unit": "aggregations/s", "cores": torch.get_num_threads(),
+    return {"value": 1.0 / total, "unit": "aggregations/s", "cores": blas_threads(), "host_cpus": os.cpu_count(),
             "kind": "oracle",
             "sample": f"f_r(x) + {k} of {w.m} candidates scored + selection/average on {d_s} of {w.d} "
-                      f"coordinates, scaled to the full step ({total:.2f} s)"}
+                      f"coordinates, scaled to the full step ({total:.2f} s); NumPy float64, matrix products on "
+                      f"{blas_threads()} BLAS threads, the rest single-threaded"}
 
 
 def read_traffic(cfg):
@@ -89,6 +106,142 @@ def read_traffic(cfg):
     except OSError:
         pass
     return None
+
+
+class Runner:
+    """One workload resident on the GPU: buffers, the step, timing and per-launch records."""
+
+    def __init__(self, B, WL, torch, cfg, row_align, n_r=None, buffers=0, w=None):
+        self.B, self.torch, self.cfg = B, torch, cfg
+        dev = torch.device("cuda", 0)
+        if w is None:
+            w = WL.make_config(cfg, device=dev, row_align=row_align, n_r=n_r)
+        elif row_align <= 1 and w.G.stride(0) != w.d:
+            w = _with_G(w, w.G.contiguous())           # same values, densely packed: G[m x d], ld = d
+        self.w = w
+        m, d, b = w.m, w.d, w.b
+        g_bytes = 4 * m * d
+        if buffers > 0:
+            n_buf = buffers
+        elif g_bytes >= (1 << 30):
+            n_buf = 1               # far larger than the 256 MB last-level cache
+        else:
+            n_buf = min(8, (1 << 30) // g_bytes + 1)
+        self.Gs = [w.G]
+        for _ in range(n_buf - 1):
+            g = WL._alloc_rows(m, d, row_align, dev) if row_align > 1 else torch.empty((m, d), device=dev)
+            g.copy_(w.G)
+            self.Gs.append(g)
+        self.n_buf = n_buf
+        self.mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
+        self.ws = B.alloc_workspace(self.mdl, m, w.n_r, dev)
+        self.scores = torch.empty(m, dtype=torch.float32, device=dev)
+        self.out = torch.empty(d, dtype=torch.float32, device=dev)
+        self.sel = torch.empty(m - b, dtype=torch.int32, device=dev)
+        self.step_bytes = 4.0 * d * (2 * m - b + 2)
+
+    def step(self, i):
+        w, B = self.w, self.B
+        G = self.Gs[i % self.n_buf]
+        B.zeno_score(self.mdl, w.x, G, w.features, w.gamma, w.rho, labels=w.labels, targets=w.targets,
+                     scores=self.scores, workspace=self.ws)
+        B.zeno_aggregate(G, self.scores, w.b, out=self.out, selected=self.sel)
+
+    def time_steps(self, steps, warmup):
+        torch = self.torch
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(i)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def time_graph(self, steps, warmup):
+        """The same steps as ONE replayed HIP graph per buffer (the calls allocate nothing and never
+        synchronise, so they can be captured after one eager warm-up call)."""
+        torch = self.torch
+        self.step(0)
+        torch.cuda.synchronize()
+        graphs = []
+        side = torch.cuda.Stream()
+        for k in range(self.n_buf):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g, stream=side):
+                    self.step(k)
+            graphs.append(g)
+        torch.cuda.synchronize()
+        for i in range(warmup):
+            graphs[i % self.n_buf].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            graphs[i % self.n_buf].replay()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def launches(self, n_prof):
+        """Per-launch durations (HIP events on the launch stream), outside the timed region."""
+        B, torch = self.B, self.torch
+        B.profile_enable(True)
+        for i in range(n_prof):
+            self.step(i)
+        torch.cuda.synchronize()
+        recs = B.profile_collect(detail=True)
+        B.profile_enable(False)
+        per, per_layer = {}, {}
+        for r in recs:
+            if r["kernel"].startswith("layer"):
+                key = f"{r['kernel']}[{r['layer']}]"
+                e = per_layer.setdefault(key, [0, 0.0, 0.0, r])
+                e[0] += 1
+                e[1] += r["ms"]
+                e[2] += r["bytes"]
+            e = per.setdefault(r["kernel"], [0, 0.0, 0.0])
+            e[0] += 1
+            e[1] += r["ms"]
+            e[2] += r["bytes"]
+        return per, per_layer
+
+    def summary(self, steps, warmup, graph=False):
+        """ms per step, roofline fraction of the step, and the per-launch table of one workload."""
+        elapsed = self.time_steps(steps, warmup)
+        ms = 1e3 * elapsed / steps
+        per, per_layer = self.launches(max(3, min(steps, 10)))
+        n_prof = max(3, min(steps, 10))
+        w = self.w
+        out = {"workload": describe(self.cfg, w), "G_row_pitch_floats": int(w.G.stride(0)) if w.m > 1 else w.d,
+               "G_buffers_rotated": self.n_buf, "steps": steps, "ms_per_step": ms, "aggregations_per_s": steps / elapsed,
+               "step_algorithmic_GBps": self.step_bytes / (ms * 1e-3) / 1e9,
+               "step_frac_of_hbm_peak": self.step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               "launches": {k: {"per_step": v[0] / n_prof, "avg_ms": v[1] / v[0],
+                                "algorithmic_GBps": (v[2] / v[0]) / (v[1] / v[0]) / 1e6} for k, v in per.items()},
+               "layers": layer_table(per_layer)}
+        if graph:
+            g_elapsed = self.time_graph(steps, warmup)
+            out["graph_replay_ms_per_step"] = 1e3 * g_elapsed / steps
+            out["graph_replay_aggregations_per_s"] = steps / g_elapsed
+        return out
+
+
+def _with_G(w, G):
+    import copy
+    w2 = copy.copy(w)
+    w2.G = G
+    return w2
+
+
+def describe(cfg, w):
+    return (f"config {cfg}: " + "->".join(str(v) for v in w.dims) +
+            f" {w.loss}, d={w.d}, m={w.m}, b={w.b}, n_r={w.n_r}, gamma={w.gamma}, rho={w.rho}")
+
+
+def layer_table(per_layer):
+    return {k: {"avg_ms": v[1] / v[0], "algorithmic_GBps": v[2] / v[1] / 1e6,
+                "shape": {key: v[3][key] for key in ("waves", "k_split", "streaming", "row_blocks", "merged", "second")}}
+            for k, v in per_layer.items()}
 
 
 def main():
@@ -107,30 +260,10 @@ def main():
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
 
-    w = WL.make_config(a.config, device=dev, row_align=a.row_align, n_r=a.n_r or None)
+    R = Runner(B, WL, torch, a.config, a.row_align, n_r=a.n_r or None, buffers=a.buffers)
+    w = R.w
     m, d, b = w.m, w.d, w.b
     g_bytes = 4 * m * d
-    if a.buffers > 0:
-        n_buf = a.buffers
-    elif g_bytes >= (1 << 30):
-        n_buf = 1               # far larger than the 256 MB last-level cache
-    else:
-        n_buf = min(8, (1 << 30) // g_bytes + 1)
-    Gs = [w.G]
-    for _ in range(n_buf - 1):
-        Gs.append(WL._alloc_rows(m, d, a.row_align, dev))
-        Gs[-1].copy_(w.G)
-    mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
-    ws = B.alloc_workspace(mdl, m, w.n_r, dev)
-    scores = torch.empty(m, dtype=torch.float32, device=dev)
-    out = torch.empty(d, dtype=torch.float32, device=dev)
-    sel = torch.empty(m - b, dtype=torch.int32, device=dev)
-
-    def step(i):
-        G = Gs[i % n_buf]
-        B.zeno_score(mdl, w.x, G, w.features, w.gamma, w.rho, labels=w.labels, targets=w.targets,
-                     scores=scores, workspace=ws)
-        B.zeno_aggregate(G, scores, b, out=out, selected=sel)
 
     if a.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.float32, device=dev).normal_()
@@ -140,47 +273,22 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(a.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(a.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    elapsed = R.time_steps(a.steps, a.warmup)
     ms_per_step = 1e3 * elapsed / a.steps
 
-    # per-launch durations (HIP events on the launch stream), in a separate loop so
-    # that the event records do not sit inside the timed region above
-    B.profile_enable(True)
     n_prof = max(3, min(a.steps, 10))
-    for i in range(n_prof):
-        step(i)
-    torch.cuda.synchronize()
-    recs = B.profile_collect()
-    B.profile_enable(False)
-    per, per_layer = {}, {}
-    for name, layer, ms, nbytes in recs:
-        if name.startswith("layer"):
-            e = per_layer.setdefault(f"{name}[{layer}]", [0, 0.0, 0.0])
-            e[0] += 1
-            e[1] += ms
-            e[2] += nbytes
-        e = per.setdefault(name, [0, 0.0, 0.0])
-        e[0] += 1
-        e[1] += ms
-        e[2] += nbytes
+    per, per_layer = R.launches(n_prof)
     # the baseline aggregators on the same G (Section 6.1.1, Definitions 4 and 5), and the variant of
     # the aggregation that also takes the server's SGD step (Algorithm 1), in place on a copy of x
     x_step = w.x.clone()
     for i in range(-1, 3):                             # the first pass is an unrecorded warm-up
         B.profile_enable(i >= 0)
-        B.zeno_mean(Gs[i % n_buf], out=out)
-        B.zeno_median(Gs[i % n_buf], out=out)
-        B.zeno_aggregate_update(Gs[i % n_buf], scores, b, w.gamma, x_step, x_next=x_step, want_out=False,
-                                selected=sel)
+        B.zeno_mean(R.Gs[i % R.n_buf], out=R.out)
+        B.zeno_median(R.Gs[i % R.n_buf], out=R.out)
+        B.zeno_aggregate_update(R.Gs[i % R.n_buf], R.scores, b, w.gamma, x_step, x_next=x_step, want_out=False,
+                                selected=R.sel)
         if 3 <= m <= 128 and m - b - 2 >= 1:
-            B.zeno_krum(Gs[i % n_buf], b, out=out)     # Krum_b (Definition 5), the paper's main baseline
+            B.zeno_krum(R.Gs[i % R.n_buf], b, out=R.out)     # Krum_b (Definition 5), the paper's main baseline
     torch.cuda.synchronize()
     for name, layer, ms, nbytes in B.profile_collect():
         e = per.setdefault(name, [0, 0.0, 0.0])
@@ -190,12 +298,10 @@ def main():
     B.profile_enable(False)
     kernels = {k: {"launches_per_step": v[0] / (3 if k in ("mean", "median", "average_update", "krum") else n_prof), "avg_ms": v[1] / v[0],
                    "algorithmic_GBps": (v[2] / v[0]) / (v[1] / v[0]) / 1e6} for k, v in per.items()}
-    layers = {k: {"avg_ms": v[1] / v[0], "algorithmic_GBps": v[2] / v[1] / 1e6} for k, v in per_layer.items()}
     dom = per["layer_cand"]
     dom_avg_ms = dom[1] / dom[0]
     dom_bytes = dom[2] / dom[0]
     achieved = dom_bytes / (dom_avg_ms * 1e-3) / 1e9
-    step_bytes = 4.0 * d * (2 * m - b + 2)
 
     result = {
         "metric": "Zeno aggregations/sec (m candidates scored+averaged) and achieved HBM GB/s",
@@ -210,20 +316,35 @@ def main():
         "vs_baseline": None,
         "dtype": w.fwd if w.fwd == "bf16" else "f32",
         "data": "synthetic",
-        "config": {"workload": f"config {a.config}: " + "->".join(str(v) for v in w.dims) +
-                               f" {w.loss}, d={d}, m={m}, b={b}, n_r={w.n_r}, gamma={w.gamma}, rho={w.rho}",
-                   "G_bytes": g_bytes, "G_row_pitch_floats": int(w.G.stride(0)), "G_buffers_rotated": n_buf},
-        "step_algorithmic_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
-        "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "config": {"workload": describe(a.config, w),
+                   "G_bytes": g_bytes, "G_row_pitch_floats": int(w.G.stride(0)), "G_buffers_rotated": R.n_buf},
+        "step_algorithmic_GBps": R.step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": R.step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "layer_kernel (candidate layers, streams G)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(a.config),
                      "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_ms": dom_avg_ms},
         "kernels": kernels,
-        "layers": layers,
+        "layers": layer_table(per_layer),
     }
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, a.cpu_seconds)
+
+    if not a.no_extras and a.config == 5 and not a.n_r:
+        # the other bandwidth-bound measurements, after the headline one (not part of `value`)
+        also = {}
+        extra_steps = max(5, a.steps // 2)
+        if a.row_align > 1:
+            Rd = Runner(B, WL, torch, 5, 1, w=w)                 # the same candidates as G[m x d], ld = d
+            also["config5_dense_rows"] = Rd.summary(extra_steps, 2)
+            del Rd
+        del R
+        torch.cuda.empty_cache()
+        also["config4"] = Runner(B, WL, torch, 4, a.row_align).summary(extra_steps, 2)
+        torch.cuda.empty_cache()
+        for cfg in (3, 2, 1):
+            also[f"config{cfg}"] = Runner(B, WL, torch, cfg, a.row_align).summary(200, 20, graph=True)
+        result["also"] = also
     print(json.dumps(result))
 
 

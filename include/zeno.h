@@ -29,9 +29,11 @@
  *   floats apart (ldg = d: densely packed).  Neither d nor ldg need be a
  *   multiple of 4, so rows may be only 4-byte aligned and every kernel accepts
  *   that.  The server decides where the workers' vectors land, and the layout
- *   the kernels are fastest on is G 128-byte aligned with ldg a multiple of 32
- *   floats: then every 128-byte memory line of a row belongs to one load
- *   instruction and the rows are streamed with loads that bypass cache retention.
+ *   the kernels are fastest on is G 128-byte aligned with ldg an ODD multiple of
+ *   32 floats: then every 128-byte memory line of a row belongs to one load
+ *   instruction, the rows are streamed with loads that bypass cache retention,
+ *   and the rows of different candidates start on different halves of a 256-byte
+ *   span (an even multiple measures about 2 % slower on multi-gigabyte G).
  * Errors.  Every call returns a zeno_status_t; nothing is thrown across the
  *   ABI.  Argument errors are detected on the host before anything is
  *   enqueued, so a failed call leaves the outputs untouched.

@@ -137,11 +137,23 @@ def _rows(G: torch.Tensor):
     return G.data_ptr(), ldg
 
 
-def alloc_candidates(m: int, d: int, device=None, align: int = 32) -> torch.Tensor:
-    """An [m x d] float32 view whose rows start `align`-float (128-byte) aligned: the
-    layout the streaming kernels are fastest on."""
+def candidate_pitch(d: int, align: int = 32) -> int:
+    """Row pitch in floats for an [m x d] candidate matrix: d rounded up to `align` floats, and, for
+    line-aligned layouts (align a multiple of 32 floats = 128 bytes), to an ODD number of 128-byte
+    lines.  With an even number of lines the rows of all candidates start at the same offset modulo
+    256 bytes, and the workgroups that stream the same columns of 16 candidates at the same time then
+    lean on the same memory channels (measured on the 14 GB workload: 2 % slower)."""
+    align = max(1, int(align))
     ldg = (int(d) + align - 1) // align * align
-    buf = torch.empty((int(m), ldg), dtype=torch.float32,
+    if align % 32 == 0 and (ldg // 32) % 2 == 0:
+        ldg += 32
+    return ldg
+
+
+def alloc_candidates(m: int, d: int, device=None, align: int = 32) -> torch.Tensor:
+    """An [m x d] float32 view whose rows start `align`-float (128-byte) aligned, an odd number of
+    128-byte lines apart: the layout the streaming kernels are fastest on."""
+    buf = torch.empty((int(m), candidate_pitch(d, align)), dtype=torch.float32,
                       device=device or torch.device("cuda", torch.cuda.current_device()))
     return buf[:, :int(d)]
 

@@ -179,8 +179,12 @@ def _draw_batch(dims, loss, n, gen, device, feat="normal"):
 
 
 def _alloc_rows(m, d, row_align, device):
-    """[m x d] float32 whose rows are row_align floats aligned (a view of a wider buffer)."""
+    """[m x d] float32 whose rows are row_align floats aligned (a view of a wider buffer).  Line-aligned
+    layouts (row_align a multiple of 32 floats) take an odd number of 128-byte lines per row, the pitch
+    the library's binding recommends (binding.candidate_pitch)."""
     ldg = (d + row_align - 1) // row_align * row_align
+    if row_align % 32 == 0 and (ldg // 32) % 2 == 0:
+        ldg += 32
     return torch.empty((m, ldg), dtype=torch.float32, device=device)[:, :d]
 
 

@@ -273,3 +273,64 @@ def test_score_error_codes(B):
     with pytest.raises(B.ZenoError) as e:
         B.zeno_score(mdl, x, G, F, 0.1, 1e-3, targets=t, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
     assert e.value.status == 3
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3])
+def test_step_can_be_captured_in_a_hip_graph(B, cfg):
+    """zeno_score + zeno_aggregate only enqueue kernels on the caller's stream: no allocation, no
+    host synchronisation, no memset.  After one eager warm-up call (which sets the kernels' LDS
+    attributes) the pair is captured into a HIP graph; every replay, with fresh candidates written
+    into the captured buffers and eager work of the same library in between, must reproduce the eager
+    result bit for bit."""
+    w = WL.make_config(cfg)
+    dev = torch.device("cuda", 0)
+    mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
+    x, F = w.x.to(dev), w.features.to(dev)
+    lab = None if w.labels is None else w.labels.to(dev)
+    tgt = None if w.targets is None else w.targets.to(dev)
+    G = B.alloc_candidates(w.m, w.d, dev)
+    G.copy_(w.G)
+    ws = B.alloc_workspace(mdl, w.m, w.n_r, dev)
+    scores = torch.empty(w.m, device=dev)
+    out = torch.empty(w.d, device=dev)
+    sel = torch.empty(w.m - w.b, dtype=torch.int32, device=dev)
+
+    def step(G_, scores_, out_, sel_, ws_):
+        B.zeno_score(mdl, x, G_, F, w.gamma, w.rho, labels=lab, targets=tgt, scores=scores_, workspace=ws_)
+        B.zeno_aggregate(G_, scores_, w.b, out=out_, selected=sel_)
+
+    step(G, scores, out, sel, ws)                      # eager warm-up
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(G, scores, out, sel, ws)
+    torch.cuda.synchronize()
+
+    # eager reference on buffers of its own
+    G2 = B.alloc_candidates(w.m, w.d, dev)
+    ws2 = B.alloc_workspace(mdl, w.m, w.n_r, dev)
+    s2, o2, sel2 = torch.empty_like(scores), torch.empty_like(out), torch.empty_like(sel)
+    gen = torch.Generator(device=dev).manual_seed(cfg)
+    for rep in range(4):
+        if rep:                                        # new candidates: a permutation of the rows plus a little noise
+            perm = torch.randperm(w.m, generator=gen, device=dev)
+            G.copy_(G[perm] * (1.0 + 0.01 * rep))
+        G2.copy_(G)
+        scores.fill_(float("nan"))
+        out.fill_(float("nan"))
+        sel.fill_(-1)
+        graph.replay()
+        step(G2, s2, o2, sel2, ws2)                    # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(scores, s2) and torch.equal(out, o2) and torch.equal(sel, sel2), (cfg, rep)
+    s_ref, scale = exact_terms(_with_rows(w, G.cpu()))
+    assert np.all(score_error(npy(scores), s_ref, scale) <= SCORE_TOL[w.fwd])
+
+
+def _with_rows(w, G):
+    import copy
+    w2 = copy.copy(w)
+    w2.G = G.contiguous()
+    return w2
