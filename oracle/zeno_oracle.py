@@ -218,21 +218,26 @@ def zeno_step(x, G, b, gamma, rho, dims, has_bias, loss, features, labels=None, 
 #     here stands for the fp32 accumulator); biases are added unrounded;
 #   * the pass at x computes z0_l = rb(h0_{l-1}) rb(W_l)^T + b_l, h0_l = relu(z0_l),
 #     h0_0 = the batch;
-#   * candidate u is propagated as the CHANGE of the pre-activations,
-#       dz_l = -gamma ( rb(h_{l-1}) rb(U_l)^T + rb(D_{l-1}) rb(W_l)^T + ub_l ),
-#       D_l = (relu(z0_l + dz_l) - relu(z0_l)) (-1/gamma),  D_0 = 0,  h_0 = the batch,
-#     and only D_l is carried from layer to layer: the candidate's activations are
-#     rebuilt as  h_l = fl32( rb(h0_l) - gamma rb(D_l) )  (one float32 rounding, a
-#     fused multiply-add) from the operands as they are stored.  In exact arithmetic
-#     h_l = relu(z0_l + dz_l) and z0_l + dz_l equals the pre-activation of the model
-#     at x - gamma u, so without rounding this is Definition 2 unchanged;
+#   * candidate u is propagated as the CHANGE of the pre-activations relative to the pass at x,
+#       dz_l = -gamma ( rb(h0_{l-1}) rb(U_l)^T + rb(D_{l-1}) rb(W'_l)^T + ub_l ),
+#       W'_l = fl32( rb(W_l) - gamma rb(U_l) )   (one float32 rounding, a fused multiply-add),
+#       D_l = (relu(z0_l + dz_l) - relu(z0_l)) (-1/gamma),  D_0 = 0,  h0_0 = the batch,
+#     and only D_l is carried from layer to layer.  In exact arithmetic the candidate's
+#     activations are h_l = h0_l - gamma D_l, so its own product h_{l-1} U_l^T + D_{l-1} W_l^T
+#     equals h0_{l-1} U_l^T + D_{l-1} (W_l - gamma U_l)^T: the first product runs on the
+#     activations of the pass at x, the second on the perturbed weights, and z0_l + dz_l equals
+#     the pre-activation of the model at x - gamma u.  Without rounding this is Definition 2
+#     unchanged;
 #   * loss difference per sample and the final combine as in the exact oracle.
 #
-# Pinned by: exact equality with the float64 oracle when every operand is
-# bf16-representable (tests/test_oracle_bf16.py), and a forward-error bound
-# against the float64 oracle on random inputs.  Beyond that the contract has no
-# external reference ("parity unpinned" applies to the choice of rounding
-# points, not to the arithmetic).
+# Pinned by (tests/test_oracle_bf16.py): exact equality with the float64 oracle when
+# every operand is bf16-representable; a forward-error bound against the float64
+# oracle on random inputs; and agreement, within one unit of the bf16 rounding of
+# the losses, with Definition 2 written as two plain forward passes per candidate
+# whose operands are rounded to bf16 (no change propagation), a form in which a
+# wrong sign, a dropped term or a missing product lands far outside that bound.
+# Beyond that the contract has no external reference ("parity unpinned" applies to
+# the choice of rounding points, not to the arithmetic).
 # ---------------------------------------------------------------------------
 def round_bf16(a):
     """Nearest bfloat16 (ties to even) of the fp32 rounding of a, as float64."""
@@ -272,18 +277,19 @@ def scores_bf16(x, G, gamma, rho, dims, has_bias, loss, features, labels=None, t
             forward_evaluations += 1
             u = np.asarray(G[i], dtype=np.float64)
             layers_u = unflatten(u, dims, has_bias)
-            h, dprime, dz = batch, None, None
+            dprime, dz = None, None
+            g32 = np.float64(np.float32(gamma))
             for l, ((U, ub), (W, _)) in enumerate(zip(layers_u, layers_x)):
-                acc = rb(h) @ rb(U).T + ub
+                acc = rb(h0[l]) @ rb(U).T + ub
                 if dprime is not None:
-                    acc = acc + rb(dprime) @ rb(W).T
-                dz = _f32(-np.float64(np.float32(gamma)) * _f32(acc))
+                    w_perturbed = _f32(rb(W) - g32 * rb(U))
+                    acc = acc + rb(dprime) @ rb(w_perturbed).T
+                dz = _f32(-g32 * _f32(acc))
                 if l + 1 < L:
                     zs = _f32(z0[l] + dz)
                     h_new = np.where(zs <= 0.0, 0.0, zs)
                     delta = np.where(z0[l] > 0.0, np.where(dz < -z0[l], -z0[l], dz), h_new)
                     dprime = _f32(delta * neg_inv_gamma)
-                    h = _f32(rb(h0[l + 1]) - np.float64(np.float32(gamma)) * rb(dprime))
             diff = sample_losses(z0[-1] + dz, loss, labels, targets) - base_losses
             out.append(-float(np.mean(diff)) - rho * float(np.dot(u, u)))
     return np.array(out, dtype=np.float64)

@@ -5,18 +5,19 @@
 // output features and streams the corresponding rows of that source's weight
 // block from HBM exactly once, K-chunk by K-chunk:
 //
-//   source m (pass at x):   Z0   = H0 W^T + b                 (pre-activations at x)
-//   source s < m:           dZ_s = -gamma ( H_s U_s^T + D_s W^T + ub_s )
+//   source m (pass at x):   Z0   = H0 W^T + b                           (pre-activations at x)
+//   source s < m:           dZ_s = -gamma ( H0 U_s^T + D_s (W - gamma U_s)^T + ub_s )
 //
-// where H_s are candidate s's input activations, U_s / ub_s its weight / bias
-// block, and D_s = (H_s - H0) * (-1/gamma) the scaled change of the input
-// activations (absent at the first layer, where H_s = H0 = the batch).  Only D_s
-// is stored per candidate: H_s = H0 - gamma D_s is rebuilt in LDS, once per chunk
-// and workgroup, from the shared H0 (which stays in the caches) and D_s.  dZ_s is
-// the change of the pre-activations caused by moving x to x - gamma u_s, so the
-// perturbed parameters are never formed and f_r(x) - f_r(x - gamma u) is later
-// obtained without subtracting two nearly equal losses.  ||u_s||^2 is
-// accumulated from the same registers that feed the matrix cores.
+// where H0 are the input activations of the pass at x (shared by all candidates), U_s / ub_s
+// candidate s's weight / bias block, and D_s = (H_s - H0) * (-1/gamma) the scaled change of the
+// candidate's input activations (absent at the first layer, where H_s = H0 = the batch).  Only
+// D_s is stored per candidate.  With H_s = H0 - gamma D_s the candidate's own product
+// H_s U_s^T + D_s W^T equals H0 U_s^T + D_s (W - gamma U_s)^T: the first product runs on the
+// shared activations, and the second on the perturbed weights, which a wave forms in registers
+// for the 32 x 64 tile it has just staged and never stores.  dZ_s is the change of the
+// pre-activations caused by moving x to x - gamma u_s, so f_r(x) - f_r(x - gamma u) is later
+// obtained without subtracting two nearly equal losses.  ||u_s||^2 is accumulated from the same
+// registers that feed the matrix cores.
 //
 // Matrix-core mapping (wave64): each wave owns 32 output features (the rows of its
 // 32x32 accumulator blocks, i.e. the weight tile is the FIRST operand) and all
@@ -30,7 +31,8 @@
 //    order ("tiled"), copied asynchronously global -> LDS (no registers) into a
 //    double buffer and shared by the waves of the workgroup: one barrier per chunk.
 //  * W operand of the second product: written in operand order by the pass at x,
-//    loaded straight into registers.
+//    loaded straight into registers, where gamma times the staged U operand (same
+//    layout) is subtracted from it.
 #ifndef ZENO_LAYER_IMPL_H_
 #define ZENO_LAYER_IMPL_H_
 
@@ -373,77 +375,23 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       }
     }
   };
-  // Rebuild the candidate's activations in LDS buffer `buf`: the H half holds H0 (copied
-  // from the pass at x), the D half the candidate's D; H0 - gamma D replaces H0 in place
-  // (fp32 fused multiply-add per element, then the operand rounding).  All threads of the
-  // workgroup share the work; the caller brackets this with barriers.
   const float neg_gamma = -a.gamma;
-  auto rebuild_H = [&](int buf) __attribute__((always_inline)) {
-    unsigned char* bh = lds + buf * AD_BYTES;
-    const unsigned char* bd = bh + A_BYTES;
-    constexpr int PIECES = A_BYTES / 16;
-    constexpr int PER = (PIECES + 64 * NW - 1) / (64 * NW);   // 16-byte pieces per thread
-    f32x4 hraw[PER], draw[PER];
+  // Operand of the second product: W - gamma U for one k-step, from the W operand (operand-order
+  // copy written by the pass at x) and the staged U operand, which share one register layout.
+  // One fused multiply-add per element in fp32, then the operand rounding.
+  auto perturbed_w = [&](const f32x4& wv, const f32x4& uv) __attribute__((always_inline)) {
+    f32x4 out;
+    if (BF16) {
+      const bf16x8 wb = __builtin_bit_cast(bf16x8, wv), ub = __builtin_bit_cast(bf16x8, uv);
+      bf16x8 r;
 #pragma unroll
-    for (int q = 0; q < PER; ++q) {
-      const int i = tid + q * 64 * NW;
-      if (PIECES % (64 * NW) == 0 || i < PIECES) {
-        hraw[q] = *reinterpret_cast<const f32x4*>(bh + i * 16);
-        draw[q] = *reinterpret_cast<const f32x4*>(bd + i * 16);
-      }
+      for (int e = 0; e < 8; ++e) r[e] = (__bf16)__builtin_fmaf(neg_gamma, (float)ub[e], (float)wb[e]);
+      out = __builtin_bit_cast(f32x4, r);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) out[e] = __builtin_fmaf(neg_gamma, uv[e], wv[e]);
     }
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-      const int i = tid + q * 64 * NW;
-      if (PIECES % (64 * NW) == 0 || i < PIECES) {
-        f32x4 out;
-        if (BF16) {
-          const bf16x8 hv = __builtin_bit_cast(bf16x8, hraw[q]), dv = __builtin_bit_cast(bf16x8, draw[q]);
-          bf16x8 r;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) r[e] = (__bf16)__builtin_fmaf(neg_gamma, (float)dv[e], (float)hv[e]);
-          out = __builtin_bit_cast(f32x4, r);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) out[e] = __builtin_fmaf(neg_gamma, draw[q][e], hraw[q][e]);
-        }
-        *reinterpret_cast<f32x4*>(bh + i * 16) = out;
-      }
-    }
-  };
-  // The same for the 1 KB pieces this wave copied itself.  When the H pieces and the D
-  // pieces of a chunk fall to the same waves (A_KB a multiple of NW: piece q and piece
-  // q + A_KB are both copied by wave q % NW), a wave can rebuild its pieces as soon as
-  // its own copies have landed, before the barrier that publishes the buffer, and the
-  // chunk needs one barrier instead of two.
-  constexpr bool OWN_PIECES = (A_KB % NW) == 0;
-  auto rebuild_own = [&](int buf) __attribute__((always_inline)) {
-    unsigned char* bh = lds + buf * AD_BYTES;
-    const unsigned char* bd = bh + A_BYTES;
-    constexpr int PER = A_KB / NW > 0 ? A_KB / NW : 1;
-    f32x4 hraw[PER], draw[PER];
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-      const int off = (wave + q * NW) * 1024 + lane * 16;
-      hraw[q] = *reinterpret_cast<const f32x4*>(bh + off);
-      draw[q] = *reinterpret_cast<const f32x4*>(bd + off);
-    }
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-      const int off = (wave + q * NW) * 1024 + lane * 16;
-      f32x4 out;
-      if (BF16) {
-        const bf16x8 hv = __builtin_bit_cast(bf16x8, hraw[q]), dv = __builtin_bit_cast(bf16x8, draw[q]);
-        bf16x8 r;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) r[e] = (__bf16)__builtin_fmaf(neg_gamma, (float)dv[e], (float)hv[e]);
-        out = __builtin_bit_cast(f32x4, r);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) out[e] = __builtin_fmaf(neg_gamma, draw[q][e], hraw[q][e]);
-      }
-      *reinterpret_cast<f32x4*>(bh + off) = out;
-    }
+    return out;
   };
   auto load_W = [&](f32x4 (&w)[WREGS], int c) __attribute__((always_inline)) {
 #pragma unroll
@@ -490,10 +438,6 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       } else {
         wait_vmcnt<0>();
       }
-      if (SECOND && OWN_PIECES) {
-        asm volatile("" ::: "memory");  // the compiler must not move these LDS reads above the wait
-        rebuild_own(buf);               // this wave's own pieces have landed
-      }
       if (KS == 1) {
         __syncthreads();  // copies of every wave have landed; everyone is done with buffer buf^1
       } else {
@@ -508,10 +452,6 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       __syncthreads();
     }
     if (STEADY || c + 2 < c_end) load_tile<MODE, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
-    if (SECOND && !(DBUF && OWN_PIECES)) {
-      rebuild_H(buf);   // behind the tile requests, so that it does not delay them
-      __syncthreads();
-    }
 
     // Matrix products of this chunk in groups of MB products that share one B
     // operand (k-step t, operand H or D).  The scheduler is fenced so that the LDS
@@ -540,7 +480,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     for (int g = 0; g < NG; ++g) {
       const int t = g / OPS, op = g % OPS;
       __builtin_amdgcn_sched_barrier(0);
-      const f32x4 bv = op ? w[t] : bq[t];
+      const f32x4 bv = op ? (SECOND ? perturbed_w(w[t], bq[t]) : w[t]) : bq[t];
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         if (op == 1 && !SECOND) break;  // the pass at x has no second product
