@@ -191,7 +191,8 @@ size_t zeno_krum_workspace_bytes(int32_t m);
 zeno_status_t zeno_krum(const float* G, int64_t ldg, int32_t m, int64_t d, int32_t b, float* out, int32_t* chosen,
                         float* krum_scores, void* workspace, size_t workspace_bytes, void* stream);
 
-const char* zeno_status_string(zeno_status_t status);
+/* Text of a status code; any other value gives "unknown status". */
+const char* zeno_status_string(int32_t status);
 
 /* Host-only self-check of the scratch layout of zeno_score (Definition 2's m+1 forward passes keep
  * their activations there): walks the launch sequence for (model, m, n_r) without touching a

@@ -548,7 +548,7 @@ zeno_status_t zeno_krum(const float* G, int64_t ldg, int32_t m, int64_t d, int32
   return ZENO_OK;
 }
 
-const char* zeno_status_string(zeno_status_t status) {
+const char* zeno_status_string(int32_t status) {
   switch (status) {
     case ZENO_OK: return "ok";
     case ZENO_ERR_INVALID_ARG: return "invalid argument";
