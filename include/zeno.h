@@ -178,9 +178,13 @@ zeno_status_t zeno_median(const float* G, int64_t ldg, int32_t m, int64_t d, flo
 /* Krum_b (Definition 5, the paper's main baseline): out = the row of G whose sum of squared
  * distances to its m-b-2 nearest other rows is smallest (ties: lower index).  The distances
  * come from the Gram matrix G G^T, taken in one pass over G on the bf16 matrix cores (every
- * float split into three bf16 pieces, six piece products: float32 accuracy) and
- * summed in float64; they are therefore exact to about 1e-5 of ||G_i||^2 + ||G_j||^2, and two
- * rows whose Krum scores differ by less than that may be chosen either way.  Requires
+ * float split into three bf16 pieces, six piece products: float32 accuracy) and summed in
+ * float64, as S_ii + S_jj - 2 S_ij; they are exact to about 1e-5 of ||G_i||^2 + ||G_j||^2.  When a
+ * distance that enters a score is below 1e-3 of that scale (rows much closer to each other than to
+ * the origin), a second pass over G repeats the computation on the rows minus the row the first
+ * pass chose, which makes the distances around that row exact to about 1e-5 of themselves; the
+ * decision is taken on the device and costs nothing when it is not needed.  Two rows whose Krum
+ * scores differ by less than these errors may be chosen either way.  Requires
  * m - b - 2 >= 1; UNSUPPORTED for m > 128.  A row that holds NaN or Inf is at infinite distance
  * from every row: it is nobody's near neighbour and its own score is +infinity.
  *   out         DEVICE [d]    copy of the chosen row

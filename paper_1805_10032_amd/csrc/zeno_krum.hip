@@ -9,6 +9,15 @@
 // columns in 192 cycles where the fp32 instruction (v_mfma_f32_32x32x2_f32) needs 512.
 // The squared distances follow as S_ii + S_jj - 2 S_ij.
 //
+// That difference cancels when two rows are much closer to each other than to the origin
+// (the honest workers' gradients late in training): its error is about 1e-7 of
+// ||G_i||^2 + ||G_j||^2.  When a distance that enters a score is below 1e-3 of that scale
+// (and the two rows are not bit-identical, whose distance is exactly 0), the whole
+// computation is repeated on the rows minus the row that the first pass chose: distances do
+// not change under a common shift, and the rows of the cluster around the chosen row then
+// have norms of the size of their distances.  The second pass is decided on the device (a
+// flag in the workspace) and its kernels return at once when it is not needed.
+//
 // krum_gram_kernel<RB>: the m <= 32 RB rows are cut into RB row blocks.  A wave owns a
 // contiguous range of 64-column chunks; per chunk it loads the RB tiles of 32 rows x 64
 // columns with coalesced 128-bit loads (rows at or beyond m read row m-1 and are
@@ -40,10 +49,15 @@ __device__ inline void split3(const f32x4& v0, const f32x4& v1, bf16x8& h, bf16x
   l = __builtin_convertvector(r2, bf16x8);
 }
 
-template <int RB>
+// CENTER: second pass; runs only if *run_flag != 0 and subtracts row *center from every row.
+template <int RB, bool CENTER>
 __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) void krum_gram_kernel(const float* __restrict__ G, long long ldg,
-                                                                    int m, long long d, float* __restrict__ partial) {
+                                                                    int m, long long d, float* __restrict__ partial,
+                                                                    const int32_t* __restrict__ center,
+                                                                    const int32_t* __restrict__ run_flag) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  if (CENTER && *run_flag == 0) return;   // uniform over the launch
+  const float* __restrict__ crow = CENTER ? G + (long long)(*center) * ldg : G;
   constexpr int PAIRS = RB * (RB + 1) / 2;
   constexpr int TILE_BYTES = 32 * 64 * 4;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -68,6 +82,11 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) voi
   auto load_chunk = [&](f32x4 (&u)[RB][8], long long c) __attribute__((always_inline)) {
     const long long k0 = c * 64;
     const bool k_full = k0 + 64 <= d;  // wave-uniform
+    f32x4 cv = {0.f, 0.f, 0.f, 0.f};
+    if (CENTER) {
+      if (k_full) cv = *reinterpret_cast<const f32x4_a4*>(crow + k0 + kq);
+      else cv = load4_masked(crow + k0, kq, (int)(d - k0), true);
+    }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -82,7 +101,7 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) voi
           v = load4_masked(p, kq, (int)(d - k0), true);
         }
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        u[rb][j] = row < m ? v : zero;
+        u[rb][j] = row < m ? (CENTER ? v - cv : v) : zero;
       }
     }
   };
@@ -173,9 +192,13 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) voi
 }
 
 // Sum of the per-workgroup partial Grams in float64, in workgroup order: one thread per entry.
+// pass 0 clears the flag that asks for the second pass; pass 1 runs only if it is set.
 __global__ __launch_bounds__(256) void krum_reduce_kernel(const float* __restrict__ partial, int n_partials,
-                                                          int entries, double* __restrict__ gram) {
+                                                          int entries, double* __restrict__ gram, int pass,
+                                                          int32_t* __restrict__ flag) {
   const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (pass == 1 && *flag == 0) return;
+  if (pass == 0 && e == 0) *flag = 0;   // (set, if at all, by the score kernel that follows)
   if (e >= entries) return;
   double t = 0.0;
   int w = 0;
@@ -194,9 +217,12 @@ __global__ __launch_bounds__(256) void krum_reduce_kernel(const float* __restric
 // blocks, ranked by counting (ties to the lower index), the m-b-2 smallest summed in
 // ascending order.
 __global__ __launch_bounds__(128) void krum_score_kernel(const double* __restrict__ gram, int rb, int m, int b,
-                                                         double* __restrict__ score64, float* __restrict__ scores_out) {
+                                                         double* __restrict__ score64, float* __restrict__ scores_out,
+                                                         int pass, int32_t* __restrict__ flag) {
   __shared__ double dist[128];
   __shared__ double sorted[128];
+  __shared__ int cancels[128];
+  if (pass == 1 && *flag == 0) return;
   const int i = blockIdx.x, j = threadIdx.x;
   auto S = [&](int r, int c) {   // Gram entry (r, c), stored for block pairs a <= b only
     if (r > c) { const int t = r; r = c; c = t; }
@@ -205,7 +231,11 @@ __global__ __launch_bounds__(128) void krum_score_kernel(const double* __restric
     return gram[p * 1024 + (r & 31) * 32 + (c & 31)];
   };
   if (j < m) {
-    double dd = S(i, i) + S(j, j) - 2.0 * S(i, j);
+    const double sii = S(i, i), sjj = S(j, j), sij = S(i, j);
+    double dd = sii + sjj - 2.0 * sij;
+    // the difference is rounding noise when it is far below the squares it is formed from, unless
+    // the rows are bit-identical (all three entries equal, the distance exactly 0)
+    cancels[j] = (j != i) && (dd < 1e-3 * (sii + sjj)) && !(sii == sjj && sii == sij);
     dd = dd < 0.0 ? 0.0 : dd;
     dd = (dd == dd) ? dd : __builtin_inf();      // a NaN/Inf row is infinitely far from every row: ranks stay a permutation
     dist[j] = (j == i) ? __builtin_inf() : dd;   // the row itself is never a neighbour
@@ -219,6 +249,8 @@ __global__ __launch_bounds__(128) void krum_score_kernel(const double* __restric
       rank += (dk < dj) || (dk == dj && k < j);
     }
     sorted[rank] = dj;
+    // a cancelling distance among the m-b-2 that enter the score: ask for the second pass
+    if (pass == 0 && rank < m - b - 2 && cancels[j]) *flag = 1;
   }
   __syncthreads();
   if (j == 0) {
@@ -230,7 +262,9 @@ __global__ __launch_bounds__(128) void krum_score_kernel(const double* __restric
 }
 
 // Winner: smallest score, ties to the lower index.
-__global__ void krum_argmin_kernel(const double* __restrict__ score64, int m, int32_t* __restrict__ chosen) {
+__global__ void krum_argmin_kernel(const double* __restrict__ score64, int m, int32_t* __restrict__ chosen, int pass,
+                                   const int32_t* __restrict__ flag) {
+  if (pass == 1 && *flag == 0) return;
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     int best = 0;
     for (int i = 1; i < m; ++i)
@@ -254,9 +288,9 @@ int gram_resident() {
       n_cu = 256;
     constexpr int lds = kGramWaves * RB * 32 * 64 * 4;
     if (lds > 48 * 1024)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB>),
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&krum_gram_kernel<RB>),
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&krum_gram_kernel<RB, false>),
                                                      64 * kGramWaves, lds) != hipSuccess || per_cu < 1)
       per_cu = 1;
     return n_cu * per_cu;
@@ -269,16 +303,27 @@ int gram_grid(int rb) {
   return rb == 1 ? gram_resident<1>() : rb == 2 ? gram_resident<2>() : rb == 3 ? gram_resident<3>() : gram_resident<4>();
 }
 
-template <int RB>
-hipError_t launch_gram(const float* G, long long ldg, int m, long long d, float* partial, int grid, hipStream_t stream) {
+template <int RB, bool CENTER>
+hipError_t launch_gram(const float* G, long long ldg, int m, long long d, float* partial, int grid, const int32_t* center,
+                       const int32_t* run_flag, hipStream_t stream) {
   constexpr int lds = kGramWaves * RB * 32 * 64 * 4;
   static const hipError_t attr_err =
-      lds > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB>),
+      lds > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB, CENTER>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds)
                       : hipSuccess;
   if (attr_err != hipSuccess) return attr_err;
-  hipLaunchKernelGGL(krum_gram_kernel<RB>, dim3(grid), dim3(64 * kGramWaves), lds, stream, G, ldg, m, d, partial);
+  hipLaunchKernelGGL((krum_gram_kernel<RB, CENTER>), dim3(grid), dim3(64 * kGramWaves), lds, stream, G, ldg, m, d, partial,
+                     center, run_flag);
   return hipGetLastError();
+}
+
+template <bool CENTER>
+hipError_t launch_gram_rb(int rb, const float* G, long long ldg, int m, long long d, float* partial, int grid,
+                          const int32_t* center, const int32_t* run_flag, hipStream_t stream) {
+  if (rb == 1) return launch_gram<1, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  if (rb == 2) return launch_gram<2, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  if (rb == 3) return launch_gram<3, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  return launch_gram<4, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
 }
 
 }  // namespace
@@ -287,7 +332,7 @@ size_t krum_workspace_bytes(int m) {
   const int rb = (m + 31) / 32;
   const size_t entries = (size_t)(rb * (rb + 1) / 2) * 1024;
   return align_up((size_t)gram_grid(rb) * entries * sizeof(float), 256) + align_up(entries * sizeof(double), 256) +
-         align_up(128 * sizeof(double), 256);
+         align_up(128 * sizeof(double), 256) + 256;   // partial Grams, summed Gram, scores, second-pass flag
 }
 
 hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b, float* out, int32_t* chosen,
@@ -295,25 +340,28 @@ hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b,
   const int rb = (m + 31) / 32;
   const int grid = gram_grid(rb);
   float* partial = reinterpret_cast<float*>(workspace);
-  hipError_t e;
-  if (rb == 1) e = launch_gram<1>(G, ldg, m, d, partial, grid, stream);
-  else if (rb == 2) e = launch_gram<2>(G, ldg, m, d, partial, grid, stream);
-  else if (rb == 3) e = launch_gram<3>(G, ldg, m, d, partial, grid, stream);
-  else e = launch_gram<4>(G, ldg, m, d, partial, grid, stream);
-  if (e != hipSuccess) return e;
   const int entries = (rb * (rb + 1) / 2) * 1024;
   double* gram = reinterpret_cast<double*>(reinterpret_cast<unsigned char*>(workspace) +
                                            align_up((size_t)grid * entries * sizeof(float), 256));
-  hipLaunchKernelGGL(krum_reduce_kernel, dim3((entries + 255) / 256), dim3(256), 0, stream, partial, grid, entries, gram);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
   double* score64 = gram + align_up((size_t)entries * sizeof(double), 256) / sizeof(double);
-  hipLaunchKernelGGL(krum_score_kernel, dim3(m), dim3(128), 0, stream, gram, rb, m, b, score64, scores_out);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(krum_argmin_kernel, dim3(1), dim3(64), 0, stream, score64, m, chosen);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  int32_t* flag = reinterpret_cast<int32_t*>(score64 + align_up(128 * sizeof(double), 256) / sizeof(double));
+  // pass 0 on the rows as they are; pass 1, only if pass 0 found a cancelling distance (decided on the
+  // device: its kernels return at once otherwise), on the rows minus the row pass 0 chose
+  for (int pass = 0; pass < 2; ++pass) {
+    hipError_t e = pass == 0 ? launch_gram_rb<false>(rb, G, ldg, m, d, partial, grid, nullptr, nullptr, stream)
+                             : launch_gram_rb<true>(rb, G, ldg, m, d, partial, grid, chosen, flag, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(krum_reduce_kernel, dim3((entries + 255) / 256), dim3(256), 0, stream, partial, grid, entries, gram,
+                       pass, flag);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(krum_score_kernel, dim3(m), dim3(128), 0, stream, gram, rb, m, b, score64, scores_out, pass, flag);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(krum_argmin_kernel, dim3(1), dim3(64), 0, stream, score64, m, chosen, pass, flag);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   long long want = (d + 255) / 256;
   const int cgrid = (int)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
   hipLaunchKernelGGL(krum_copy_kernel, dim3(cgrid), dim3(256), 0, stream, G, ldg, d, chosen, out);

@@ -140,3 +140,29 @@ def test_krum_non_finite_rows(B):
     assert np.all(np.abs(ks[ok] - ref[ok]) <= DIST_TOL * (m - b - 2) * 4.0 * sq.max())
     idx = int(chosen.item())
     assert idx not in (4, 9) and np.array_equal(npy(out), npy(G[idx]))
+
+
+@pytest.mark.parametrize("m,d,b,spread", [(24, 50003, 6, 1e-4), (70, 9000, 20, 1e-5), (100, 4099, 30, 1e-3)])
+def test_krum_tight_honest_cluster(B, m, d, b, spread):
+    """The late-training case of the Discussion section: honest gradients that agree to `spread` of
+    their norm, plus b rows far away.  Squared distances inside the cluster are `spread`^2 of the
+    squared norms, far below the 1e-7 that S_ii + S_jj - 2 S_ij can resolve, so the scores of the
+    honest rows must come from the second pass (rows minus the first pass's choice): they are held
+    to 1e-3 of THEMSELVES against the float64 oracle, and the chosen row must be a minimiser."""
+    g = torch.Generator().manual_seed(31 * m + b)
+    centre = torch.randn(1, d, generator=g)
+    G = centre + spread * torch.randn(m, d, generator=g)
+    bad = torch.randperm(m, generator=g)[:b]
+    G[bad] = -2.0 * centre + 0.5 * torch.randn(b, d, generator=g)
+    ref = O.krum_scores(npy(G), b)
+    out, chosen, ks = B.zeno_krum(rows_to_gpu(B, G, 32), b)
+    torch.cuda.synchronize()
+    ks = npy(ks).astype(np.float64)
+    honest = np.array([i for i in range(m) if i not in set(bad.tolist())])
+    sq_min = float((npy(G).astype(np.float64) ** 2).sum(1).min())
+    assert ref[honest].max() / (m - b - 2) < 1e-5 * sq_min      # every distance inside the cluster is a cancelling one
+    rel = np.abs(ks[honest] - ref[honest]) / ref[honest]
+    assert rel.max() <= 1e-3, rel.max()
+    idx = int(chosen.item())
+    assert idx in set(honest.tolist()) and ref[idx] <= ref.min() * (1.0 + 2e-3)
+    assert np.array_equal(npy(out), npy(G[idx]))
