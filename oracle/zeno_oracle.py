@@ -293,3 +293,117 @@ def scores_bf16(x, G, gamma, rho, dims, has_bias, loss, features, labels=None, t
             diff = sample_losses(z0[-1] + dz, loss, labels, targets) - base_losses
             out.append(-float(np.mean(diff)) - rho * float(np.dot(u, u)))
     return np.array(out, dtype=np.float64)
+
+
+# ---------------------------------------------------------------------------
+# Convolutional f_r (Section 6.1: "4 convolutional layers followed by 1 fully
+# connected layer" on 32 x 32 x 3 images; the paper gives no widths, strides or
+# pooling, so those are free choices of the model description, not of the paper).
+#
+# Model class: n_conv convolutions with 3 x 3 kernels, zero padding 1, stride 1 or 2,
+# ReLU after each; then one fully connected layer on the flattened last map, no
+# activation.  Images and maps are NHWC.  Parameter layout (interface convention): for
+# every convolution the kernel W[c_out][ky][kx][c_in] row-major, then its bias[c_out]
+# if the model has biases; then the fully connected W[fc_out][h * w * c] whose input is
+# the last map flattened in (y, x, c) order, then its bias.
+#
+# Pinned by (tests/test_oracle_conv.py): a hand-computed 3 x 3 example, a six-loop
+# brute force, torch.nn.functional.conv2d on the CPU, the reduction of a 1 x 1 image
+# to a linear layer on the centre tap, and the same score pins as the linear models
+# (zero candidate, rho shift, finite-difference limit against autograd).
+# ---------------------------------------------------------------------------
+def conv_out_size(n, stride):
+    """Output width of a 3-wide kernel with zero padding 1 over n positions."""
+    return (n - 1) // stride + 1
+
+
+def cnn_shapes(desc):
+    """[(h, w, c)] of the input and of every map, for desc = dict(in_h, in_w, in_c,
+    conv_c=[...], conv_stride=[...], fc_out, has_bias)."""
+    shapes = [(desc["in_h"], desc["in_w"], desc["in_c"])]
+    for c, s in zip(desc["conv_c"], desc["conv_stride"]):
+        h, w, _ = shapes[-1]
+        shapes.append((conv_out_size(h, s), conv_out_size(w, s), c))
+    return shapes
+
+
+def cnn_num_params(desc):
+    shapes = cnn_shapes(desc)
+    d = 0
+    for (h, w, c_in), (_, _, c_out) in zip(shapes[:-1], shapes[1:]):
+        d += c_out * 9 * c_in + (c_out if desc["has_bias"] else 0)
+    h, w, c = shapes[-1]
+    d += desc["fc_out"] * h * w * c + (desc["fc_out"] if desc["has_bias"] else 0)
+    return d
+
+
+def cnn_unflatten(p, desc):
+    """([(kernel[c_out,3,3,c_in], bias[c_out])], (W_fc, b_fc)) following the layout above."""
+    p = np.asarray(p, dtype=np.float64)
+    assert p.ndim == 1 and p.shape[0] == cnn_num_params(desc)
+    shapes = cnn_shapes(desc)
+    off, convs = 0, []
+    for (h, w, c_in), (_, _, c_out) in zip(shapes[:-1], shapes[1:]):
+        n = c_out * 9 * c_in
+        kern = p[off:off + n].reshape(c_out, 3, 3, c_in)
+        off += n
+        if desc["has_bias"]:
+            bias = p[off:off + c_out]
+            off += c_out
+        else:
+            bias = np.zeros(c_out)
+        convs.append((kern, bias))
+    h, w, c = shapes[-1]
+    n = desc["fc_out"] * h * w * c
+    W = p[off:off + n].reshape(desc["fc_out"], h * w * c)
+    off += n
+    b = p[off:off + desc["fc_out"]] if desc["has_bias"] else np.zeros(desc["fc_out"])
+    return convs, (W, b)
+
+
+def conv3x3(h, kern, bias, stride):
+    """z[n, y, x, co] = bias[co] + sum over ky, kx, ci of hpad[n, y*stride + ky, x*stride + kx, ci] * kern[co, ky, kx, ci],
+    hpad = h with one ring of zeros around every image."""
+    n, hh, ww, c_in = h.shape
+    ho, wo = conv_out_size(hh, stride), conv_out_size(ww, stride)
+    hpad = np.zeros((n, hh + 2, ww + 2, c_in))
+    hpad[:, 1:hh + 1, 1:ww + 1, :] = h
+    z = np.zeros((n, ho, wo, kern.shape[0]))
+    for ky in range(3):
+        for kx in range(3):
+            patch = hpad[:, ky:ky + stride * (ho - 1) + 1:stride, kx:kx + stride * (wo - 1) + 1:stride, :]
+            z += patch @ kern[:, ky, kx, :].T
+    return z + bias
+
+
+def cnn_forward(p, desc, images):
+    """Model output [n x fc_out] for images [n x in_h x in_w x in_c]."""
+    convs, (W, b) = cnn_unflatten(p, desc)
+    h = np.asarray(images, dtype=np.float64).reshape(-1, desc["in_h"], desc["in_w"], desc["in_c"])
+    for (kern, bias), s in zip(convs, desc["conv_stride"]):
+        h = np.maximum(conv3x3(h, kern, bias, s), 0.0)
+    return h.reshape(h.shape[0], -1) @ W.T + b
+
+
+def cnn_f_r(p, desc, loss, images, labels=None, targets=None):
+    """f_r(p) = (1/n_r) sum_k f(p; z_k) for the convolutional model (Definition 2)."""
+    global forward_evaluations
+    forward_evaluations += 1
+    with np.errstate(invalid="ignore", over="ignore"):
+        return float(np.mean(sample_losses(cnn_forward(p, desc, images), loss, labels, targets)))
+
+
+def cnn_scores(x, G, gamma, rho, desc, loss, images, labels=None, targets=None, rows=None):
+    """Definition 2 for the convolutional model: (scores, scale) with scale = |f_r(x) - f_r(x - gamma u)| + rho ||u||^2."""
+    x = np.asarray(x, dtype=np.float64)
+    f0 = cnn_f_r(x, desc, loss, images, labels, targets)
+    idx = range(G.shape[0]) if rows is None else rows
+    s, scale = [], []
+    for i in idx:
+        u = np.asarray(G[i], dtype=np.float64)
+        with np.errstate(invalid="ignore", over="ignore"):
+            fi = cnn_f_r(x - gamma * u, desc, loss, images, labels, targets)
+            pen = rho * float(np.dot(u, u))
+        s.append(f0 - fi - pen)
+        scale.append(abs(f0 - fi) + pen)
+    return np.array(s), np.array(scale)

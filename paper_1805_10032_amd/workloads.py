@@ -45,6 +45,7 @@ class Workload:
     labels: Optional[torch.Tensor]     # [n_r] int32 (softmax_ce)
     targets: Optional[torch.Tensor]    # [n_r] fp32 (squared)
     faulty: list = field(default_factory=list)   # indices of injected rows
+    desc: Optional[dict] = None        # convolutional models: in_h, in_w, in_c, conv_c, conv_stride, fc_out, has_bias
 
     @property
     def d(self) -> int:
@@ -114,6 +115,103 @@ def minibatch_gradient(x, dims, has_bias, loss, features, labels=None, targets=N
         val = 0.5 * torch.mean((h[:, 0] - targets) ** 2)
     val.backward()
     return p.grad.detach()
+
+
+def cnn_shapes(desc):
+    """[(h, w, c)] of the input and of every map of a convolutional model (3 x 3 kernels, zero padding 1)."""
+    shapes = [(desc["in_h"], desc["in_w"], desc["in_c"])]
+    for c, st in zip(desc["conv_c"], desc["conv_stride"]):
+        h, w, _ = shapes[-1]
+        shapes.append(((h - 1) // st + 1, (w - 1) // st + 1, c))
+    return shapes
+
+
+def cnn_num_params(desc) -> int:
+    shapes = cnn_shapes(desc)
+    d = sum(co * 9 * ci + (co if desc["has_bias"] else 0) for (_, _, ci), (_, _, co) in zip(shapes[:-1], shapes[1:]))
+    h, w, c = shapes[-1]
+    return d + desc["fc_out"] * h * w * c + (desc["fc_out"] if desc["has_bias"] else 0)
+
+
+def _cnn_views(p, desc):
+    """([(kernel [c_out,3,3,c_in], bias)], (W_fc, b_fc)) as views of the flat vector p (the interface's layout)."""
+    shapes = cnn_shapes(desc)
+    off, convs = 0, []
+    for (_, _, ci), (_, _, co) in zip(shapes[:-1], shapes[1:]):
+        kern = p[off:off + co * 9 * ci].view(co, 3, 3, ci)
+        off += co * 9 * ci
+        bias = None
+        if desc["has_bias"]:
+            bias = p[off:off + co]
+            off += co
+        convs.append((kern, bias))
+    h, w, c = shapes[-1]
+    W = p[off:off + desc["fc_out"] * h * w * c].view(desc["fc_out"], h * w * c)
+    off += desc["fc_out"] * h * w * c
+    b = p[off:off + desc["fc_out"]] if desc["has_bias"] else None
+    return convs, (W, b)
+
+
+def init_cnn_params(desc, gen, device):
+    """He-normal kernels and weights (std sqrt(2/fan_in)), zero biases."""
+    x = torch.zeros(cnn_num_params(desc), dtype=torch.float32, device=device)
+    convs, (W, _) = _cnn_views(x, desc)
+    for kern, _ in convs:
+        kern.copy_(_randn(kern.shape, gen, device, (2.0 / (9 * kern.shape[3])) ** 0.5))
+    W.copy_(_randn(W.shape, gen, device, (2.0 / W.shape[1]) ** 0.5))
+    return x
+
+
+def cnn_minibatch_gradient(x, desc, loss, images, labels=None, targets=None):
+    """Gradient at x of the mean loss of the convolutional model over the batch (torch's own convolution
+    and autograd: input generation only), flattened in x's layout.  images: [n x in_h*in_w*in_c], NHWC."""
+    p = x.detach().clone().requires_grad_(True)
+    convs, (W, b) = _cnn_views(p, desc)
+    h = images.view(-1, desc["in_h"], desc["in_w"], desc["in_c"]).permute(0, 3, 1, 2)
+    for (kern, bias), st in zip(convs, desc["conv_stride"]):
+        h = torch.relu(torch.nn.functional.conv2d(h, kern.permute(0, 3, 1, 2), bias, stride=st, padding=1))
+    z = torch.nn.functional.linear(h.permute(0, 2, 3, 1).reshape(h.shape[0], -1), W, b)
+    if loss == "softmax_ce":
+        val = torch.nn.functional.cross_entropy(z, labels.long())
+    else:
+        val = 0.5 * torch.mean((z[:, 0] - targets) ** 2)
+    val.backward()
+    return p.grad.detach()
+
+
+def make_cnn_workload(name, cfg, desc, m, b, n_r, gamma, rho, *, seed=0, device="cpu", loss="softmax_ce",
+                      n_flip=0, flip_scale=-4.0, n_noise=0, noise_std=1.0, worker_batch=None, row_align=1):
+    """m candidates for a convolutional model (Section 6.1's model class on synthetic images): honest rows are
+    exact minibatch gradients at x on each worker's own i.i.d. batch of N(0,1) images with uniform labels;
+    faults as in make_mlp_workload.  fp32 forward."""
+    device = torch.device(device)
+    d_in = desc["in_h"] * desc["in_w"] * desc["in_c"]
+    dims = [d_in, desc["fc_out"]]
+    x = init_cnn_params(desc, _gen(seed, cfg, 1, device), device)
+    features, labels, targets = _draw_batch(dims, loss, n_r, _gen(seed, cfg, 2, device), device)
+    d = x.numel()
+    q = n_flip + n_noise
+    assert q < m
+    perm = torch.randperm(m, generator=_gen(seed, cfg, 3, "cpu")).tolist()
+    flip_rows, noise_rows, faulty = sorted(perm[:n_flip]), sorted(perm[n_flip:q]), sorted(perm[:q])
+    G = _alloc_rows(m, d, row_align, device)
+    honest_sum = torch.zeros(d, dtype=torch.float64, device=device)
+    n_honest = 0
+    for i in range(m):
+        if i in faulty:
+            continue
+        fi, li, ti = _draw_batch(dims, loss, worker_batch or n_r, _gen(seed, cfg, 100 + i, device), device)
+        G[i] = cnn_minibatch_gradient(x, desc, loss, fi, li, ti)
+        honest_sum += G[i].double()
+        n_honest += 1
+    if n_flip:
+        flipped = (flip_scale * honest_sum / n_honest).float()
+        for i in flip_rows:
+            G[i] = flipped
+    for i in noise_rows:
+        G[i] = _randn((d,), _gen(seed, cfg, 100 + i, device), device, noise_std)
+    return Workload(name, dims, bool(desc["has_bias"]), loss, "fp32", m, b, n_r, gamma, rho,
+                    x, G, features, labels, targets, faulty, dict(desc))
 
 
 ATTACKS = ("none", "sign_flip", "bit_flip", "label_flip")
