@@ -100,6 +100,33 @@ typedef struct {
 zeno_status_t zeno_model_create(const zeno_model_desc_t* desc, zeno_model_t** out);
 void zeno_model_destroy(zeno_model_t* model);
 
+/* Convolutional model (Section 6.1 evaluates Zeno on a network of four convolutional layers and one
+ * fully connected layer; the paper gives no widths, so they are the caller's): n_conv convolutions
+ * with 3 x 3 kernels, zero padding 1 and stride 1 or 2, ReLU after each, then one fully connected
+ * layer on the flattened last map, no activation.  Images and maps are NHWC; a map shrinks to
+ * (h - 1) / stride + 1 rows (integer division), likewise columns.
+ * Parameter layout of x and of every row of G: for every convolution the kernel
+ * W[c_out][ky][kx][c_in] row-major followed, if has_bias, by bias[c_out]; then the fully connected
+ * W[fc_out][h * w * c], whose input is the last map flattened in (y, x, c) order, and its bias.
+ * The batch's features are the images, [n_r x in_h * in_w * in_c].
+ * Forward passes run in fp32 on the fp32 matrix cores; batches of more than 128 samples are
+ * UNSUPPORTED by zeno_score for these models.  HOST struct, copied by zeno_cnn_model_create. */
+#define ZENO_MAX_CONV 8
+typedef struct {
+  int32_t in_h, in_w, in_c;            /* each >= 1 */
+  int32_t n_conv;                      /* 1..ZENO_MAX_CONV */
+  int32_t conv_c[ZENO_MAX_CONV];       /* output channels of every convolution, >= 1 */
+  int32_t conv_stride[ZENO_MAX_CONV];  /* 1 or 2 */
+  int32_t fc_out;                      /* output width, >= 1 */
+  int32_t has_bias;                    /* 0 or 1 */
+  int32_t loss;                        /* zeno_loss_t; ZENO_LOSS_SQUARED requires fc_out == 1 */
+} zeno_cnn_desc_t;
+
+/* Handle for a convolutional model; used with zeno_score, zeno_score_static, zeno_model_num_params,
+ * zeno_score_workspace_bytes and zeno_model_destroy like the handle of zeno_model_create.
+ * Errors: INVALID_ARG for NULL pointers or fields out of range. */
+zeno_status_t zeno_cnn_model_create(const zeno_cnn_desc_t* desc, zeno_model_t** out);
+
 /* d, the length of a parameter vector in the layout above. */
 int64_t zeno_model_num_params(const zeno_model_t* model);
 
@@ -203,7 +230,7 @@ const char* zeno_status_string(int32_t status);
  * device and verifies, for every workgroup width a launch may take, that everything the launch
  * writes lies inside its slot of the workspace.  OK, INVALID_ARG for bad arguments, WORKSPACE if a
  * launch would leave its slot (a bug in the library: zeno_score makes the same check for the
- * widths it really uses and then enqueues nothing). */
+ * widths it really uses and then enqueues nothing).  UNSUPPORTED for convolutional models. */
 zeno_status_t zeno_score_plan_check(const zeno_model_t* model, int32_t m, int32_t n_r);
 
 /* Per-launch timing, a measurement aid (Section 5.3 prices the step by its
@@ -226,7 +253,10 @@ typedef enum {
   ZENO_KERNEL_MEAN = 6,
   ZENO_KERNEL_MEDIAN = 7,
   ZENO_KERNEL_AVERAGE_UPDATE = 8, /* selection + average + x_next = x - gamma * average */
-  ZENO_KERNEL_KRUM = 9            /* Gram matrix + selection + copy of the chosen row */
+  ZENO_KERNEL_KRUM = 9,           /* Gram matrix + selection + copy of the chosen row */
+  ZENO_KERNEL_CONV_BASE = 10,     /* one convolution of the pass at x */
+  ZENO_KERNEL_CONV_CAND = 11,     /* one convolution of the m candidate passes */
+  ZENO_KERNEL_AUX = 12            /* fills, squared norms of the convolution kernels */
 } zeno_kernel_t;
 
 typedef struct {

@@ -21,13 +21,14 @@ LOSS = {"squared": 0, "softmax_ce": 1}
 FWD = {"fp32": 0, "bf16": 1}
 STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported size", 3: "workspace", 4: "device"}
 
-EXPORTS = ["zeno_model_create", "zeno_model_destroy", "zeno_model_num_params",
+EXPORTS = ["zeno_model_create", "zeno_cnn_model_create", "zeno_model_destroy", "zeno_model_num_params",
            "zeno_score_workspace_bytes", "zeno_score", "zeno_score_static", "zeno_aggregate", "zeno_aggregate_update", "zeno_mean",
            "zeno_median", "zeno_krum_workspace_bytes", "zeno_krum", "zeno_status_string", "zeno_profile_enable", "zeno_profile_collect",
            "zeno_score_plan_check"]
 
 KERNEL_NAMES = ["pack", "layer_base", "layer_cand", "loss", "combine", "average", "mean", "median", "average_update",
-                "krum"]
+                "krum", "conv_base", "conv_cand", "aux"]
+ZENO_MAX_CONV = 8
 
 
 class ZenoError(RuntimeError):
@@ -42,6 +43,14 @@ class _ModelDesc(ctypes.Structure):
                 ("has_bias", ctypes.c_int32),
                 ("loss", ctypes.c_int32),
                 ("fwd", ctypes.c_int32)]
+
+
+class _CnnDesc(ctypes.Structure):
+    _fields_ = [("in_h", ctypes.c_int32), ("in_w", ctypes.c_int32), ("in_c", ctypes.c_int32),
+                ("n_conv", ctypes.c_int32),
+                ("conv_c", ctypes.c_int32 * ZENO_MAX_CONV),
+                ("conv_stride", ctypes.c_int32 * ZENO_MAX_CONV),
+                ("fc_out", ctypes.c_int32), ("has_bias", ctypes.c_int32), ("loss", ctypes.c_int32)]
 
 
 class _ProfileRecord(ctypes.Structure):
@@ -74,6 +83,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
     lib.zeno_model_create.argtypes = [ctypes.POINTER(_ModelDesc), ctypes.POINTER(vp)]
     lib.zeno_model_create.restype = ctypes.c_int
+    lib.zeno_cnn_model_create.argtypes = [ctypes.POINTER(_CnnDesc), ctypes.POINTER(vp)]
+    lib.zeno_cnn_model_create.restype = ctypes.c_int
     lib.zeno_model_destroy.argtypes = [vp]
     lib.zeno_model_destroy.restype = None
     lib.zeno_model_num_params.argtypes = [vp]
@@ -201,6 +212,34 @@ class ZenoModel:
             self.close()
         except Exception:
             pass
+
+
+class ZenoCnnModel(ZenoModel):
+    """Handle of a convolutional model (zeno_cnn_model_create): desc = dict(in_h, in_w, in_c, conv_c=[...],
+    conv_stride=[...], fc_out, has_bias); fp32 forward."""
+
+    def __init__(self, desc, loss="softmax_ce"):
+        lib = load_library()
+        cd = _CnnDesc()
+        cd.in_h, cd.in_w, cd.in_c = int(desc["in_h"]), int(desc["in_w"]), int(desc["in_c"])
+        conv_c, conv_stride = list(desc["conv_c"]), list(desc["conv_stride"])
+        if not (1 <= len(conv_c) <= ZENO_MAX_CONV) or len(conv_c) != len(conv_stride):
+            raise ZenoError(1, "ZenoCnnModel")
+        cd.n_conv = len(conv_c)
+        for i, (c, s) in enumerate(zip(conv_c, conv_stride)):
+            cd.conv_c[i], cd.conv_stride[i] = int(c), int(s)
+        cd.fc_out = int(desc["fc_out"])
+        cd.has_bias = int(bool(desc["has_bias"]))
+        cd.loss = LOSS[loss]
+        handle = ctypes.c_void_p()
+        st = lib.zeno_cnn_model_create(ctypes.byref(cd), ctypes.byref(handle))
+        if st != 0:
+            raise ZenoError(st, "zeno_cnn_model_create")
+        self._lib = lib
+        self._h = handle
+        self.desc = dict(desc)
+        self.dims = [cd.in_h * cd.in_w * cd.in_c, cd.fc_out]      # input width of a sample, output width
+        self.has_bias, self.loss, self.fwd = bool(desc["has_bias"]), loss, "fp32"
 
 
 def alloc_workspace(model: ZenoModel, m: int, n_r: int, device=None) -> torch.Tensor:

@@ -19,7 +19,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["zeno_capi.hip", "zeno_layer.hip", "zeno_layer_bf16_delta.hip", "zeno_layer_bf16_first.hip",
            "zeno_layer_f32_delta.hip", "zeno_layer_f32_first.hip", "zeno_loss.hip", "zeno_aggregate.hip",
-           "zeno_median.hip", "zeno_krum.hip"]
+           "zeno_median.hip", "zeno_krum.hip", "zeno_conv.hip"]
 
 # Packed-fp32 instruction selection is switched off for all device code.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -45,7 +45,7 @@ def _fresh(obj, src, stamp):
             return False
         t = os.path.getmtime(obj)
         deps = [os.path.join(CSRC, src), os.path.join(CSRC, "zeno_internal.h"), os.path.join(ROOT, "include", "zeno.h")]
-        if src.startswith("zeno_layer") or src == "zeno_krum.hip":
+        if src.startswith("zeno_layer") or src in ("zeno_krum.hip", "zeno_conv.hip"):
             deps.append(os.path.join(CSRC, "zeno_layer_impl.h"))
         return all(os.path.getmtime(d) < t for d in deps)
     except OSError:

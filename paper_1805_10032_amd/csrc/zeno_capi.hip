@@ -10,13 +10,6 @@
 
 #include "zeno_internal.h"
 
-struct zeno_model {
-  zeno_model_desc_t desc;
-  int64_t w_off[ZENO_MAX_LAYERS];  // offset of W_l (l = 0..L-1) inside a parameter vector
-  int64_t b_off[ZENO_MAX_LAYERS];  // offset of b_l, or -1
-  int64_t d;
-};
-
 // Scratch of zeno_score_static: a file-scope device array, one copy per GPU at that GPU's own
 // address, held until the process ends.  In host code this name is only a handle for
 // hipGetSymbolAddress, never an address to pass to a kernel.
@@ -354,6 +347,188 @@ zeno_status_t score_enqueue(const zeno_model* model, const Plan& p, const float*
   return ZENO_OK;
 }
 
+
+// ---- convolutional models: workspace layout and launch sequence
+constexpr int kConvNormBlocks = 8;   // pieces the squared norm of a candidate's convolution kernels is summed in
+
+struct CnnPlan {
+  int n_conv, MB, n_pad, Kfc, Kp, P;
+  size_t off_z0[ZENO_MAX_CONV], off_h0[ZENO_MAX_CONV], off_d[2], d_stride;  // maps (floats per candidate in d_stride)
+  size_t off_h0t, off_dt, dt_stride, sz_h0t;                                  // operands of the fully connected layer
+  size_t off_wt, off_z0fc, off_dz, off_norm, off_diff, total;
+};
+
+CnnPlan make_cnn_plan(const zeno_model* mdl, int m, int n_r) {
+  CnnPlan p;
+  std::memset(&p, 0, sizeof(p));
+  const int C = mdl->cnn.n_conv;
+  p.n_conv = C;
+  p.MB = blocks_for(n_r);
+  p.n_pad = 32 * p.MB;
+  p.Kfc = mdl->map_h[C] * mdl->map_w[C] * mdl->map_c[C];
+  p.Kp = pad64(p.Kfc);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  };
+  size_t max_map = 0;
+  for (int l = 0; l < C; ++l) {
+    const size_t map = (size_t)n_r * mdl->map_h[l + 1] * mdl->map_w[l + 1] * mdl->map_c[l + 1];
+    p.off_z0[l] = take(map * sizeof(float));
+    if (l + 1 < C) {
+      p.off_h0[l] = take(map * sizeof(float));
+      if (map > max_map) max_map = map;
+    }
+  }
+  p.d_stride = align_up(max_map * sizeof(float), 256) / sizeof(float);
+  if (C > 1)
+    for (int i = 0; i < 2; ++i) p.off_d[i] = take(p.d_stride * sizeof(float) * m);
+  p.sz_h0t = (size_t)p.n_pad * p.Kp * sizeof(float);
+  p.off_h0t = take(p.sz_h0t);
+  p.dt_stride = align_up(p.sz_h0t, 256);
+  p.off_dt = take(p.dt_stride * m);
+  const int N = mdl->cnn.fc_out;
+  p.off_wt = take((size_t)wt_rows_alloc(N, true) * p.Kp * sizeof(float));
+  p.off_z0fc = take((size_t)n_r * N * sizeof(float));
+  p.off_dz = take((size_t)m * n_r * N * sizeof(float));
+  p.P = (pad64(N) + 31) / 32 + kConvNormBlocks;
+  p.off_norm = take((size_t)m * p.P * sizeof(double));
+  p.off_diff = take((size_t)m * n_r * sizeof(double));
+  p.total = off;
+  return p;
+}
+
+zeno_status_t cnn_score_enqueue(const zeno_model* mdl, const CnnPlan& p, const float* x, const float* G, int64_t ldg,
+                                int m, const zeno_batch_t* batch, float gamma, float rho, float* scores,
+                                unsigned char* ws, hipStream_t stream) {
+  const int C = p.n_conv, n_r = batch->n_r, N = mdl->cnn.fc_out;
+  const float neg_inv_gamma = gamma > 0.f ? -1.0f / gamma : 0.f;
+  double* norm_partials = reinterpret_cast<double*>(ws + p.off_norm);
+  double* sample_diff = reinterpret_cast<double*>(ws + p.off_diff);
+  float* dZ = reinterpret_cast<float*>(ws + p.off_dz);
+
+  // the padding of the fully connected layer's operands (samples beyond n_r, columns beyond K) must hold
+  // zeros, not whatever the workspace held: the convolutions only write the live entries
+  {
+    ProfScope ps(ZENO_KERNEL_AUX, 0, 0.0, stream);
+    ZENO_TRY(launch_fill_zero(ws + p.off_h0t, p.sz_h0t, stream));
+    ZENO_TRY(launch_fill_zero(ws + p.off_dt, p.dt_stride * m, stream));
+  }
+  auto conv_args = [&](int l) {
+    ConvArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.G = G;
+    a.x = x;
+    a.ldg = ldg;
+    a.n_r = n_r;
+    a.L.w_off = mdl->conv_w_off[l];
+    a.L.b_off = mdl->conv_b_off[l];
+    a.L.Hin = mdl->map_h[l];
+    a.L.Win = mdl->map_w[l];
+    a.L.Cin = mdl->map_c[l];
+    a.L.Hout = mdl->map_h[l + 1];
+    a.L.Wout = mdl->map_w[l + 1];
+    a.L.Cout = mdl->map_c[l + 1];
+    a.L.stride = mdl->cnn.conv_stride[l];
+    a.H0_in = l == 0 ? batch->features : reinterpret_cast<const float*>(ws + p.off_h0[l - 1]);
+    a.Z0 = reinterpret_cast<float*>(ws + p.off_z0[l]);
+    a.tiled_out = l + 1 == C;
+    a.Kp_fc = p.Kp;
+    a.gamma = gamma;
+    a.neg_inv_gamma = neg_inv_gamma;
+    return a;
+  };
+  auto conv_flops = [&](int l) {   // reported in place of bytes: 2 * positions * 9 c_in * c_out per source
+    return 2.0 * n_r * mdl->map_h[l + 1] * mdl->map_w[l + 1] * 9.0 * mdl->map_c[l] * mdl->map_c[l + 1];
+  };
+  // pass at x through the convolutions, then the candidates (layer l of the candidates needs Z0 of layer l
+  // and the input map of layer l, both written by the pass at x)
+  for (int l = 0; l < C; ++l) {
+    ConvArgs a = conv_args(l);
+    a.out = l + 1 == C ? reinterpret_cast<float*>(ws + p.off_h0t) : reinterpret_cast<float*>(ws + p.off_h0[l]);
+    ProfScope ps(ZENO_KERNEL_CONV_BASE, l, conv_flops(l), stream);
+    ZENO_TRY(launch_conv(a, stream));
+  }
+  for (int l = 0; l < C; ++l) {
+    ConvArgs a = conv_args(l);
+    a.n_cand = m;
+    if (l > 0) {
+      a.D_in = reinterpret_cast<const float*>(ws + p.off_d[(l - 1) & 1]);
+      a.D_in_stride = (long long)p.d_stride;
+    }
+    if (l + 1 == C) {
+      a.out = reinterpret_cast<float*>(ws + p.off_dt);
+      a.out_stride = (long long)(p.dt_stride / sizeof(float));
+    } else {
+      a.out = reinterpret_cast<float*>(ws + p.off_d[l & 1]);
+      a.out_stride = (long long)p.d_stride;
+    }
+    ProfScope ps(ZENO_KERNEL_CONV_CAND, l, conv_flops(l) * m * (l > 0 ? 2 : 1), stream);
+    ZENO_TRY(launch_conv(a, stream));
+  }
+  // the fully connected layer on the streaming layer kernel (fp32, with the second product)
+  LayerJob j;
+  std::memset(&j, 0, sizeof(j));
+  j.w_off = mdl->w_off[0];
+  j.b_off = mdl->b_off[0];
+  j.N = N;
+  j.K = p.Kfc;
+  j.Kp = p.Kp;
+  j.Np = pad64(N);
+  j.last = 1;
+  j.A_base = ws + p.off_h0t;
+  j.Wt = ws + p.off_wt;
+  j.Z0 = reinterpret_cast<float*>(ws + p.off_z0fc);
+  LayerArgs common;
+  std::memset(&common, 0, sizeof(common));
+  common.G = G;
+  common.x = x;
+  common.ldg = ldg;
+  common.dZ = dZ;
+  common.gamma = gamma;
+  common.neg_inv_gamma = neg_inv_gamma;
+  common.n_r = n_r;
+  const double fc_bytes = 4.0 * ((double)N * p.Kfc + (j.b_off >= 0 ? N : 0));
+  {
+    LayerArgs b = common;
+    b.has_base = 1;
+    b.bj = j;
+    ProfScope ps(ZENO_KERNEL_LAYER_BASE, C, fc_bytes, stream);
+    ZENO_TRY(launch_layer(b, false, false, p.MB, stream));
+  }
+  LayerArgs c = common;
+  c.n_cand = m;
+  c.cj = j;
+  c.D_cand = ws + p.off_dt;
+  c.A_stride = (long long)p.dt_stride;
+  c.norm_partials = norm_partials;
+  c.P = p.P;
+  c.p_off = 0;
+  const int fc_tiles = layer_tiles(c, false, true, p.MB);
+  if (fc_tiles + kConvNormBlocks > p.P) return ZENO_ERR_WORKSPACE;
+  {
+    ProfScope ps(ZENO_KERNEL_LAYER_CAND, C, fc_bytes * m, stream);
+    ZENO_TRY(launch_layer(c, false, true, p.MB, stream));
+  }
+  // ||u||^2 runs over all d coordinates: the fully connected block was summed by the layer kernel, the
+  // convolutions' kernels and biases (the first mdl->w_off[0] coordinates) are summed here; slots that no
+  // launch writes are cleared
+  {
+    ProfScope ps(ZENO_KERNEL_AUX, 1, 4.0 * (double)mdl->w_off[0] * m, stream);
+    ZENO_TRY(launch_sumsq(G, ldg, m, 0, mdl->w_off[0], kConvNormBlocks, norm_partials, p.P, fc_tiles, stream));
+  }
+  const int P_used = fc_tiles + kConvNormBlocks;
+  {
+    ProfScope ps(ZENO_KERNEL_LOSS, 0, 4.0 * (m + 1) * n_r * N, stream);
+    ZENO_TRY(launch_loss(j.Z0, dZ, batch->labels, batch->targets, mdl->cnn.loss, m, n_r, 0, n_r, N, sample_diff, stream));
+  }
+  ProfScope ps(ZENO_KERNEL_COMBINE, 0, 8.0 * m * (n_r + P_used), stream);
+  ZENO_TRY(launch_score_combine_strided(sample_diff, norm_partials, p.P, P_used, m, n_r, rho, scores, stream));
+  return ZENO_OK;
+}
+
 // Device address of `scratch` on the current device, looked up once per device.
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
@@ -413,6 +588,8 @@ zeno_status_t zeno_model_create(const zeno_model_desc_t* desc, zeno_model_t** ou
   if (desc->loss == ZENO_LOSS_SQUARED && desc->dims[desc->n_layers] != 1) return ZENO_ERR_INVALID_ARG;
   zeno_model* mdl = new (std::nothrow) zeno_model;
   if (mdl == nullptr) return ZENO_ERR_DEVICE;
+  std::memset(mdl, 0, sizeof(*mdl));
+  mdl->kind = 0;
   mdl->desc = *desc;
   int64_t off = 0;
   for (int l = 0; l < desc->n_layers; ++l) {
@@ -429,12 +606,68 @@ zeno_status_t zeno_model_create(const zeno_model_desc_t* desc, zeno_model_t** ou
   return ZENO_OK;
 }
 
+zeno_status_t zeno_cnn_model_create(const zeno_cnn_desc_t* desc, zeno_model_t** out) {
+  if (desc == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
+  if (desc->n_conv < 1 || desc->n_conv > ZENO_MAX_CONV) return ZENO_ERR_INVALID_ARG;
+  if (desc->in_h < 1 || desc->in_w < 1 || desc->in_c < 1 || desc->fc_out < 1) return ZENO_ERR_INVALID_ARG;
+  if (desc->has_bias != 0 && desc->has_bias != 1) return ZENO_ERR_INVALID_ARG;
+  if (desc->loss != ZENO_LOSS_SQUARED && desc->loss != ZENO_LOSS_SOFTMAX_CE) return ZENO_ERR_INVALID_ARG;
+  if (desc->loss == ZENO_LOSS_SQUARED && desc->fc_out != 1) return ZENO_ERR_INVALID_ARG;
+  for (int l = 0; l < desc->n_conv; ++l)
+    if (desc->conv_c[l] < 1 || (desc->conv_stride[l] != 1 && desc->conv_stride[l] != 2)) return ZENO_ERR_INVALID_ARG;
+  zeno_model* mdl = new (std::nothrow) zeno_model;
+  if (mdl == nullptr) return ZENO_ERR_DEVICE;
+  std::memset(mdl, 0, sizeof(*mdl));
+  mdl->kind = 1;
+  mdl->cnn = *desc;
+  mdl->map_h[0] = desc->in_h;
+  mdl->map_w[0] = desc->in_w;
+  mdl->map_c[0] = desc->in_c;
+  int64_t off = 0;
+  for (int l = 0; l < desc->n_conv; ++l) {
+    mdl->map_h[l + 1] = (mdl->map_h[l] - 1) / desc->conv_stride[l] + 1;
+    mdl->map_w[l + 1] = (mdl->map_w[l] - 1) / desc->conv_stride[l] + 1;
+    mdl->map_c[l + 1] = desc->conv_c[l];
+    mdl->conv_w_off[l] = off;
+    off += (int64_t)desc->conv_c[l] * 9 * mdl->map_c[l];
+    mdl->conv_b_off[l] = -1;
+    if (desc->has_bias) {
+      mdl->conv_b_off[l] = off;
+      off += desc->conv_c[l];
+    }
+  }
+  const int C = desc->n_conv;
+  const int64_t kfc = (int64_t)mdl->map_h[C] * mdl->map_w[C] * mdl->map_c[C];
+  if (kfc > (int64_t)1 << 30) {
+    delete mdl;
+    return ZENO_ERR_INVALID_ARG;
+  }
+  // the fully connected layer, described as a one-layer chain for the code that sizes things by `desc`
+  mdl->desc.n_layers = 1;
+  mdl->desc.dims[0] = (int32_t)kfc;
+  mdl->desc.dims[1] = desc->fc_out;
+  mdl->desc.has_bias = desc->has_bias;
+  mdl->desc.loss = desc->loss;
+  mdl->desc.fwd = ZENO_FWD_FP32;
+  mdl->w_off[0] = off;
+  off += kfc * desc->fc_out;
+  mdl->b_off[0] = -1;
+  if (desc->has_bias) {
+    mdl->b_off[0] = off;
+    off += desc->fc_out;
+  }
+  mdl->d = off;
+  *out = mdl;
+  return ZENO_OK;
+}
+
 void zeno_model_destroy(zeno_model_t* model) { delete model; }
 
 int64_t zeno_model_num_params(const zeno_model_t* model) { return model == nullptr ? 0 : model->d; }
 
 size_t zeno_score_workspace_bytes(const zeno_model_t* model, int32_t m, int32_t n_r) {
   if (model == nullptr || m < 1 || m > ZENO_MAX_CANDIDATES || n_r < 1) return 0;
+  if (model->kind == 1) return n_r > kMaxPassRows ? 0 : make_cnn_plan(model, m, n_r).total;
   return make_plan(model, m, n_r).total;
 }
 
@@ -443,6 +676,13 @@ zeno_status_t zeno_score(const zeno_model_t* model, const float* x, const float*
                          size_t workspace_bytes, void* stream_) {
   zeno_status_t st = check_score_args(model, x, G, ldg, m, batch, gamma, rho, scores);
   if (st != ZENO_OK) return st;
+  if (model->kind == 1) {
+    if (batch->n_r > kMaxPassRows) return ZENO_ERR_UNSUPPORTED;
+    const CnnPlan cp = make_cnn_plan(model, m, batch->n_r);
+    if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < cp.total) return ZENO_ERR_WORKSPACE;
+    return cnn_score_enqueue(model, cp, x, G, ldg, m, batch, gamma, rho, scores, reinterpret_cast<unsigned char*>(workspace),
+                             reinterpret_cast<hipStream_t>(stream_));
+  }
   const Plan p = make_plan(model, m, batch->n_r);
   if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < p.total) return ZENO_ERR_WORKSPACE;
   return score_enqueue(model, p, x, G, ldg, m, batch, gamma, rho, scores, reinterpret_cast<unsigned char*>(workspace),
@@ -453,6 +693,14 @@ zeno_status_t zeno_score_static(const zeno_model_t* model, const float* x, const
                                 const zeno_batch_t* batch, float gamma, float rho, float* scores, void* stream_) {
   zeno_status_t st = check_score_args(model, x, G, ldg, m, batch, gamma, rho, scores);
   if (st != ZENO_OK) return st;
+  if (model->kind == 1) {
+    if (batch->n_r > kMaxPassRows) return ZENO_ERR_UNSUPPORTED;
+    const CnnPlan cp = make_cnn_plan(model, m, batch->n_r);
+    if (cp.total > (size_t)ZENO_STATIC_SCRATCH_BYTES) return ZENO_ERR_UNSUPPORTED;
+    unsigned char* cws = nullptr;
+    if (static_scratch(&cws) != hipSuccess) return ZENO_ERR_DEVICE;
+    return cnn_score_enqueue(model, cp, x, G, ldg, m, batch, gamma, rho, scores, cws, reinterpret_cast<hipStream_t>(stream_));
+  }
   const Plan p = make_plan(model, m, batch->n_r);
   if (p.total > (size_t)ZENO_STATIC_SCRATCH_BYTES) return ZENO_ERR_UNSUPPORTED;
   unsigned char* ws = nullptr;
@@ -464,6 +712,7 @@ zeno_status_t zeno_score_static(const zeno_model_t* model, const float* x, const
 
 zeno_status_t zeno_score_plan_check(const zeno_model_t* model, int32_t m, int32_t n_r) {
   if (model == nullptr || m < 1 || m > ZENO_MAX_CANDIDATES || n_r < 1) return ZENO_ERR_INVALID_ARG;
+  if (model->kind != 0) return ZENO_ERR_UNSUPPORTED;
   const Plan p = make_plan(model, m, n_r);
   // a fictitious, suitably aligned workspace address: nothing is dereferenced
   unsigned char* ws = reinterpret_cast<unsigned char*>(uintptr_t(1) << 40);

@@ -8,6 +8,20 @@
 
 #include "zeno.h"
 
+// Host-side model object behind zeno_model_t: a chain of linear layers (kind 0) or a
+// convolutional network (kind 1: 3 x 3 convolutions, then one fully connected layer).
+struct zeno_model {
+  int kind;
+  zeno_model_desc_t desc;          // kind 0; for kind 1 it describes the fully connected layer alone
+  int64_t w_off[ZENO_MAX_LAYERS];  // offset of W_l (l = 0..L-1) inside a parameter vector
+  int64_t b_off[ZENO_MAX_LAYERS];  // offset of b_l, or -1
+  int64_t d;
+  // kind 1
+  zeno_cnn_desc_t cnn;
+  int map_h[ZENO_MAX_CONV + 1], map_w[ZENO_MAX_CONV + 1], map_c[ZENO_MAX_CONV + 1];  // input and every map
+  int64_t conv_w_off[ZENO_MAX_CONV], conv_b_off[ZENO_MAX_CONV];
+};
+
 namespace zeno {
 
 // Four floats with 4-byte alignment: rows of G and the per-layer blocks inside a
@@ -102,6 +116,9 @@ hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, 
                        double* sample_diff, hipStream_t stream);
 hipError_t launch_score_combine(const double* sample_diff, const double* norm_partials, int P, int m,
                                 int n_r_total, float rho, float* scores, hipStream_t stream);
+// the same with the candidates' partial norms P_stride slots apart, the first P of them in use
+hipError_t launch_score_combine_strided(const double* sample_diff, const double* norm_partials, int P_stride, int P,
+                                        int m, int n_r_total, float rho, float* scores, hipStream_t stream);
 // x_next != nullptr: also write x_next = x - gamma * average (out may then be nullptr)
 hipError_t launch_masked_average(const float* G, long long ldg, const float* scores, int m, long long d, int b,
                                  float* out, int32_t* selected, hipStream_t stream, float gamma = 0.f,
@@ -110,6 +127,35 @@ size_t krum_workspace_bytes(int m);
 hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b, float* out, int32_t* chosen,
                        float* scores_out, void* workspace, hipStream_t stream);
 hipError_t launch_median(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream);
+
+// ---- convolutional models (zeno_conv.hip)
+// One 3 x 3 convolution (zero padding 1) as the kernel sees it.
+struct ConvLayer {
+  long long w_off, b_off;  // offsets inside a parameter vector; b_off = -1: no bias
+  int Hin, Win, Cin, Hout, Wout, Cout, stride;
+};
+struct ConvArgs {
+  const float* G;         // [m x d]
+  const float* x;         // [d]
+  long long ldg;
+  int n_cand;             // m: the candidates' pass; 0: the pass at x
+  int n_r;
+  ConvLayer L;
+  const float* H0_in;     // input map of the pass at x, NHWC [n_r * Hin * Win x Cin] (the images for the first convolution)
+  const float* D_in;      // candidate 0's scaled change of the input map, or nullptr (first convolution)
+  long long D_in_stride;  // floats between candidates
+  float* Z0;              // [rows x Cout] pre-activations at x: written by the pass at x, read by the candidates
+  float* out;             // pass at x: relu map; candidates: candidate 0's scaled change of the output map
+  long long out_stride;   // floats between candidates (candidates' pass)
+  int tiled_out;          // 1: out is the operand of the fully connected layer: rows = samples, k = (position, channel),
+  int Kp_fc;              //    in matrix-operand order of padded width Kp_fc
+  float gamma, neg_inv_gamma;
+};
+hipError_t launch_conv(const ConvArgs& a, hipStream_t stream);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
+// sum of squares of G[s][begin .. begin+count) for every candidate, in n_blocks fixed pieces -> partials[s*P + p_off + blk]
+hipError_t launch_sumsq(const float* G, long long ldg, int m, long long begin, long long count, int n_blocks,
+                        double* partials, int P, int p_off, hipStream_t stream);
 
 }  // namespace zeno
 #endif

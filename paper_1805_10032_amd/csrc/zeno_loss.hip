@@ -67,13 +67,14 @@ __global__ __launch_bounds__(64) void loss_diff_kernel(const float* __restrict__
 
 // One wave per candidate: mean over the n_r samples, sum of the partial squared
 // norms, and the three-term combine, all in fp64, rounded once to fp32.
+// A candidate's partial norms lie P_stride apart, of which the first P are in use.
 __global__ __launch_bounds__(64) void score_combine_kernel(const double* __restrict__ sample_diff,
-                                                           const double* __restrict__ norm_partials, int P,
+                                                           const double* __restrict__ norm_partials, int P_stride, int P,
                                                            int n_r_total, float rho, float* __restrict__ scores) {
   const int i = blockIdx.x, lane = threadIdx.x;
   double sd = 0.0, sn = 0.0;
   for (int k = lane; k < n_r_total; k += 64) sd += sample_diff[(long long)i * n_r_total + k];
-  for (int p = lane; p < P; p += 64) sn += norm_partials[(long long)i * P + p];
+  for (int p = lane; p < P; p += 64) sn += norm_partials[(long long)i * P_stride + p];
   sd = wave_sum(sd);
   sn = wave_sum(sn);
   if (lane == 0) scores[i] = (float)(-(sd / (double)n_r_total) - (double)rho * sn);
@@ -89,11 +90,16 @@ hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, 
   return hipGetLastError();
 }
 
+hipError_t launch_score_combine_strided(const double* sample_diff, const double* norm_partials, int P_stride, int P,
+                                        int m, int n_r_total, float rho, float* scores, hipStream_t stream) {
+  hipLaunchKernelGGL(score_combine_kernel, dim3(m), dim3(64), 0, stream, sample_diff, norm_partials, P_stride, P,
+                     n_r_total, rho, scores);
+  return hipGetLastError();
+}
+
 hipError_t launch_score_combine(const double* sample_diff, const double* norm_partials, int P, int m,
                                 int n_r_total, float rho, float* scores, hipStream_t stream) {
-  hipLaunchKernelGGL(score_combine_kernel, dim3(m), dim3(64), 0, stream, sample_diff, norm_partials, P, n_r_total,
-                     rho, scores);
-  return hipGetLastError();
+  return launch_score_combine_strided(sample_diff, norm_partials, P, P, m, n_r_total, rho, scores, stream);
 }
 
 }  // namespace zeno
