@@ -9,8 +9,9 @@ dominant kernel (the candidate layer kernel that streams G), measured with HIP
 events around every launch, and the CPU oracle timed on a bounded sample of the
 same workload as a baseline.  The same line carries, under "also", the same
 measurement for the densely packed layout G[m x d] of the headline workload,
-for workload 4, and for workloads 3, 2 and 1 (buffers rotated so that G comes
-from HBM, eager launches and a replayed HIP graph).
+for workload 4, for workloads 3, 2 and 1 (buffers rotated so that G comes
+from HBM, eager launches and a replayed HIP graph), and for a convolutional
+model of the shape of the paper's own experiments.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5]
 """
@@ -244,6 +245,58 @@ def layer_table(per_layer):
             for k, v in per_layer.items()}
 
 
+CNN_DESC = dict(in_h=32, in_w=32, in_c=3, conv_c=[32, 32, 64, 64], conv_stride=[1, 2, 1, 2], fc_out=10, has_bias=True)
+
+
+def cnn_summary(B, WL, torch, row_align, steps=100, warmup=10):
+    """The shape of the paper's own experiments (Section 6: 32 x 32 x 3 images, four convolutions + one fully
+    connected layer, 10 classes, m = 20, q = b = 8, n_r = 4, gamma = 0.1, rho = 5e-4; widths 32-32-64-64 and
+    strides 1-2-1-2 are this benchmark's choice): zeno_score + zeno_aggregate per step.  d is 0.1 M, so the step is
+    bound by the latency of its launches, not by HBM; reported as time and as matrix-core work."""
+    dev = torch.device("cuda", 0)
+    w = WL.make_cnn_workload("cnn_paper_shaped", 37, CNN_DESC, 20, 8, 4, 0.1, 5e-4, n_flip=8, worker_batch=16,
+                             device=dev, row_align=row_align)
+    mdl = B.ZenoCnnModel(w.desc, w.loss)
+    ws = B.alloc_workspace(mdl, w.m, w.n_r, dev)
+    scores = torch.empty(w.m, device=dev)
+    out = torch.empty(w.d, device=dev)
+    sel = torch.empty(w.m - w.b, dtype=torch.int32, device=dev)
+
+    def step():
+        B.zeno_score(mdl, w.x, w.G, w.features, w.gamma, w.rho, labels=w.labels, scores=scores, workspace=ws)
+        B.zeno_aggregate(w.G, scores, w.b, out=out, selected=sel)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / steps
+    B.profile_enable(True)
+    for _ in range(5):
+        step()
+    torch.cuda.synchronize()
+    recs = B.profile_collect(detail=True)
+    B.profile_enable(False)
+    per = {}
+    for r in recs:
+        e = per.setdefault(f"{r['kernel']}[{r['layer']}]", [0, 0.0, r["bytes"]])
+        e[0] += 1
+        e[1] += r["ms"]
+    shapes = WL.cnn_shapes(w.desc)
+    flops = 0.0
+    for l, ((_, _, ci), (ho, wo, co)) in enumerate(zip(shapes[:-1], shapes[1:])):
+        flops += 2.0 * w.n_r * ho * wo * 9 * ci * co * (1 + w.m * (2 if l > 0 else 1))
+    ho, wo, co = shapes[-1]
+    flops += 2.0 * w.n_r * ho * wo * co * w.desc["fc_out"] * (1 + 2 * w.m)
+    return {"workload": f"CNN 32x32x3 -> conv {w.desc['conv_c']} strides {w.desc['conv_stride']} -> fc 10, d={w.d}, "
+                        f"m={w.m}, b={w.b}, n_r={w.n_r}, gamma={w.gamma}, rho={w.rho}, fp32 forward",
+            "ms_per_step": ms, "aggregations_per_s": 1e3 / ms, "matrix_core_TFLOPs": flops / (ms * 1e-3) / 1e12,
+            "launches": {k: {"avg_ms": v[1] / v[0]} for k, v in per.items()}}
+
+
 def main():
     a = parse_args()
     if a.gpus != 1:
@@ -344,6 +397,7 @@ def main():
         torch.cuda.empty_cache()
         for cfg in (3, 2, 1):
             also[f"config{cfg}"] = Runner(B, WL, torch, cfg, a.row_align).summary(200, 20, graph=True)
+        also["cnn_paper_shaped"] = cnn_summary(B, WL, torch, a.row_align)
         result["also"] = also
     print(json.dumps(result))
 

@@ -409,9 +409,11 @@ zeno_status_t cnn_score_enqueue(const zeno_model* mdl, const CnnPlan& p, const f
   double* sample_diff = reinterpret_cast<double*>(ws + p.off_diff);
   float* dZ = reinterpret_cast<float*>(ws + p.off_dz);
 
-  // the padding of the fully connected layer's operands (samples beyond n_r, columns beyond K) must hold
-  // zeros, not whatever the workspace held: the convolutions only write the live entries
-  {
+  // the padded columns of the fully connected layer's operands (beyond K) must hold zeros, not whatever the
+  // workspace held (they meet the zeros of the masked weight tile, and 0 x NaN is NaN); the convolutions only
+  // write the live entries
+  // (rows beyond n_r may hold anything: a sample's row only reaches its own, discarded, results)
+  if (p.Kp != p.Kfc) {
     ProfScope ps(ZENO_KERNEL_AUX, 0, 0.0, stream);
     ZENO_TRY(launch_fill_zero(ws + p.off_h0t, p.sz_h0t, stream));
     ZENO_TRY(launch_fill_zero(ws + p.off_dt, p.dt_stride * m, stream));

@@ -69,10 +69,13 @@ __global__ __launch_bounds__(64) void conv_layer_kernel(const ConvArgs a) {
     const float* __restrict__ wp = Wrow + tap * L.Cin;
     // channels two at a time: this lane's half h takes channel c0 + h
     int c0 = 0;
-    for (; c0 + 8 <= L.Cin; c0 += 8) {   // four matrix instructions per product with their loads batched
-      float u[4], b1[4], w[4], b2[4];
+    // Batches of eight, then four, matrix instructions per product with all their loads issued first: a
+    // wave walks its 9 c_in operand pairs alone, so the loads in flight per batch set its pace.
+    auto batch = [&](auto nq_c) __attribute__((always_inline)) {
+      constexpr int NQ = decltype(nq_c)::value;
+      float u[NQ], b1[NQ], w[NQ], b2[NQ];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < NQ; ++q) {
         const int c = c0 + 2 * q + h;
         u[q] = f_ok ? up[c] : 0.f;
         b1[q] = p_ok ? hp[c] : 0.f;
@@ -82,11 +85,13 @@ __global__ __launch_bounds__(64) void conv_layer_kernel(const ConvArgs a) {
         }
       }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < NQ; ++q) {
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(u[q], b1[q], acc, 0, 0, 0);
         if (second) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_fmaf(neg_gamma, u[q], w[q]), b2[q], acc, 0, 0, 0);
       }
-    }
+    };
+    for (; c0 + 16 <= L.Cin; c0 += 16) batch(std::integral_constant<int, 8>{});
+    for (; c0 + 8 <= L.Cin; c0 += 8) batch(std::integral_constant<int, 4>{});
     for (; c0 < L.Cin; c0 += 2) {
       const int c = c0 + h;
       const bool c_ok = c < L.Cin;

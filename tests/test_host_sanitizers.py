@@ -26,7 +26,7 @@ def test_argument_layer_under_address_and_ub_sanitizers(tmp_path):
         if src not in ("zeno_capi.hip", "zeno_layer.hip"):
             objs.append(os.path.join(build.OBJ_DIR, src.replace(".hip", ".o")))
     main_obj = str(tmp_path / "host_checks.o")
-    subprocess.run([hipcc, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fsanitize=undefined",
+    subprocess.run([hipcc, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
                     "-fno-sanitize-recover=undefined", "-I", os.path.join(ROOT, "include"),
                     "-c", os.path.join(ROOT, "tests", "sanitize", "host_checks.cpp"), "-o", main_obj],
                    check=True, capture_output=True, text=True)
