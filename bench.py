@@ -241,7 +241,7 @@ def describe(cfg, w):
 
 def layer_table(per_layer):
     return {k: {"avg_ms": v[1] / v[0], "algorithmic_GBps": v[2] / v[1] / 1e6,
-                "shape": {key: v[3][key] for key in ("waves", "k_split", "streaming", "row_blocks", "merged", "second")}}
+                "shape": {key: v[3][key] for key in ("waves", "k_split", "k_slices", "streaming", "row_blocks", "merged", "second")}}
             for k, v in per_layer.items()}
 
 

@@ -43,6 +43,10 @@ struct Plan {
   int wt_rows[ZENO_MAX_LAYERS];    // rows of that copy (features, rounded up to whole workgroup tiles)
   size_t off_dc[2], cand_stride, off_dz, off_norm, off_diff, total;
   size_t sz_hbase[ZENO_MAX_LAYERS], sz_z0[ZENO_MAX_LAYERS], sz_wt[ZENO_MAX_LAYERS], sz_dz;  // bytes of the slots
+  // pass at x with K split over workgroups: partial accumulators (one launch at a time) and, per layer, the
+  // arrival counters of its feature tiles
+  size_t off_slice_part, sz_slice_part, off_slice_cnt;
+  int cnt_off[ZENO_MAX_LAYERS], n_counters;
 };
 
 Plan make_plan(const zeno_model* mdl, int m, int n_r) {
@@ -78,7 +82,12 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
       p.off_wt[l] = take(p.sz_wt[l]);
     }
     p.P += (pad64(N) + 31) / 32;  // upper bound on the partial-norm slots of this layer
+    p.cnt_off[l] = p.n_counters;
+    p.n_counters += (pad64(N) + 31) / 32;
   }
+  p.sz_slice_part = (size_t)kMaxBaseSliceGroups * p.MB * 16 * 64 * sizeof(float);
+  p.off_slice_part = take(p.sz_slice_part);
+  p.off_slice_cnt = take((size_t)p.n_counters * sizeof(unsigned int));
   p.cand_stride = align_up((size_t)p.n_pad * max_np * p.esize, 256);
   if (p.L > 1) {
     for (int i = 0; i < 2; ++i) p.off_dc[i] = take(p.cand_stride * m);
@@ -123,7 +132,7 @@ struct ProfScope {
     e.rec.layer = layer;
     e.rec.ms = 0.f;
     e.rec.algorithmic_bytes = bytes;
-    e.rec.waves = e.rec.k_split = e.rec.streaming = e.rec.row_blocks = e.rec.merged = e.rec.second = 0;
+    e.rec.waves = e.rec.k_split = e.rec.streaming = e.rec.row_blocks = e.rec.merged = e.rec.second = e.rec.k_slices = 0;
     (void)hipEventRecord(e.start, stream);
     g_prof.push_back(e);
     slot = (int)g_prof.size() - 1;
@@ -139,6 +148,7 @@ struct ProfScope {
     r.row_blocks = s.row_blocks;
     r.merged = merged ? 1 : 0;
     r.second = second ? 1 : 0;
+    r.k_slices = s.k_slices;
   }
   ~ProfScope() {
     if (slot < 0) return;
@@ -233,6 +243,8 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
     b.a = common;
     b.a.has_base = 1;
     b.a.bj = make_job(0);
+    b.a.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
+    b.a.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt) + p.cnt_off[0];
     b.delta = false;
     b.kernel = ZENO_KERNEL_LAYER_BASE;
     b.layer = 0;
@@ -278,6 +290,8 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
           b.a = common;
           b.a.has_base = 1;
           b.a.bj = c.a.bj;
+          b.a.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
+          b.a.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt) + p.cnt_off[l + 1];
           b.delta = false;
           b.kernel = ZENO_KERNEL_LAYER_BASE;
           b.layer = l + 1;
@@ -308,6 +322,9 @@ bool launch_fits(const Plan& p, const Launch& L, int NW) {
     if ((size_t)e.dz_floats * sizeof(float) > p.sz_dz) return false;
     if (L.a.P > p.P || L.a.p_off + e.norm_slots > L.a.P) return false;
   }
+  if ((size_t)e.slice_bytes > p.sz_slice_part) return false;
+  if (e.slice_counters > 0 && L.base_layer >= 0 &&
+      p.cnt_off[L.base_layer] + e.slice_counters > p.n_counters) return false;
   return true;
 }
 
@@ -330,7 +347,8 @@ zeno_status_t score_enqueue(const zeno_model* model, const Plan& p, const float*
     {
       ProfScope ps(ZENO_KERNEL_PACK, 0, 4.0 * rows * D.dims[0], stream);
       ZENO_TRY(launch_pack_features(batch->features + (size_t)begin * D.dims[0], rows, D.dims[0], pad64(D.dims[0]),
-                                    p.MB, bf16, ws + p.off_feat, stream));
+                                    p.MB, bf16, ws + p.off_feat,
+                                    reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt), p.n_counters, stream));
     }
     for (const Launch& l : seq) {
       ProfScope ps(l.kernel, l.layer, l.bytes, stream);

@@ -82,17 +82,26 @@ struct LayerArgs {
   float gamma;
   float neg_inv_gamma;  // -1/gamma, or 0 when gamma == 0
   double* norm_partials;  // [m x P] partial sums of squares, or NULL in passes after the first
+  // pass at x on its own with K split over waves: K is also split over base_slices workgroups per feature
+  // tile; each writes its partial accumulators to slice_partials and the last one to arrive (slice_counters,
+  // zero on entry, zero again on exit) adds them in slice order and finishes the tile
+  int base_slices;
+  float* slice_partials;
+  unsigned int* slice_counters;
   int P;                // partial slots per candidate
   int p_off;            // first slot of this layer
 };
 
 // Launchers.  Each returns the hipError_t of its launches.
+// also clears the n_counters workgroup-arrival counters of the pass (may be 0)
 hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, int MB, bool bf16,
-                                void* tiled, hipStream_t stream);
+                                void* tiled, unsigned int* counters, int n_counters, hipStream_t stream);
+constexpr int kMaxBaseSliceGroups = 512;  // workgroups of a sliced pass at x (feature tiles x slices) never exceed this
 // Which instantiation of the layer kernel a launch took (reported in the per-launch timing records).
 struct LaunchShape {
   int waves;       // waves per workgroup that own different feature tiles (1, 4 or 8)
   int k_split;     // waves that share one feature tile and split K (1, 2 or 4)
+  int k_slices;    // workgroups that share one feature tile and split K (pass at x on its own)
   int streaming;   // 1: rows read with non-temporal loads (line-aligned layout)
   int row_blocks;  // 32-sample accumulator blocks per wave (1, 2 or 4)
 };
@@ -109,6 +118,8 @@ struct LayerExtents {
   long long d_bytes_per_cand;  // tiled scaled activation differences of one candidate
   long long dz_floats;         // output layer's change of pre-activations, all candidates
   int norm_slots;              // partial-norm slots per candidate
+  long long slice_bytes;       // partial accumulators of a sliced pass at x
+  int slice_counters;          // arrival counters it uses
 };
 LayerExtents layer_extents(const LayerArgs& a, bool bf16, int MB, int NW);  // partial-norm slots (feature tiles) of the candidate job of this launch
 hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, const float* targets,

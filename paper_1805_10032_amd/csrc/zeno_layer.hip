@@ -67,6 +67,18 @@ LayerExtents layer_extents(const LayerArgs& a, bool bf16, int MB, int NW) {
     if (j.Wt != nullptr) e.wt_bytes = (long long)job_tiles(j, 32 * NW) * NW * (j.Kp >> 6) * wregs * 1024;
     e.z0_floats = (long long)a.n_r * j.N;
     if (!j.last) e.hbase_bytes = tiled_bytes(j.Np);
+    // K split over workgroups as well (only a pass at x on its own in one-wave tiles): at most 8 slices per tile
+    if (NW == 1 && a.n_cand == 0 && a.slice_partials != nullptr) {
+      int worst = 1;
+      for (int ks = 2; ks <= 4; ks *= 2) {
+        const int sl = base_slices_for(a, ks);
+        if (sl > worst) worst = sl;
+      }
+      if (worst > 1) {
+        e.slice_bytes = (long long)job_tiles(j, 32) * worst * MB * 16 * 64 * (long long)sizeof(float);
+        e.slice_counters = job_tiles(j, 32);
+      }
+    }
   }
   if (a.n_cand > 0) {
     const LayerJob& j = a.cj;
@@ -96,14 +108,16 @@ bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB) {
 }
 
 hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, int MB, bool bf16, void* tiled,
-                                hipStream_t stream) {
+                                unsigned int* counters, int n_counters, hipStream_t stream) {
   const int n_pad = 32 * MB;
   const long long total = (long long)n_pad * Kp;
   const int grid = (int)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
   if (bf16) {
-    hipLaunchKernelGGL(pack_features_kernel<true>, dim3(grid), dim3(256), 0, stream, features, n_r, K, Kp, n_pad, tiled);
+    hipLaunchKernelGGL(pack_features_kernel<true>, dim3(grid), dim3(256), 0, stream, features, n_r, K, Kp, n_pad, tiled,
+                       counters, n_counters);
   } else {
-    hipLaunchKernelGGL(pack_features_kernel<false>, dim3(grid), dim3(256), 0, stream, features, n_r, K, Kp, n_pad, tiled);
+    hipLaunchKernelGGL(pack_features_kernel<false>, dim3(grid), dim3(256), 0, stream, features, n_r, K, Kp, n_pad, tiled,
+                       counters, n_counters);
   }
   return hipGetLastError();
 }

@@ -310,8 +310,15 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   const int n_chunks = J.Kp >> 6;
   const int n_tiles = (cover_rows(N, last) + BN - 1) / BN;
   int nt, s = 0;
+  int ks = 0, n_slices = 1;   // K slice of this workgroup (pass at x on its own, K split over workgroups too)
   if (is_base) {
-    nt = blockIdx.x;
+    if (KS > 1 && a.base_slices > 1) {
+      n_slices = a.base_slices;
+      nt = blockIdx.x / n_slices;
+      ks = blockIdx.x % n_slices;
+    } else {
+      nt = blockIdx.x;
+    }
     if (nt >= n_tiles) return;
   } else {
     const int bid = blockIdx.x - a.base_blocks;
@@ -344,8 +351,9 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // loads lets a chunk wait for exactly its own activation copies) / ragged in K, and BASE (pass at x: no second product, writes W in operand order) or
   // candidate.
   const bool all_full = (K & 63) == 0;
-  const int c_begin = KS > 1 ? n_chunks * kw / KS : 0;
-  const int c_end = KS > 1 ? n_chunks * (kw + 1) / KS : n_chunks;
+  const int cs0 = n_chunks * ks / n_slices, cs1 = n_chunks * (ks + 1) / n_slices;   // this workgroup's chunks
+  const int c_begin = KS > 1 ? cs0 + (cs1 - cs0) * kw / KS : 0;
+  const int c_end = KS > 1 ? cs0 + (cs1 - cs0) * (kw + 1) / KS : n_chunks;
 
   f32x16 acc[MB];
 #pragma unroll
@@ -593,6 +601,65 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       }
     }
     if (kw != 0) return;
+    if (n_slices > 1) {
+      // K was also split over workgroups: publish this workgroup's partial accumulators, and let the last
+      // workgroup of the tile to arrive add all of them, in slice order whoever it is, and finish the tile
+      // layout: per slice MB*4 pieces of 64 lanes x 16 bytes (accumulator registers 4q..4q+3 of block mb)
+      float* part = a.slice_partials + (long long)nt * n_slices * (MB * 16 * 64);
+      float* mine = part + (long long)ks * (MB * 16 * 64);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 v = {acc[mb][4 * q], acc[mb][4 * q + 1], acc[mb][4 * q + 2], acc[mb][4 * q + 3]};
+          // written through to memory (system scope): the compute units' L2 caches are per XCD and the
+          // workgroup that adds the partials may sit on another one
+          asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(mine + ((mb * 4 + q) * 64 + lane) * 4), "v"(v) : "memory");
+        }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partials have reached memory before the arrival is counted
+      unsigned arrived = 0;
+      if (lane == 0) arrived = __hip_atomic_fetch_add(&a.slice_counters[nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      arrived = __builtin_amdgcn_readfirstlane(arrived);
+      if (arrived != (unsigned)(n_slices - 1)) return;
+      // The other workgroups' partials are read with system-scope loads (they bypass the caches on the way,
+      // as the stores did, so no cache has to be written back or invalidated), a slice's MB*4 loads issued
+      // together and completed by one wait.  The wait statements name
+      // the loaded registers as operands so that no use of them can be scheduled ahead of it.  This
+      // workgroup's own slice comes from its registers (bit-identical to what it stored).
+      f32x16 total[MB];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) total[mb][j] = 0.f;
+      for (int q = 0; q < n_slices; ++q) {
+        if (q == ks) {   // uniform over the wave
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) total[mb][j] += acc[mb][j];
+          continue;
+        }
+        const float* other = part + (long long)q * (MB * 16 * 64);
+        f32x4 t[MB][4];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1" : "=v"(t[mb][r]) : "v"(other + ((mb * 4 + r) * 64 + lane) * 4) : "memory");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(t[mb][0]), "+v"(t[mb][1]), "+v"(t[mb][2]), "+v"(t[mb][3])::"memory");
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) total[mb][4 * r + e] += t[mb][r][e];
+      }
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) acc[mb] = total[mb];
+      if (lane == 0) __hip_atomic_store(&a.slice_counters[nt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next pass
+    }
   }
 
   // ---- epilogue.  The weight tile is the first operand of the products, so the
@@ -733,8 +800,10 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
 
 template <bool BF16>
 __global__ void pack_features_kernel(const float* __restrict__ features, int n_r, int K, int Kp, int n_pad,
-                                     void* __restrict__ tiled) {
+                                     void* __restrict__ tiled, unsigned int* __restrict__ counters, int n_counters) {
   const long long total = (long long)n_pad * Kp;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n_counters; i += (long long)gridDim.x * blockDim.x)
+    counters[i] = 0u;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
     const int r = (int)(i / Kp), k = (int)(i % Kp);
     const float v = (r < n_r && k < K) ? features[(long long)r * K + k] : 0.f;
@@ -744,12 +813,25 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
 
 int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
 
+// Workgroups per feature tile of a pass at x that runs on its own with K split over KS waves: as many as
+// bring the launch to about one workgroup per compute unit, while every wave keeps at least two chunks.
+inline int base_slices_for(const LayerArgs& a, int KS) {
+  if (!a.has_base || a.n_cand > 0 || a.slice_partials == nullptr || a.slice_counters == nullptr || KS <= 1) return 1;
+  const int tiles = job_tiles(a.bj, 32), n_chunks = a.bj.Kp >> 6;
+  int s = 256 / (tiles > 0 ? tiles : 1);
+  if (s > n_chunks / (2 * KS)) s = n_chunks / (2 * KS);
+  if (s > 8) s = 8;
+  while (s > 1 && tiles * s > kMaxBaseSliceGroups) --s;
+  return s < 1 ? 1 : s;
+}
+
 template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1>
 hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
   constexpr int BN = 32 * NW;
   if (shape != nullptr) {
     shape->waves = NW;
     shape->k_split = KS;
+    shape->k_slices = KS > 1 ? base_slices_for(a, KS) : 1;
     shape->streaming = NT ? 1 : 0;
     shape->row_blocks = MB;
   }
@@ -760,7 +842,9 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)
                             : hipSuccess;
   if (attr_err != hipSuccess) return attr_err;
-  a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) + 7) / 8 * 8 : 0;
+  if (KS > 1) a.base_slices = base_slices_for(a, KS);
+  else a.base_slices = 1;
+  a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) * a.base_slices + 7) / 8 * 8 : 0;
   int cand_blocks = 0;
   if (a.n_cand > 0) {
     const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
