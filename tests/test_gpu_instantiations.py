@@ -135,3 +135,28 @@ def test_zz_which_instantiations_ran(B):
             missing.append((fwd, "k_split"))
     print("\n  launch shapes seen:", sorted(SEEN))
     assert not missing, missing
+
+
+@pytest.mark.parametrize("fwd,n_r", [("fp32", 200), ("bf16", 300), ("bf16", 64)])
+def test_pass_at_x_split_over_workgroups(B, fwd, n_r):
+    """A pass at x on its own whose feature tiles are too few to fill the chip splits K over workgroups as well
+    as over waves: partial accumulators go through memory and the last workgroup of a tile to arrive adds them.
+    Batches of more than 128 samples run it once per pass over G (the arrival counters are cleared every pass);
+    scores are compared on all rows and must not change from run to run."""
+    w, s_ref, s_exact, scale = _workload(("slices", fwd, n_r), [2048, 320, 1024, 10], 12, 3, n_r, fwd, 2, 1)
+    shapes = _run(B, w, s_ref, s_exact, scale, 32)
+    print(f"\n  slices {fwd} n_r={n_r}: {shapes}")
+    assert any(s[0] == "layer_base" for s in shapes)
+    dev = torch.device("cuda", 0)
+    mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
+    G = rows_to_gpu(B, w.G, 32, dev)
+    B.profile_enable(True)
+    try:
+        a = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
+        torch.cuda.synchronize()
+        recs = B.profile_collect(detail=True)
+    finally:
+        B.profile_enable(False)
+    assert max(r["k_slices"] for r in recs if r["kernel"] == "layer_base") > 1, recs
+    b = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
+    assert torch.equal(a, b)
