@@ -15,8 +15,9 @@
 //
 // One wave owns 32 output positions x 32 output channels in one 32x32 fp32 accumulator block
 // (v_mfma_f32_32x32x2_f32, kernel values as the first operand so that a lane is a position and
-// its registers are channels), walks the nine taps and, per tap, the input channels two at a
-// time.  Kernels are a few hundred KB per candidate and the maps a few MB, so everything but
+// its registers are channels), walks the nine taps and, per tap, the input channels eight at a
+// time (one 128-bit load per lane and operand feeds four matrix instructions; the tail of a channel
+// count that is not a multiple of eight goes two at a time).  Kernels are a few hundred KB per candidate and the maps a few MB, so everything but
 // the first touch comes from the caches; the path is bound by instruction issue and latency,
 // not by HBM.  The last convolution writes its outputs straight into the matrix-operand
 // order of the fully connected layer (rows = samples, columns = (y, x, c)), which the
@@ -69,29 +70,35 @@ __global__ __launch_bounds__(64) void conv_layer_kernel(const ConvArgs a) {
     const float* __restrict__ wp = Wrow + tap * L.Cin;
     // channels two at a time: this lane's half h takes channel c0 + h
     int c0 = 0;
-    // Batches of eight, then four, matrix instructions per product with all their loads issued first: a
-    // wave walks its 9 c_in operand pairs alone, so the loads in flight per batch set its pace.
-    auto batch = [&](auto nq_c) __attribute__((always_inline)) {
-      constexpr int NQ = decltype(nq_c)::value;
-      float u[NQ], b1[NQ], w[NQ], b2[NQ];
+    // Eight channels at a time: each lane loads FOUR consecutive channels of its kernel row / its position with
+    // one 128-bit load (half h takes channels c0 + 4h .. c0 + 4h + 3) and feeds four matrix instructions, the
+    // i-th of which contracts the channel pair (c0 + i, c0 + 4 + i).  Two such groups are loaded ahead of
+    // their instructions.  A wave walks its operands alone, so the loads in flight set its pace.
+    auto group8 = [&](auto ng_c) __attribute__((always_inline)) {
+      constexpr int NG = decltype(ng_c)::value;
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      f32x4 u[NG], b1[NG], w[NG], b2[NG];
 #pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        const int c = c0 + 2 * q + h;
-        u[q] = f_ok ? up[c] : 0.f;
-        b1[q] = p_ok ? hp[c] : 0.f;
+      for (int g = 0; g < NG; ++g) {
+        const int c = c0 + 8 * g + 4 * h;
+        u[g] = f_ok ? *reinterpret_cast<const f32x4_a4*>(up + c) : zero;
+        b1[g] = p_ok ? *reinterpret_cast<const f32x4_a4*>(hp + c) : zero;
         if (second) {
-          w[q] = f_ok ? wp[c] : 0.f;
-          b2[q] = p_ok ? dp[c] : 0.f;
+          w[g] = f_ok ? *reinterpret_cast<const f32x4_a4*>(wp + c) : zero;
+          b2[g] = p_ok ? *reinterpret_cast<const f32x4_a4*>(dp + c) : zero;
         }
       }
 #pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(u[q], b1[q], acc, 0, 0, 0);
-        if (second) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_fmaf(neg_gamma, u[q], w[q]), b2[q], acc, 0, 0, 0);
-      }
+      for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(u[g][i], b1[g][i], acc, 0, 0, 0);
+          if (second)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_fmaf(neg_gamma, u[g][i], w[g][i]), b2[g][i], acc, 0, 0, 0);
+        }
     };
-    for (; c0 + 16 <= L.Cin; c0 += 16) batch(std::integral_constant<int, 8>{});
-    for (; c0 + 8 <= L.Cin; c0 += 8) batch(std::integral_constant<int, 4>{});
+    for (; c0 + 16 <= L.Cin; c0 += 16) group8(std::integral_constant<int, 2>{});
+    for (; c0 + 8 <= L.Cin; c0 += 8) group8(std::integral_constant<int, 1>{});
     for (; c0 < L.Cin; c0 += 2) {
       const int c = c0 + h;
       const bool c_ok = c < L.Cin;
