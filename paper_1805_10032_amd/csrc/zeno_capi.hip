@@ -35,6 +35,15 @@ inline int wt_rows_alloc(int N, bool last) {
   return (cover + kMaxTileRows - 1) / kMaxTileRows * kMaxTileRows;
 }
 
+// Upper bound on the partial-norm slots of a layer N wide: its 32-row tiles, times up to 8 K slices while
+// tiles x slices stays within 256 (launches are only sliced while they have fewer workgroups than that).
+inline int norm_slots_bound(int N) {
+  const int tiles = (pad64(N) + 31) / 32;
+  const int sliced = 8 * tiles < 256 ? 8 * tiles : 256;
+  return tiles > sliced ? tiles : sliced;
+}
+constexpr int kMaxSlicedGroups = 256;   // tiles (x candidates) of a launch that is sliced at all
+
 // Workspace layout, shared by the size query and the call itself.
 struct Plan {
   int L, pass_rows, MB, n_pad, esize, P;
@@ -46,7 +55,7 @@ struct Plan {
   // pass at x with K split over workgroups: partial accumulators (one launch at a time) and, per layer, the
   // arrival counters of its feature tiles
   size_t off_slice_part, sz_slice_part, off_slice_cnt;
-  int cnt_off[ZENO_MAX_LAYERS], n_counters;
+  int cnt_off[ZENO_MAX_LAYERS], cnt_off_cand[ZENO_MAX_LAYERS], n_counters;
 };
 
 Plan make_plan(const zeno_model* mdl, int m, int n_r) {
@@ -81,9 +90,11 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
       p.sz_wt[l] = (size_t)p.wt_rows[l] * pad64(D.dims[l]) * p.esize;
       p.off_wt[l] = take(p.sz_wt[l]);
     }
-    p.P += (pad64(N) + 31) / 32;  // upper bound on the partial-norm slots of this layer
+    p.P += norm_slots_bound(N);   // upper bound on the partial-norm slots of this layer
     p.cnt_off[l] = p.n_counters;
     p.n_counters += (pad64(N) + 31) / 32;
+    p.cnt_off_cand[l] = p.n_counters;
+    p.n_counters += kMaxSlicedGroups;
   }
   p.sz_slice_part = (size_t)kMaxBaseSliceGroups * p.MB * 16 * 64 * sizeof(float);
   p.off_slice_part = take(p.sz_slice_part);
@@ -226,17 +237,6 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
   common.neg_inv_gamma = gamma > 0.f ? -1.0f / gamma : 0.f;
   common.n_r = rows;
 
-  // partial-norm slots actually used by the candidate launches
-  int p_off[ZENO_MAX_LAYERS], P = 0;
-  for (int l = 0; l < L; ++l) {
-    LayerArgs t = common;
-    t.n_cand = m;
-    t.cj = make_job(l);
-    p_off[l] = P;
-    P += query_device ? layer_tiles(t, bf16, l > 0, p.MB) : (pad64(D.dims[l + 1]) + 31) / 32;
-  }
-  *P_out = P;
-
   std::vector<Launch> seq;
   if (L > 1) {
     Launch b;
@@ -259,8 +259,6 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
     c.a.n_cand = m;
     c.a.cj = make_job(l);
     c.a.norm_partials = first_pass ? reinterpret_cast<double*>(ws + p.off_norm) : nullptr;
-    c.a.P = P;
-    c.a.p_off = p_off[l];
     c.delta = l > 0;
     c.kernel = ZENO_KERNEL_LAYER_CAND;
     c.layer = l;
@@ -305,13 +303,28 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
     }
     seq.push_back(c);
   }
+  // Partial-norm slots of the candidate launches, now that it is known which of them also carry the pass at x
+  // (those are never split over workgroups): a launch gets feature tiles x K slices slots.
+  int P = 0;
+  for (Launch& c : seq) {
+    if (c.a.n_cand <= 0) continue;
+    if (!c.a.has_base) {
+      c.a.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
+      c.a.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt) + p.cnt_off_cand[c.layer];
+    }
+    c.a.p_off = P;
+    P += query_device ? layer_tiles(c.a, bf16, c.delta, p.MB) : norm_slots_bound(D.dims[c.layer + 1]);
+  }
+  for (Launch& c : seq)
+    if (c.a.n_cand > 0) c.a.P = P;
+  *P_out = P;
   return seq;
 }
 
 // Does everything a launch writes with NW waves per workgroup lie inside its workspace slot?
 bool launch_fits(const Plan& p, const Launch& L, int NW) {
   const bool bf16 = p.esize == 2;
-  const LayerExtents e = layer_extents(L.a, bf16, p.MB, NW);
+  const LayerExtents e = layer_extents(L.a, bf16, L.delta, p.MB, NW);
   if (L.wt_layer >= 0 ? (size_t)e.wt_bytes > p.sz_wt[L.wt_layer] : e.wt_bytes != 0) return false;
   if (L.base_layer >= 0) {
     if ((size_t)e.z0_floats * sizeof(float) > p.sz_z0[L.base_layer]) return false;
@@ -323,8 +336,10 @@ bool launch_fits(const Plan& p, const Launch& L, int NW) {
     if (L.a.P > p.P || L.a.p_off + e.norm_slots > L.a.P) return false;
   }
   if ((size_t)e.slice_bytes > p.sz_slice_part) return false;
-  if (e.slice_counters > 0 && L.base_layer >= 0 &&
-      p.cnt_off[L.base_layer] + e.slice_counters > p.n_counters) return false;
+  if (e.slice_counters > 0) {
+    if (L.a.n_cand > 0 ? e.slice_counters > kMaxSlicedGroups
+                       : (L.base_layer < 0 || e.slice_counters > (pad64(L.a.bj.N) + 31) / 32)) return false;
+  }
   return true;
 }
 
@@ -374,6 +389,7 @@ struct CnnPlan {
   size_t off_z0[ZENO_MAX_CONV], off_h0[ZENO_MAX_CONV], off_d[2], d_stride;  // maps (floats per candidate in d_stride)
   size_t off_h0t, off_dt, dt_stride, sz_h0t;                                  // operands of the fully connected layer
   size_t off_wt, off_z0fc, off_dz, off_norm, off_diff, total;
+  size_t off_slice_part, off_slice_cnt, sz_slice_cnt;   // K slices of the fully connected layer's launches
 };
 
 CnnPlan make_cnn_plan(const zeno_model* mdl, int m, int n_r) {
@@ -411,8 +427,11 @@ CnnPlan make_cnn_plan(const zeno_model* mdl, int m, int n_r) {
   p.off_wt = take((size_t)wt_rows_alloc(N, true) * p.Kp * sizeof(float));
   p.off_z0fc = take((size_t)n_r * N * sizeof(float));
   p.off_dz = take((size_t)m * n_r * N * sizeof(float));
-  p.P = (pad64(N) + 31) / 32 + kConvNormBlocks;
+  p.P = norm_slots_bound(N) + kConvNormBlocks;
   p.off_norm = take((size_t)m * p.P * sizeof(double));
+  p.off_slice_part = take((size_t)kMaxBaseSliceGroups * p.MB * 16 * 64 * sizeof(float));
+  p.sz_slice_cnt = align_up(((size_t)(pad64(N) + 31) / 32 + kMaxSlicedGroups) * sizeof(unsigned int), 256);
+  p.off_slice_cnt = take(p.sz_slice_cnt);
   p.off_diff = take((size_t)m * n_r * sizeof(double));
   p.total = off;
   return p;
@@ -431,6 +450,10 @@ zeno_status_t cnn_score_enqueue(const zeno_model* mdl, const CnnPlan& p, const f
   // workspace held (they meet the zeros of the masked weight tile, and 0 x NaN is NaN); the convolutions only
   // write the live entries
   // (rows beyond n_r may hold anything: a sample's row only reaches its own, discarded, results)
+  {
+    ProfScope ps(ZENO_KERNEL_AUX, 2, 0.0, stream);
+    ZENO_TRY(launch_fill_zero(ws + p.off_slice_cnt, p.sz_slice_cnt, stream));   // arrival counters start at zero
+  }
   if (p.Kp != p.Kfc) {
     ProfScope ps(ZENO_KERNEL_AUX, 0, 0.0, stream);
     ZENO_TRY(launch_fill_zero(ws + p.off_h0t, p.sz_h0t, stream));
@@ -515,6 +538,8 @@ zeno_status_t cnn_score_enqueue(const zeno_model* mdl, const CnnPlan& p, const f
     LayerArgs b = common;
     b.has_base = 1;
     b.bj = j;
+    b.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
+    b.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt);
     ProfScope ps(ZENO_KERNEL_LAYER_BASE, C, fc_bytes, stream);
     ZENO_TRY(launch_layer(b, false, false, p.MB, stream));
   }
@@ -526,6 +551,8 @@ zeno_status_t cnn_score_enqueue(const zeno_model* mdl, const CnnPlan& p, const f
   c.norm_partials = norm_partials;
   c.P = p.P;
   c.p_off = 0;
+  c.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
+  c.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt) + (pad64(N) + 31) / 32;
   const int fc_tiles = layer_tiles(c, false, true, p.MB);
   if (fc_tiles + kConvNormBlocks > p.P) return ZENO_ERR_WORKSPACE;
   {

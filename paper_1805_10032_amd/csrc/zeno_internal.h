@@ -82,10 +82,11 @@ struct LayerArgs {
   float gamma;
   float neg_inv_gamma;  // -1/gamma, or 0 when gamma == 0
   double* norm_partials;  // [m x P] partial sums of squares, or NULL in passes after the first
-  // pass at x on its own with K split over waves: K is also split over base_slices workgroups per feature
-  // tile; each writes its partial accumulators to slice_partials and the last one to arrive (slice_counters,
-  // zero on entry, zero again on exit) adds them in slice order and finishes the tile
-  int base_slices;
+  // launches of one-wave tiles with K split over waves that run the pass at x or the candidates alone: K is
+  // also split over k_slices workgroups per tile; each writes its partial accumulators to slice_partials and
+  // the last one to arrive (slice_counters, zero on entry, zero again on exit) adds them in slice order and
+  // finishes the tile (k_slices is set by the launcher)
+  int k_slices;
   float* slice_partials;
   unsigned int* slice_counters;
   int P;                // partial slots per candidate
@@ -121,7 +122,7 @@ struct LayerExtents {
   long long slice_bytes;       // partial accumulators of a sliced pass at x
   int slice_counters;          // arrival counters it uses
 };
-LayerExtents layer_extents(const LayerArgs& a, bool bf16, int MB, int NW);  // partial-norm slots (feature tiles) of the candidate job of this launch
+LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, int NW);  // partial-norm slots (feature tiles) of the candidate job of this launch
 hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, const float* targets,
                        int loss, int m, int n_r_total, int chunk_begin, int chunk_rows, int C,
                        double* sample_diff, hipStream_t stream);

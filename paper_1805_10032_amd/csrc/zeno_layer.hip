@@ -12,6 +12,10 @@ hipError_t launch_layer_bf16_delta(const LayerArgs& a, int MB, int NW, hipStream
 hipError_t launch_layer_bf16_first(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
 hipError_t launch_layer_f32_delta(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
 hipError_t launch_layer_f32_first(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
+int ks_waves_bf16_delta(int MB);
+int ks_waves_bf16_first(int MB);
+int ks_waves_f32_delta(int MB);
+int ks_waves_f32_first(int MB);
 int wgs_per_cu_bf16_delta(int MB, int NW);
 int wgs_per_cu_bf16_first(int MB, int NW);
 int wgs_per_cu_f32_delta(int MB, int NW);
@@ -51,9 +55,21 @@ static int nw_for(const LayerArgs& a, bool bf16, bool delta, int MB) {
 
 int layer_nw(const LayerArgs& a, bool bf16, bool delta, int MB) { return nw_for(a, bf16, delta, MB); }
 
+// K slices (workgroups per tile) the launch will take: the conditions of the launcher in zeno_layer_impl.h.
+static int launch_slices(const LayerArgs& a, bool bf16, bool delta, int MB) {
+  if (nw_for(a, bf16, delta, MB) != 1) return 1;
+  const int KS = bf16 ? (delta ? ks_waves_bf16_delta(MB) : ks_waves_bf16_first(MB))
+                      : (delta ? ks_waves_f32_delta(MB) : ks_waves_f32_first(MB));
+  if (KS <= 1) return 1;
+  const bool base_ok = !a.has_base || (a.bj.Kp >> 6) >= 2 * KS;
+  const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * KS;
+  if (!((a.has_base || a.n_cand > 0) && base_ok && cand_ok)) return 1;
+  return slices_for(a, KS);
+}
+
 // What a launch of workgroup width NW writes, from the kernel's own index formulas: the
 // host checks these against the workspace slots before anything is enqueued.
-LayerExtents layer_extents(const LayerArgs& a, bool bf16, int MB, int NW) {
+LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, int NW) {
   LayerExtents e;
   std::memset(&e, 0, sizeof(e));
   const int esize = bf16 ? 2 : 4, wregs = bf16 ? 4 : 8, n_pad = 32 * MB;
@@ -67,18 +83,6 @@ LayerExtents layer_extents(const LayerArgs& a, bool bf16, int MB, int NW) {
     if (j.Wt != nullptr) e.wt_bytes = (long long)job_tiles(j, 32 * NW) * NW * (j.Kp >> 6) * wregs * 1024;
     e.z0_floats = (long long)a.n_r * j.N;
     if (!j.last) e.hbase_bytes = tiled_bytes(j.Np);
-    // K split over workgroups as well (only a pass at x on its own in one-wave tiles): at most 8 slices per tile
-    if (NW == 1 && a.n_cand == 0 && a.slice_partials != nullptr) {
-      int worst = 1;
-      for (int ks = 2; ks <= 4; ks *= 2) {
-        const int sl = base_slices_for(a, ks);
-        if (sl > worst) worst = sl;
-      }
-      if (worst > 1) {
-        e.slice_bytes = (long long)job_tiles(j, 32) * worst * MB * 16 * 64 * (long long)sizeof(float);
-        e.slice_counters = job_tiles(j, 32);
-      }
-    }
   }
   if (a.n_cand > 0) {
     const LayerJob& j = a.cj;
@@ -86,10 +90,25 @@ LayerExtents layer_extents(const LayerArgs& a, bool bf16, int MB, int NW) {
     else e.d_bytes_per_cand = tiled_bytes(j.Np);
     e.norm_slots = job_tiles(j, 32 * NW);
   }
+  // K split over workgroups as well (one-wave tiles, the pass at x or the candidates alone)
+  if (NW == 1 && a.slice_partials != nullptr && (a.has_base != 0) != (a.n_cand > 0)) {
+    const int KS = bf16 ? (delta ? ks_waves_bf16_delta(MB) : ks_waves_bf16_first(MB))
+                        : (delta ? ks_waves_f32_delta(MB) : ks_waves_f32_first(MB));
+    const bool long_enough = ((a.has_base ? a.bj.Kp : a.cj.Kp) >> 6) >= 2 * KS;
+    const int worst = (KS > 1 && long_enough) ? slices_for(a, KS) : 1;
+    if (worst > 1) {
+      const long long groups = (long long)job_tiles(a.has_base ? a.bj : a.cj, 32) * (a.has_base ? 1 : a.n_cand);
+      e.slice_bytes = groups * worst * MB * 16 * 64 * (long long)sizeof(float);
+      e.slice_counters = (int)groups;
+      if (a.n_cand > 0) e.norm_slots *= worst;
+    }
+  }
   return e;
 }
 
-int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB) { return job_tiles(a.cj, 32 * nw_for(a, bf16, delta, MB)); }
+int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB) {
+  return job_tiles(a.cj, 32 * nw_for(a, bf16, delta, MB)) * launch_slices(a, bf16, delta, MB);
+}
 
 // Should the pass at x (a.bj) ride in the candidates' launch?  Workgroups run in
 // rounds of (compute units x resident workgroups); the extra workgroups are free

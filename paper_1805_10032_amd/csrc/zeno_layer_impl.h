@@ -310,18 +310,18 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   const int n_chunks = J.Kp >> 6;
   const int n_tiles = (cover_rows(N, last) + BN - 1) / BN;
   int nt, s = 0;
-  int ks = 0, n_slices = 1;   // K slice of this workgroup (pass at x on its own, K split over workgroups too)
+  // K slice of this workgroup: a launch of one-wave tiles that runs the pass at x OR the candidates (not
+  // both) and has too few tiles to fill the chip splits K over k_slices workgroups per tile as well
+  int ks = 0;
+  const int n_slices = (KS > 1 && a.k_slices > 1) ? a.k_slices : 1;
   if (is_base) {
-    if (KS > 1 && a.base_slices > 1) {
-      n_slices = a.base_slices;
-      nt = blockIdx.x / n_slices;
-      ks = blockIdx.x % n_slices;
-    } else {
-      nt = blockIdx.x;
-    }
+    nt = blockIdx.x / n_slices;
+    ks = blockIdx.x % n_slices;
     if (nt >= n_tiles) return;
   } else {
-    const int bid = blockIdx.x - a.base_blocks;
+    int bid = blockIdx.x - a.base_blocks;
+    ks = bid % n_slices;
+    bid /= n_slices;
     const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
     const int n_cchunks = (a.n_cand + cc - 1) / cc;
     const int xcd = bid & 7, slot = bid >> 3;
@@ -605,7 +605,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       // K was also split over workgroups: publish this workgroup's partial accumulators, and let the last
       // workgroup of the tile to arrive add all of them, in slice order whoever it is, and finish the tile
       // layout: per slice MB*4 pieces of 64 lanes x 16 bytes (accumulator registers 4q..4q+3 of block mb)
-      float* part = a.slice_partials + (long long)nt * n_slices * (MB * 16 * 64);
+      const long long grp = is_base ? nt : (long long)s * n_tiles + nt;   // the tile this workgroup shares
+      float* part = a.slice_partials + grp * n_slices * (MB * 16 * 64);
       float* mine = part + (long long)ks * (MB * 16 * 64);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
@@ -618,9 +619,13 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
         }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partials have reached memory before the arrival is counted
       unsigned arrived = 0;
-      if (lane == 0) arrived = __hip_atomic_fetch_add(&a.slice_counters[nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (lane == 0) arrived = __hip_atomic_fetch_add(&a.slice_counters[grp], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       arrived = __builtin_amdgcn_readfirstlane(arrived);
-      if (arrived != (unsigned)(n_slices - 1)) return;
+      if (arrived != (unsigned)(n_slices - 1)) {
+        // not the last one: only this slice's share of ||u||^2 is left to deliver (lane 0 holds it)
+        if (do_norm && lane == 0) a.norm_partials[(long long)s * a.P + a.p_off + nt * n_slices + ks] = nrm;
+        return;
+      }
       // The other workgroups' partials are read with system-scope loads (they bypass the caches on the way,
       // as the stores did, so no cache has to be written back or invalidated), a slice's MB*4 loads issued
       // together and completed by one wait.  The wait statements name
@@ -658,7 +663,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       }
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) acc[mb] = total[mb];
-      if (lane == 0) __hip_atomic_store(&a.slice_counters[nt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next pass
+      if (lane == 0) __hip_atomic_store(&a.slice_counters[grp], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next pass
     }
   }
 
@@ -782,8 +787,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
     if (KS > 1) {
-      // only wave 0 is left, and it holds the whole tile's sum
-      if (lane == 0) a.norm_partials[(long long)s * a.P + a.p_off + nt] = nrm;
+      // only wave 0 is left, and it holds the sum over this workgroup's chunks
+      if (lane == 0) a.norm_partials[(long long)s * a.P + a.p_off + nt * n_slices + ks] = nrm;
     } else {
       __syncthreads();
       double* red = reinterpret_cast<double*>(lds);
@@ -813,16 +818,20 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
 
 int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
 
-// Workgroups per feature tile of a pass at x that runs on its own with K split over KS waves: as many as
-// bring the launch to about one workgroup per compute unit, while every wave keeps at least two chunks.
-inline int base_slices_for(const LayerArgs& a, int KS) {
-  if (!a.has_base || a.n_cand > 0 || a.slice_partials == nullptr || a.slice_counters == nullptr || KS <= 1) return 1;
-  const int tiles = job_tiles(a.bj, 32), n_chunks = a.bj.Kp >> 6;
-  int s = 256 / (tiles > 0 ? tiles : 1);
+// Workgroups per feature tile of a launch of one-wave tiles with K split over KS waves that runs the pass at x
+// or the candidates alone: as many as bring the launch to about one workgroup per compute unit, while every
+// wave keeps at least two chunks.
+inline int slices_for(const LayerArgs& a, int KS) {
+  if (KS <= 1 || a.slice_partials == nullptr || a.slice_counters == nullptr) return 1;
+  if ((a.has_base != 0) == (a.n_cand > 0)) return 1;   // both jobs in one launch (or none)
+  const LayerJob& j = a.has_base ? a.bj : a.cj;
+  const long long groups = (long long)job_tiles(j, 32) * (a.has_base ? 1 : a.n_cand);
+  const int n_chunks = j.Kp >> 6;
+  long long s = 256 / (groups > 0 ? groups : 1);
   if (s > n_chunks / (2 * KS)) s = n_chunks / (2 * KS);
   if (s > 8) s = 8;
-  while (s > 1 && tiles * s > kMaxBaseSliceGroups) --s;
-  return s < 1 ? 1 : s;
+  while (s > 1 && groups * s > kMaxBaseSliceGroups) --s;
+  return s < 1 ? 1 : (int)s;
 }
 
 template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1>
@@ -831,7 +840,7 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
   if (shape != nullptr) {
     shape->waves = NW;
     shape->k_split = KS;
-    shape->k_slices = KS > 1 ? base_slices_for(a, KS) : 1;
+    shape->k_slices = KS > 1 ? slices_for(a, KS) : 1;
     shape->streaming = NT ? 1 : 0;
     shape->row_blocks = MB;
   }
@@ -842,14 +851,13 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)
                             : hipSuccess;
   if (attr_err != hipSuccess) return attr_err;
-  if (KS > 1) a.base_slices = base_slices_for(a, KS);
-  else a.base_slices = 1;
-  a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) * a.base_slices + 7) / 8 * 8 : 0;
+  a.k_slices = KS > 1 ? slices_for(a, KS) : 1;
+  a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) * (a.n_cand > 0 ? 1 : a.k_slices) + 7) / 8 * 8 : 0;
   int cand_blocks = 0;
   if (a.n_cand > 0) {
     const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
     const int units = job_tiles(a.cj, BN) * ((a.n_cand + cc - 1) / cc);
-    cand_blocks = ((units + 7) / 8) * 8 * cc;
+    cand_blocks = ((units + 7) / 8) * 8 * cc * a.k_slices;
   }
   hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW, NT, KS>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW * KS),
                      lds_bytes, stream, a);
@@ -964,6 +972,10 @@ int launch_nw_for(const LayerArgs& a) {
     return launch_mb<BF16, DELTA>(a, MB, NW, stream, shape);                                      \
   }                                                                                               \
   int wgs_per_cu_##NAME(int MB, int NW) { return wgs_per_cu_mb<BF16, DELTA>(MB, NW); }            \
+  int ks_waves_##NAME(int MB) {                                                                   \
+    return MB == 1 ? split_k_waves<BF16, DELTA, 1>() : MB == 2 ? split_k_waves<BF16, DELTA, 2>()  \
+                                                               : split_k_waves<BF16, DELTA, 4>(); \
+  }                                                                                               \
   }
 
 #endif  // ZENO_LAYER_IMPL_H_
