@@ -28,10 +28,14 @@ namespace zeno {
 
 namespace {
 
-template <bool CAND>
-__global__ __launch_bounds__(64) void conv_layer_kernel(const ConvArgs a) {
+// TW = 3: three waves share one tile and take one kernel row (ky) each; their accumulators are added through
+// LDS in the fixed order (0 + 1) + 2 and wave 0 finishes the tile.  Used when the launch has too few tiles
+// to occupy the matrix cores otherwise (a wave's 9 c_in / 2 dependent matrix instructions set its pace).
+template <bool CAND, int TW>
+__global__ __launch_bounds__(64 * TW) void conv_layer_kernel(const ConvArgs a) {
   const ConvLayer& L = a.L;
-  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const int lane = threadIdx.x & 63, n = lane & 31, h = lane >> 5;
+  const int tw = TW > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) : 0;
   const int ftiles = (L.Cout + 31) / 32;
   const int ft = blockIdx.x % ftiles, rb = blockIdx.x / ftiles;
   const int s = blockIdx.y;
@@ -59,7 +63,7 @@ __global__ __launch_bounds__(64) void conv_layer_kernel(const ConvArgs a) {
   for (int j = 0; j < 16; ++j) acc[j] = 0.f;
   const float neg_gamma = -a.gamma;
 
-  for (int tap = 0; tap < 9; ++tap) {
+  for (int tap = (TW > 1 ? 3 * tw : 0); tap < (TW > 1 ? 3 * tw + 3 : 9); ++tap) {
     const int ky = tap / 3, kx = tap % 3;
     const int iy = oy * L.stride + ky - 1, ix = ox * L.stride + kx - 1;
     const bool p_ok = r_ok && iy >= 0 && iy < L.Hin && ix >= 0 && ix < L.Win;
@@ -113,6 +117,17 @@ __global__ __launch_bounds__(64) void conv_layer_kernel(const ConvArgs a) {
     }
   }
 
+  if (TW > 1) {
+    __shared__ float red[2][16][64];
+    if (tw > 0) {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) red[tw - 1][j][lane] = acc[j];
+    }
+    __syncthreads();
+    if (tw > 0) return;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = (acc[j] + red[0][j][lane]) + red[1][j][lane];
+  }
   // accumulator element j of lane (n, h): position r (this lane's), output channel ft*32 + 8 (j/4) + 4 h + j%4
   if (!r_ok) return;
   float* __restrict__ out = CAND ? a.out + (long long)s * a.out_stride : a.out;
@@ -173,11 +188,16 @@ hipError_t launch_conv(const ConvArgs& a, hipStream_t stream) {
   const long long rows = (long long)a.n_r * a.L.Hout * a.L.Wout;
   const long long row_blocks = (rows + 31) / 32;
   const int ftiles = (a.L.Cout + 31) / 32;
-  const dim3 grid((unsigned)(row_blocks * ftiles), a.n_cand > 0 ? a.n_cand : 1);
+  const int sources = a.n_cand > 0 ? a.n_cand : 1;
+  const dim3 grid((unsigned)(row_blocks * ftiles), sources);
+  // one wave per tile when there are tiles enough for every SIMD of the chip twice over, else three
+  const bool wide = row_blocks * ftiles * sources >= 2048;
   if (a.n_cand > 0) {
-    hipLaunchKernelGGL(conv_layer_kernel<true>, grid, dim3(64), 0, stream, a);
+    if (wide) hipLaunchKernelGGL((conv_layer_kernel<true, 1>), grid, dim3(64), 0, stream, a);
+    else hipLaunchKernelGGL((conv_layer_kernel<true, 3>), grid, dim3(192), 0, stream, a);
   } else {
-    hipLaunchKernelGGL(conv_layer_kernel<false>, grid, dim3(64), 0, stream, a);
+    if (wide) hipLaunchKernelGGL((conv_layer_kernel<false, 1>), grid, dim3(64), 0, stream, a);
+    else hipLaunchKernelGGL((conv_layer_kernel<false, 3>), grid, dim3(192), 0, stream, a);
   }
   return hipGetLastError();
 }
