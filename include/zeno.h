@@ -59,7 +59,8 @@ typedef enum {
   ZENO_ERR_INVALID_ARG = 1, /* NULL/misaligned pointer, m<1, m>1024, b<0, b>=m, n_r<1, ldg<d, bad gamma/rho/dims */
   ZENO_ERR_UNSUPPORTED = 2, /* a size beyond what the kernels cover (see each call) */
   ZENO_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned (256 B) or smaller than the query says */
-  ZENO_ERR_DEVICE = 4       /* a HIP launch failed */
+  ZENO_ERR_DEVICE = 4,      /* a HIP launch failed */
+  ZENO_ERR_HOST_MEMORY = 5  /* the host-side model object could not be allocated */
 } zeno_status_t;
 
 typedef enum {

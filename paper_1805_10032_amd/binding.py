@@ -19,7 +19,7 @@ ZENO_MAX_LAYERS = 8
 ZENO_MAX_CANDIDATES = 1024
 LOSS = {"squared": 0, "softmax_ce": 1}
 FWD = {"fp32": 0, "bf16": 1}
-STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported size", 3: "workspace", 4: "device"}
+STATUS = {0: "ok", 1: "invalid argument", 2: "unsupported size", 3: "workspace", 4: "device", 5: "host memory"}
 
 EXPORTS = ["zeno_model_create", "zeno_cnn_model_create", "zeno_model_destroy", "zeno_model_num_params",
            "zeno_score_workspace_bytes", "zeno_score", "zeno_score_static", "zeno_aggregate", "zeno_aggregate_update", "zeno_mean",

@@ -634,7 +634,7 @@ zeno_status_t zeno_model_create(const zeno_model_desc_t* desc, zeno_model_t** ou
   if (desc->fwd != ZENO_FWD_FP32 && desc->fwd != ZENO_FWD_BF16) return ZENO_ERR_INVALID_ARG;
   if (desc->loss == ZENO_LOSS_SQUARED && desc->dims[desc->n_layers] != 1) return ZENO_ERR_INVALID_ARG;
   zeno_model* mdl = new (std::nothrow) zeno_model;
-  if (mdl == nullptr) return ZENO_ERR_DEVICE;
+  if (mdl == nullptr) return ZENO_ERR_HOST_MEMORY;
   std::memset(mdl, 0, sizeof(*mdl));
   mdl->kind = 0;
   mdl->desc = *desc;
@@ -663,7 +663,7 @@ zeno_status_t zeno_cnn_model_create(const zeno_cnn_desc_t* desc, zeno_model_t** 
   for (int l = 0; l < desc->n_conv; ++l)
     if (desc->conv_c[l] < 1 || (desc->conv_stride[l] != 1 && desc->conv_stride[l] != 2)) return ZENO_ERR_INVALID_ARG;
   zeno_model* mdl = new (std::nothrow) zeno_model;
-  if (mdl == nullptr) return ZENO_ERR_DEVICE;
+  if (mdl == nullptr) return ZENO_ERR_HOST_MEMORY;
   std::memset(mdl, 0, sizeof(*mdl));
   mdl->kind = 1;
   mdl->cnn = *desc;
@@ -851,6 +851,7 @@ const char* zeno_status_string(int32_t status) {
     case ZENO_ERR_UNSUPPORTED: return "unsupported size";
     case ZENO_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case ZENO_ERR_DEVICE: return "HIP launch failed";
+    case ZENO_ERR_HOST_MEMORY: return "out of host memory";
   }
   return "unknown status";
 }
