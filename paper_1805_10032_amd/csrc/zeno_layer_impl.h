@@ -248,7 +248,8 @@ __device__ inline void lds_dma16(const unsigned char* src, unsigned char* dst) {
 }
 
 // LDS layout of a workgroup: [activation chunk buffers (one or two)] [one staging
-// tile per wave] [32 bias values per wave].
+// tile per wave].  (Nothing else: with 4 row blocks, bf16 operands, the second product and
+// four waves the layout is exactly 80 KB, and two such workgroups share a compute unit.)
 template <bool BF16, bool DELTA, int MB, int NW>
 struct Lds {
   using T = Tr<BF16>;
@@ -257,8 +258,7 @@ struct Lds {
   static constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
   static constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
   static constexpr int STAGE_OFF = AD_BYTES * (DBUF ? 2 : 1);
-  static constexpr int BIAS_OFF = STAGE_OFF + NW * STAGE_BYTES;
-  static constexpr int TOTAL = BIAS_OFF + NW * 32 * 4;
+  static constexpr int TOTAL = STAGE_OFF + NW * STAGE_BYTES;
 };
 
 // KS > 1 (launches of one-wave tiles, NW == 1): the KS waves of a workgroup own the SAME
@@ -293,7 +293,6 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   const int kw = KS > 1 ? wave_id : 0;     // which part of K this wave sums
   unsigned char* lds = lds_all + kw * LD::TOTAL;
   unsigned char* stU = lds + LD::STAGE_OFF + wave * STAGE_BYTES;
-  float* biasL = reinterpret_cast<float*>(lds + LD::BIAS_OFF) + wave * 32;
 
   // Which job: the leading base_blocks block indices run the pass at x (one
   // feature tile each), the rest the candidates.
@@ -366,6 +365,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
 
   f32x4 u0[8], u1[8];
   f32x4 w0[WREGS], w1[WREGS];
+  float bias_lane = 0.f;
 
   // Asynchronous copy of chunk c of the tiled activation operands into LDS buffer
   // `buf`: AD_KB pieces of 1 KB (64 lanes x 16 B land at consecutive LDS addresses),
@@ -451,6 +451,12 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       } else {
         asm volatile("" ::: "memory");  // private buffers: only the compiler must not move LDS reads above the wait
       }
+      // Issue priorities of a wave inside a chunk: highest while it requests the next copies and weight
+      // tiles (memory requests leave as early as possible), raised during the matrix products, lowest
+      // while it converts and stages a tile.  Of the two waves that share a SIMD the one that is behind
+      // (still in its products while the other already stages the next tile) is served first, and it is
+      // the one every other wave of the workgroup will wait for at the next barrier.
+      __builtin_amdgcn_s_setprio(3);
       if (STEADY || c + 1 < c_end) copy_AD(c + 1, buf ^ 1);
       __builtin_amdgcn_sched_barrier(0);  // the wait above counts on the copies being issued before the next loads
     } else {
@@ -461,6 +467,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     }
     if (STEADY || c + 2 < c_end) load_tile<MODE, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
 
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
     // Matrix products of this chunk in groups of MB products that share one B
     // operand (k-step t, operand H or D).  The scheduler is fenced so that the LDS
     // reads of group g+1 are issued right behind the products of group g.
@@ -509,6 +517,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       }
       if (BASE && pack && op == 0) *reinterpret_cast<f32x4*>(Wt_wave + ((long long)c * WREGS + t) * 1024) = bq[t];
     }
+    __builtin_amdgcn_s_setprio(0);
     if (SECOND && (STEADY || c + 2 < c_end)) load_W(w, c + 2);
   };
 
@@ -516,9 +525,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     constexpr int MODE = decltype(full_c)::value;
     constexpr bool FULL = MODE != 0;
     constexpr bool SECOND = DELTA && !decltype(base_c)::value;
-    // The wave's 32 bias values are requested first of all and parked in LDS, so
-    // that the epilogue does not start with a round trip to memory.
-    float bias_lane = 0.f;
+    // The wave's 32 bias values are requested first of all (lane i < 32 keeps feature row0 + i's),
+    // so that the epilogue does not start with a round trip to memory.
     if (J.b_off >= 0 && lane < 32 && row0 + lane < N) bias_lane = P[J.b_off + row0 + lane];
     __builtin_amdgcn_sched_barrier(0);
     if (DBUF) copy_AD(c_begin, c_begin & 1);
@@ -533,7 +541,6 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
         load_W(w0, c_begin);
         load_W(w1, c_begin + 1);
       }
-      if (lane < 32) biasL[lane] = bias_lane;
       for (; c + 3 < c_end; c += 2) {
         chunk(full_c, base_c, std::true_type{}, u0, w0, c);
         chunk(full_c, base_c, std::true_type{}, u1, w1, c + 1);
@@ -545,7 +552,6 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
         load_W(w0, c_begin);
         if (c_begin + 1 < c_end) load_W(w1, c_begin + 1);
       }
-      if (lane < 32) biasL[lane] = bias_lane;
     }
     // the last two or three chunks (all of them for a short K): every load is conditional
     for (; c < c_end; c += 2) {
@@ -677,7 +683,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   f32x4 bias[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    bias[q] = *reinterpret_cast<const f32x4*>(biasL + 8 * q + 4 * h);   // written by this wave before the main loop
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bias[q][i] = __shfl(bias_lane, 8 * q + 4 * h + i, 64);   // loaded before the main loop
     // every feature of the tile sits in exactly one of the two lanes with n == 0
     if (do_norm && n == 0)
       nrm += (double)((bias[q][0] * bias[q][0] + bias[q][1] * bias[q][1]) + (bias[q][2] * bias[q][2] + bias[q][3] * bias[q][3]));
