@@ -35,14 +35,15 @@ inline int wt_rows_alloc(int N, bool last) {
   return (cover + kMaxTileRows - 1) / kMaxTileRows * kMaxTileRows;
 }
 
-// Upper bound on the partial-norm slots of a layer N wide: its 32-row tiles, times up to 8 K slices while
-// tiles x slices stays within 256 (launches are only sliced while they have fewer workgroups than that).
-inline int norm_slots_bound(int N) {
+// Upper bound on the partial-norm slots per candidate of a layer N wide: its 32-row tiles, times up to 8 K
+// slices while the launch's tiles x candidates x slices stay within the bytes of the partial-accumulator buffer.
+inline int norm_slots_bound(int N, int m, int MB) {
   const int tiles = (pad64(N) + 31) / 32;
-  const int sliced = 8 * tiles < 256 ? 8 * tiles : 256;
-  return tiles > sliced ? tiles : sliced;
+  const long long wgs = (long long)(kSlicePartialBytes / ((size_t)MB * 16 * 64 * sizeof(float)));
+  long long sliced = wgs / (m > 0 ? m : 1);
+  if (sliced > 8LL * tiles) sliced = 8LL * tiles;
+  return tiles > sliced ? tiles : (int)sliced;
 }
-constexpr int kMaxSlicedGroups = 256;   // tiles (x candidates) of a launch that is sliced at all
 
 // Workspace layout, shared by the size query and the call itself.
 struct Plan {
@@ -52,10 +53,10 @@ struct Plan {
   int wt_rows[ZENO_MAX_LAYERS];    // rows of that copy (features, rounded up to whole workgroup tiles)
   size_t off_dc[2], cand_stride, off_dz, off_norm, off_diff, total;
   size_t sz_hbase[ZENO_MAX_LAYERS], sz_z0[ZENO_MAX_LAYERS], sz_wt[ZENO_MAX_LAYERS], sz_dz;  // bytes of the slots
-  // pass at x with K split over workgroups: partial accumulators (one launch at a time) and, per layer, the
-  // arrival counters of its feature tiles
+  // launches with K split over workgroups: partial accumulators and the arrival counters of the feature
+  // tiles, shared by all launches of a pass (they run one after the other and leave the counters at zero)
   size_t off_slice_part, sz_slice_part, off_slice_cnt;
-  int cnt_off[ZENO_MAX_LAYERS], cnt_off_cand[ZENO_MAX_LAYERS], n_counters;
+  int n_counters;
 };
 
 Plan make_plan(const zeno_model* mdl, int m, int n_r) {
@@ -90,13 +91,10 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
       p.sz_wt[l] = (size_t)p.wt_rows[l] * pad64(D.dims[l]) * p.esize;
       p.off_wt[l] = take(p.sz_wt[l]);
     }
-    p.P += norm_slots_bound(N);   // upper bound on the partial-norm slots of this layer
-    p.cnt_off[l] = p.n_counters;
-    p.n_counters += (pad64(N) + 31) / 32;
-    p.cnt_off_cand[l] = p.n_counters;
-    p.n_counters += kMaxSlicedGroups;
+    p.P += norm_slots_bound(N, m, p.MB);   // upper bound on the partial-norm slots of this layer
   }
-  p.sz_slice_part = (size_t)kMaxBaseSliceGroups * p.MB * 16 * 64 * sizeof(float);
+  p.n_counters = kMaxSliceGroups;
+  p.sz_slice_part = kSlicePartialBytes;
   p.off_slice_part = take(p.sz_slice_part);
   p.off_slice_cnt = take((size_t)p.n_counters * sizeof(unsigned int));
   p.cand_stride = align_up((size_t)p.n_pad * max_np * p.esize, 256);
@@ -236,6 +234,8 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
   common.gamma = gamma;
   common.neg_inv_gamma = gamma > 0.f ? -1.0f / gamma : 0.f;
   common.n_r = rows;
+  common.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
+  common.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt);
 
   std::vector<Launch> seq;
   if (L > 1) {
@@ -243,8 +243,6 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
     b.a = common;
     b.a.has_base = 1;
     b.a.bj = make_job(0);
-    b.a.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
-    b.a.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt) + p.cnt_off[0];
     b.delta = false;
     b.kernel = ZENO_KERNEL_LAYER_BASE;
     b.layer = 0;
@@ -288,8 +286,6 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
           b.a = common;
           b.a.has_base = 1;
           b.a.bj = c.a.bj;
-          b.a.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
-          b.a.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt) + p.cnt_off[l + 1];
           b.delta = false;
           b.kernel = ZENO_KERNEL_LAYER_BASE;
           b.layer = l + 1;
@@ -304,16 +300,12 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
     seq.push_back(c);
   }
   // Partial-norm slots of the candidate launches, now that it is known which of them also carry the pass at x
-  // (those are never split over workgroups): a launch gets feature tiles x K slices slots.
+  // (that changes how a launch of one-wave tiles splits K): a launch gets feature tiles x K slices slots.
   int P = 0;
   for (Launch& c : seq) {
     if (c.a.n_cand <= 0) continue;
-    if (!c.a.has_base) {
-      c.a.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
-      c.a.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt) + p.cnt_off_cand[c.layer];
-    }
     c.a.p_off = P;
-    P += query_device ? layer_tiles(c.a, bf16, c.delta, p.MB) : norm_slots_bound(D.dims[c.layer + 1]);
+    P += query_device ? layer_tiles(c.a, bf16, c.delta, p.MB) : norm_slots_bound(D.dims[c.layer + 1], m, p.MB);
   }
   for (Launch& c : seq)
     if (c.a.n_cand > 0) c.a.P = P;
@@ -322,9 +314,9 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
 }
 
 // Does everything a launch writes with NW waves per workgroup lie inside its workspace slot?
-bool launch_fits(const Plan& p, const Launch& L, int NW) {
+bool launch_fits(const Plan& p, const Launch& L, int NW, bool device) {
   const bool bf16 = p.esize == 2;
-  const LayerExtents e = layer_extents(L.a, bf16, L.delta, p.MB, NW);
+  const LayerExtents e = layer_extents(L.a, bf16, L.delta, p.MB, NW, device);
   if (L.wt_layer >= 0 ? (size_t)e.wt_bytes > p.sz_wt[L.wt_layer] : e.wt_bytes != 0) return false;
   if (L.base_layer >= 0) {
     if ((size_t)e.z0_floats * sizeof(float) > p.sz_z0[L.base_layer]) return false;
@@ -335,11 +327,7 @@ bool launch_fits(const Plan& p, const Launch& L, int NW) {
     if ((size_t)e.dz_floats * sizeof(float) > p.sz_dz) return false;
     if (L.a.P > p.P || L.a.p_off + e.norm_slots > L.a.P) return false;
   }
-  if ((size_t)e.slice_bytes > p.sz_slice_part) return false;
-  if (e.slice_counters > 0) {
-    if (L.a.n_cand > 0 ? e.slice_counters > kMaxSlicedGroups
-                       : (L.base_layer < 0 || e.slice_counters > (pad64(L.a.bj.N) + 31) / 32)) return false;
-  }
+  if ((size_t)e.slice_bytes > p.sz_slice_part || e.slice_counters > p.n_counters) return false;
   return true;
 }
 
@@ -358,7 +346,7 @@ zeno_status_t score_enqueue(const zeno_model* model, const Plan& p, const float*
     const std::vector<Launch> seq = layer_sequence(model, p, x, G, ldg, m, gamma, ws, rows, begin == 0, &P);
     // nothing is enqueued for a pass unless every launch of it stays inside its slots
     for (const Launch& l : seq)
-      if (!launch_fits(p, l, layer_nw(l.a, bf16, l.delta, p.MB))) return ZENO_ERR_WORKSPACE;
+      if (!launch_fits(p, l, layer_nw(l.a, bf16, l.delta, p.MB), true)) return ZENO_ERR_WORKSPACE;
     {
       ProfScope ps(ZENO_KERNEL_PACK, 0, 4.0 * rows * D.dims[0], stream);
       ZENO_TRY(launch_pack_features(batch->features + (size_t)begin * D.dims[0], rows, D.dims[0], pad64(D.dims[0]),
@@ -427,10 +415,10 @@ CnnPlan make_cnn_plan(const zeno_model* mdl, int m, int n_r) {
   p.off_wt = take((size_t)wt_rows_alloc(N, true) * p.Kp * sizeof(float));
   p.off_z0fc = take((size_t)n_r * N * sizeof(float));
   p.off_dz = take((size_t)m * n_r * N * sizeof(float));
-  p.P = norm_slots_bound(N) + kConvNormBlocks;
+  p.P = norm_slots_bound(N, m, p.MB) + kConvNormBlocks;
   p.off_norm = take((size_t)m * p.P * sizeof(double));
-  p.off_slice_part = take((size_t)kMaxBaseSliceGroups * p.MB * 16 * 64 * sizeof(float));
-  p.sz_slice_cnt = align_up(((size_t)(pad64(N) + 31) / 32 + kMaxSlicedGroups) * sizeof(unsigned int), 256);
+  p.off_slice_part = take(kSlicePartialBytes);
+  p.sz_slice_cnt = align_up((size_t)kMaxSliceGroups * sizeof(unsigned int), 256);
   p.off_slice_cnt = take(p.sz_slice_cnt);
   p.off_diff = take((size_t)m * n_r * sizeof(double));
   p.total = off;
@@ -533,13 +521,13 @@ zeno_status_t cnn_score_enqueue(const zeno_model* mdl, const CnnPlan& p, const f
   common.gamma = gamma;
   common.neg_inv_gamma = neg_inv_gamma;
   common.n_r = n_r;
+  common.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
+  common.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt);
   const double fc_bytes = 4.0 * ((double)N * p.Kfc + (j.b_off >= 0 ? N : 0));
   {
     LayerArgs b = common;
     b.has_base = 1;
     b.bj = j;
-    b.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
-    b.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt);
     ProfScope ps(ZENO_KERNEL_LAYER_BASE, C, fc_bytes, stream);
     ZENO_TRY(launch_layer(b, false, false, p.MB, stream));
   }
@@ -551,8 +539,6 @@ zeno_status_t cnn_score_enqueue(const zeno_model* mdl, const CnnPlan& p, const f
   c.norm_partials = norm_partials;
   c.P = p.P;
   c.p_off = 0;
-  c.slice_partials = reinterpret_cast<float*>(ws + p.off_slice_part);
-  c.slice_counters = reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt) + (pad64(N) + 31) / 32;
   const int fc_tiles = layer_tiles(c, false, true, p.MB);
   if (fc_tiles + kConvNormBlocks > p.P) return ZENO_ERR_WORKSPACE;
   {
@@ -776,7 +762,7 @@ zeno_status_t zeno_score_plan_check(const zeno_model_t* model, int32_t m, int32_
                                                    /*query_device=*/false);
     for (const Launch& L : seq)
       for (int NW : widths)
-        if (!launch_fits(p, L, NW)) return ZENO_ERR_WORKSPACE;
+        if (!launch_fits(p, L, NW, false)) return ZENO_ERR_WORKSPACE;
   }
   return ZENO_OK;
 }

@@ -82,11 +82,15 @@ struct LayerArgs {
   float gamma;
   float neg_inv_gamma;  // -1/gamma, or 0 when gamma == 0
   double* norm_partials;  // [m x P] partial sums of squares, or NULL in passes after the first
-  // launches of one-wave tiles with K split over waves that run the pass at x or the candidates alone: K is
-  // also split over k_slices workgroups per tile; each writes its partial accumulators to slice_partials and
-  // the last one to arrive (slice_counters, zero on entry, zero again on exit) adds them in slice order and
-  // finishes the tile (k_slices is set by the launcher)
+  // K split of a launch of one-wave tiles (the launcher fills these in from layer_k_plan): k_waves waves of a
+  // workgroup share a feature tile and split K (1, or the widest split the LDS layout allows), and K is also
+  // split over k_slices workgroups per tile.  Each of those writes its partial accumulators to slice_partials,
+  // and the last one to arrive (slice_counters, zero on entry, zero again on exit) adds them in slice order and
+  // finishes the tile.  Tiles are numbered [pass at x: its feature tiles] [candidates: slice_group0 +
+  // candidate x tiles + tile].
+  int k_waves;
   int k_slices;
+  long long slice_group0;
   float* slice_partials;
   unsigned int* slice_counters;
   int P;                // partial slots per candidate
@@ -97,19 +101,30 @@ struct LayerArgs {
 // also clears the n_counters workgroup-arrival counters of the pass (may be 0)
 hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, int MB, bool bf16,
                                 void* tiled, unsigned int* counters, int n_counters, hipStream_t stream);
-constexpr int kMaxBaseSliceGroups = 512;  // workgroups of a sliced pass at x (feature tiles x slices) never exceed this
+// Limits of a launch whose K is split over workgroups: bytes of partial accumulators (tiles x slices x row
+// blocks x 4 KB) and tiles (= arrival counters).  One buffer of each serves all launches of a pass, which run
+// one after the other and leave the counters at zero.
+constexpr size_t kSlicePartialBytes = size_t(8) << 20;
+constexpr int kMaxSliceGroups = 2048;
+struct KPlan {
+  int k_waves;    // waves of a workgroup that share a feature tile and split K
+  int k_slices;   // workgroups per feature tile
+};
+// The K split a launch with NW waves per workgroup takes (NW > 1: none).  device = false: no device is asked
+// for occupancies and the result is the widest split any device could be given (for sizing and checking).
+KPlan layer_k_plan(const LayerArgs& a, bool bf16, bool delta, int MB, int NW, bool device);
 // Which instantiation of the layer kernel a launch took (reported in the per-launch timing records).
 struct LaunchShape {
   int waves;       // waves per workgroup that own different feature tiles (1, 4 or 8)
   int k_split;     // waves that share one feature tile and split K (1, 2 or 4)
-  int k_slices;    // workgroups that share one feature tile and split K (pass at x on its own)
+  int k_slices;    // workgroups that share one feature tile and split K (1 to 8)
   int streaming;   // 1: rows read with non-temporal loads (line-aligned layout)
   int row_blocks;  // 32-sample accumulator blocks per wave (1, 2 or 4)
 };
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream,
                         LaunchShape* shape = nullptr);
 bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB);  // run a.bj inside the candidates' launch?
-int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB);
+int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB);   // partial-norm slots per candidate the launch fills
 int layer_nw(const LayerArgs& a, bool bf16, bool delta, int MB);     // waves per workgroup the launch will use
 // Extents a launch with NW waves per workgroup writes (bytes / floats / slots, counted from the start of each buffer).
 struct LayerExtents {
@@ -119,10 +134,10 @@ struct LayerExtents {
   long long d_bytes_per_cand;  // tiled scaled activation differences of one candidate
   long long dz_floats;         // output layer's change of pre-activations, all candidates
   int norm_slots;              // partial-norm slots per candidate
-  long long slice_bytes;       // partial accumulators of a sliced pass at x
+  long long slice_bytes;       // partial accumulators of a launch with K split over workgroups
   int slice_counters;          // arrival counters it uses
 };
-LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, int NW);  // partial-norm slots (feature tiles) of the candidate job of this launch
+LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, int NW, bool device);
 hipError_t launch_loss(const float* Z0, const float* dZ, const int32_t* labels, const float* targets,
                        int loss, int m, int n_r_total, int chunk_begin, int chunk_rows, int C,
                        double* sample_diff, hipStream_t stream);

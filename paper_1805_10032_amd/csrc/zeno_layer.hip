@@ -16,10 +16,10 @@ int ks_waves_bf16_delta(int MB);
 int ks_waves_bf16_first(int MB);
 int ks_waves_f32_delta(int MB);
 int ks_waves_f32_first(int MB);
-int wgs_per_cu_bf16_delta(int MB, int NW);
-int wgs_per_cu_bf16_first(int MB, int NW);
-int wgs_per_cu_f32_delta(int MB, int NW);
-int wgs_per_cu_f32_first(int MB, int NW);
+int wgs_per_cu_bf16_delta(int MB, int NW, int k_waves);
+int wgs_per_cu_bf16_first(int MB, int NW, int k_waves);
+int wgs_per_cu_f32_delta(int MB, int NW, int k_waves);
+int wgs_per_cu_f32_first(int MB, int NW, int k_waves);
 
 static int compute_units() {
   static const int n_cu = [] {
@@ -31,9 +31,14 @@ static int compute_units() {
   return n_cu;
 }
 
-static int wgs_per_cu(bool bf16, bool delta, int MB, int NW) {
-  return bf16 ? (delta ? wgs_per_cu_bf16_delta(MB, NW) : wgs_per_cu_bf16_first(MB, NW))
-              : (delta ? wgs_per_cu_f32_delta(MB, NW) : wgs_per_cu_f32_first(MB, NW));
+static int wgs_per_cu(bool bf16, bool delta, int MB, int NW, int k_waves = 1) {
+  return bf16 ? (delta ? wgs_per_cu_bf16_delta(MB, NW, k_waves) : wgs_per_cu_bf16_first(MB, NW, k_waves))
+              : (delta ? wgs_per_cu_f32_delta(MB, NW, k_waves) : wgs_per_cu_f32_first(MB, NW, k_waves));
+}
+
+static int ks_waves(bool bf16, bool delta, int MB) {
+  return bf16 ? (delta ? ks_waves_bf16_delta(MB) : ks_waves_bf16_first(MB))
+              : (delta ? ks_waves_f32_delta(MB) : ks_waves_f32_first(MB));
 }
 
 // Waves per workgroup of a launch.  Where eight would be picked, four are taken instead if two
@@ -55,21 +60,61 @@ static int nw_for(const LayerArgs& a, bool bf16, bool delta, int MB) {
 
 int layer_nw(const LayerArgs& a, bool bf16, bool delta, int MB) { return nw_for(a, bf16, delta, MB); }
 
-// K slices (workgroups per tile) the launch will take: the conditions of the launcher in zeno_layer_impl.h.
-static int launch_slices(const LayerArgs& a, bool bf16, bool delta, int MB) {
-  if (nw_for(a, bf16, delta, MB) != 1) return 1;
-  const int KS = bf16 ? (delta ? ks_waves_bf16_delta(MB) : ks_waves_bf16_first(MB))
-                      : (delta ? ks_waves_f32_delta(MB) : ks_waves_f32_first(MB));
-  if (KS <= 1) return 1;
-  const bool base_ok = !a.has_base || (a.bj.Kp >> 6) >= 2 * KS;
-  const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * KS;
-  if (!((a.has_base || a.n_cand > 0) && base_ok && cand_ok)) return 1;
-  return slices_for(a, KS);
+// K split of a launch of one-wave tiles.  Such a launch has few feature tiles (the pass at x: N/32; a narrow
+// layer: one or a few per candidate), so a tile's K is divided among the k_waves waves of its workgroup (which
+// add their accumulators through LDS) and among k_slices workgroups (which add theirs through memory, the
+// last one to arrive finishing the tile).  Every wave keeps at least two chunks.
+//  * The waves of a workgroup split K as widely as the LDS layout allows (four or two private copies).
+//  * Workgroups per tile: as many as bring the launch to about one workgroup per compute unit, at most 8.
+//    Measured: on an otherwise idle chip every doubling helps down to two chunks per wave (a ten-class
+//    layer behind 4096 inputs, 20 candidates: 8 slices 35 us, 4 slices 42 us), while a launch that already
+//    has a workgroup per compute unit only gets slower (its workgroups queue, and the round trips of the
+//    hand-over, cheap on an idle chip, take several microseconds each once the memory system is loaded).
+//  * One exception: a launch with somewhat more tiles than compute units whose wide workgroups fit only one
+//    per compute unit (four LDS layouts) would run a full round and a nearly empty one.  One-wave
+//    workgroups, two per tile, several per compute unit, run it in one round (3072 -> 512, 20 candidates:
+//    54 -> 48 us; three or four per tile: 53, 64 us).
+KPlan layer_k_plan(const LayerArgs& a, bool bf16, bool delta, int MB, int NW, bool device) {
+  KPlan plan = {1, 1};
+  if (NW != 1 || (!a.has_base && a.n_cand <= 0)) return plan;
+  const int base_chunks = a.has_base ? a.bj.Kp >> 6 : 1 << 30, cand_chunks = a.n_cand > 0 ? a.cj.Kp >> 6 : 1 << 30;
+  const int min_chunks = base_chunks < cand_chunks ? base_chunks : cand_chunks;
+  const long long groups = (a.has_base ? job_tiles(a.bj, 32) : 0) + (long long)(a.n_cand > 0 ? job_tiles(a.cj, 32) : 0) * a.n_cand;
+  const int ks_max = ks_waves(bf16, delta, MB);
+  const bool wide_ok = ks_max > 1 && min_chunks >= 2 * ks_max;
+  const bool can_slice = a.slice_partials != nullptr && a.slice_counters != nullptr && groups <= kMaxSliceGroups;
+  // most workgroups per tile that the buffers and the two-chunk rule allow
+  auto max_slices = [&](int kw) {
+    if (!can_slice) return 1;
+    long long s = min_chunks / (2 * kw);
+    const long long by_bytes = (long long)(kSlicePartialBytes / ((size_t)MB * 16 * 64 * sizeof(float))) / groups;
+    if (s > by_bytes) s = by_bytes;
+    if (s > 8) s = 8;
+    return s < 1 ? 1 : (int)s;
+  };
+  plan.k_waves = wide_ok ? ks_max : 1;
+  if (!device) {
+    // sizing: the split over workgroups is widest for one-wave workgroups
+    plan.k_slices = max_slices(1);
+    return plan;
+  }
+  const int n_cu = compute_units();
+  long long s = n_cu / groups;
+  const int cap = max_slices(plan.k_waves);
+  if (s > cap) s = cap;
+  plan.k_slices = s < 1 ? 1 : (int)s;
+  if (wide_ok && plan.k_slices == 1 && max_slices(1) >= 2 && (a.n_cand > 0 ? cand_chunks : base_chunks) >= 32 &&
+      groups > (long long)n_cu * wgs_per_cu(bf16, delta, MB, 1, ks_max) && 2 * groups <= 3LL * n_cu &&
+      2 * groups <= (long long)n_cu * wgs_per_cu(bf16, delta, MB, 1, 1)) {
+    plan.k_waves = 1;
+    plan.k_slices = 2;
+  }
+  return plan;
 }
 
 // What a launch of workgroup width NW writes, from the kernel's own index formulas: the
 // host checks these against the workspace slots before anything is enqueued.
-LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, int NW) {
+LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, int NW, bool device) {
   LayerExtents e;
   std::memset(&e, 0, sizeof(e));
   const int esize = bf16 ? 2 : 4, wregs = bf16 ? 4 : 8, n_pad = 32 * MB;
@@ -90,24 +135,20 @@ LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, in
     else e.d_bytes_per_cand = tiled_bytes(j.Np);
     e.norm_slots = job_tiles(j, 32 * NW);
   }
-  // K split over workgroups as well (one-wave tiles, the pass at x or the candidates alone)
-  if (NW == 1 && a.slice_partials != nullptr && (a.has_base != 0) != (a.n_cand > 0)) {
-    const int KS = bf16 ? (delta ? ks_waves_bf16_delta(MB) : ks_waves_bf16_first(MB))
-                        : (delta ? ks_waves_f32_delta(MB) : ks_waves_f32_first(MB));
-    const bool long_enough = ((a.has_base ? a.bj.Kp : a.cj.Kp) >> 6) >= 2 * KS;
-    const int worst = (KS > 1 && long_enough) ? slices_for(a, KS) : 1;
-    if (worst > 1) {
-      const long long groups = (long long)job_tiles(a.has_base ? a.bj : a.cj, 32) * (a.has_base ? 1 : a.n_cand);
-      e.slice_bytes = groups * worst * MB * 16 * 64 * (long long)sizeof(float);
-      e.slice_counters = (int)groups;
-      if (a.n_cand > 0) e.norm_slots *= worst;
-    }
+  // K split over workgroups as well (one-wave tiles)
+  const KPlan kp = layer_k_plan(a, bf16, delta, MB, NW, device);
+  if (kp.k_slices > 1) {
+    const long long groups = (a.has_base ? job_tiles(a.bj, 32) : 0) + (long long)(a.n_cand > 0 ? job_tiles(a.cj, 32) : 0) * a.n_cand;
+    e.slice_bytes = groups * kp.k_slices * MB * 16 * 64 * (long long)sizeof(float);
+    e.slice_counters = (int)groups;
+    if (a.n_cand > 0) e.norm_slots *= kp.k_slices;
   }
   return e;
 }
 
 int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB) {
-  return job_tiles(a.cj, 32 * nw_for(a, bf16, delta, MB)) * launch_slices(a, bf16, delta, MB);
+  const int NW = nw_for(a, bf16, delta, MB);
+  return job_tiles(a.cj, 32 * NW) * layer_k_plan(a, bf16, delta, MB, NW, true).k_slices;
 }
 
 // Should the pass at x (a.bj) ride in the candidates' launch?  Workgroups run in
@@ -143,10 +184,15 @@ hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, i
 
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream, LaunchShape* shape) {
   const int NW = nw_for(a, bf16, delta, MB);
+  LayerArgs b = a;
+  const KPlan kp = layer_k_plan(a, bf16, delta, MB, NW, true);
+  b.k_waves = kp.k_waves;
+  b.k_slices = kp.k_slices;
+  b.slice_group0 = (a.has_base && a.n_cand > 0) ? job_tiles(a.bj, 32) : 0;
   if (bf16) {
-    return delta ? launch_layer_bf16_delta(a, MB, NW, stream, shape) : launch_layer_bf16_first(a, MB, NW, stream, shape);
+    return delta ? launch_layer_bf16_delta(b, MB, NW, stream, shape) : launch_layer_bf16_first(b, MB, NW, stream, shape);
   }
-  return delta ? launch_layer_f32_delta(a, MB, NW, stream, shape) : launch_layer_f32_first(a, MB, NW, stream, shape);
+  return delta ? launch_layer_f32_delta(b, MB, NW, stream, shape) : launch_layer_f32_first(b, MB, NW, stream, shape);
 }
 
 }  // namespace zeno

@@ -309,10 +309,10 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   const int n_chunks = J.Kp >> 6;
   const int n_tiles = (cover_rows(N, last) + BN - 1) / BN;
   int nt, s = 0;
-  // K slice of this workgroup: a launch of one-wave tiles that runs the pass at x OR the candidates (not
-  // both) and has too few tiles to fill the chip splits K over k_slices workgroups per tile as well
+  // K slice of this workgroup: a launch of one-wave tiles whose tiles do not fill the chip well splits K
+  // over k_slices workgroups per tile (on top of, or instead of, the split over the KS waves of a workgroup)
   int ks = 0;
-  const int n_slices = (KS > 1 && a.k_slices > 1) ? a.k_slices : 1;
+  const int n_slices = (NW == 1 && a.k_slices > 1) ? a.k_slices : 1;
   if (is_base) {
     nt = blockIdx.x / n_slices;
     ks = blockIdx.x % n_slices;
@@ -351,8 +351,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // candidate.
   const bool all_full = (K & 63) == 0;
   const int cs0 = n_chunks * ks / n_slices, cs1 = n_chunks * (ks + 1) / n_slices;   // this workgroup's chunks
-  const int c_begin = KS > 1 ? cs0 + (cs1 - cs0) * kw / KS : 0;
-  const int c_end = KS > 1 ? cs0 + (cs1 - cs0) * (kw + 1) / KS : n_chunks;
+  const int c_begin = NW == 1 ? cs0 + (cs1 - cs0) * kw / KS : 0;
+  const int c_end = NW == 1 ? cs0 + (cs1 - cs0) * (kw + 1) / KS : n_chunks;
 
   f32x16 acc[MB];
 #pragma unroll
@@ -607,70 +607,97 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       }
     }
     if (kw != 0) return;
-    if (n_slices > 1) {
-      // K was also split over workgroups: publish this workgroup's partial accumulators, and let the last
-      // workgroup of the tile to arrive add all of them, in slice order whoever it is, and finish the tile
-      // layout: per slice MB*4 pieces of 64 lanes x 16 bytes (accumulator registers 4q..4q+3 of block mb)
-      const long long grp = is_base ? nt : (long long)s * n_tiles + nt;   // the tile this workgroup shares
-      float* part = a.slice_partials + grp * n_slices * (MB * 16 * 64);
-      float* mine = part + (long long)ks * (MB * 16 * 64);
+  }
+  if (NW == 1 && n_slices > 1) {
+    if (KS == 1 && do_norm) {
+      // one wave per workgroup: bring its share of ||u||^2 to lane 0, as the K split over waves does
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
+      for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
+      nrm = lane == 0 ? nrm : 0.0;
+    }
+    // K was also split over workgroups: publish this workgroup's partial accumulators, and let the last
+    // workgroup of the tile to arrive add all of them, in slice order whoever it is, and finish the tile
+    // layout: per slice MB*4 pieces of 64 lanes x 16 bytes (accumulator registers 4q..4q+3 of block mb)
+    const long long grp = is_base ? nt : a.slice_group0 + (long long)s * n_tiles + nt;   // the tile this workgroup shares
+    float* part = a.slice_partials + grp * n_slices * (MB * 16 * 64);
+    float* mine = part + (long long)ks * (MB * 16 * 64);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const f32x4 v = {acc[mb][4 * q], acc[mb][4 * q + 1], acc[mb][4 * q + 2], acc[mb][4 * q + 3]};
-          // written through to memory (system scope): the compute units' L2 caches are per XCD and the
-          // workgroup that adds the partials may sit on another one
-          asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(mine + ((mb * 4 + q) * 64 + lane) * 4), "v"(v) : "memory");
-        }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partials have reached memory before the arrival is counted
-      unsigned arrived = 0;
-      if (lane == 0) arrived = __hip_atomic_fetch_add(&a.slice_counters[grp], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      arrived = __builtin_amdgcn_readfirstlane(arrived);
-      if (arrived != (unsigned)(n_slices - 1)) {
-        // not the last one: only this slice's share of ||u||^2 is left to deliver (lane 0 holds it)
-        if (do_norm && lane == 0) a.norm_partials[(long long)s * a.P + a.p_off + nt * n_slices + ks] = nrm;
-        return;
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 v = {acc[mb][4 * q], acc[mb][4 * q + 1], acc[mb][4 * q + 2], acc[mb][4 * q + 3]};
+        // written through to memory (system scope): the compute units' L2 caches are per XCD and the
+        // workgroup that adds the partials may sit on another one
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(mine + ((mb * 4 + q) * 64 + lane) * 4), "v"(v) : "memory");
       }
-      // The other workgroups' partials are read with system-scope loads (they bypass the caches on the way,
-      // as the stores did, so no cache has to be written back or invalidated), a slice's MB*4 loads issued
-      // together and completed by one wait.  The wait statements name
-      // the loaded registers as operands so that no use of them can be scheduled ahead of it.  This
-      // workgroup's own slice comes from its registers (bit-identical to what it stored).
-      f32x16 total[MB];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partials have reached memory before the arrival is counted
+    unsigned arrived = 0;
+    if (lane == 0) arrived = __hip_atomic_fetch_add(&a.slice_counters[grp], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    arrived = __builtin_amdgcn_readfirstlane(arrived);
+    if (arrived != (unsigned)(n_slices - 1)) {
+      // not the last one: only this slice's share of ||u||^2 is left to deliver (lane 0 holds it)
+      if (do_norm && lane == 0) a.norm_partials[(long long)s * a.P + a.p_off + nt * n_slices + ks] = nrm;
+      return;
+    }
+    // The other workgroups' partials are read with system-scope loads (they bypass the caches on the way,
+    // as the stores did, so no cache has to be written back or invalidated).  A round trip to memory is
+    // long while other workgroups stream at full rate, so the loads of several slices (up to 64 registers'
+    // worth) are issued together and completed by one wait; the wait statements name the loaded registers
+    // as operands so that no use of them can be scheduled ahead of it.  The sum is taken in slice order
+    // whoever adds it; this workgroup's own slice comes from its registers (bit-identical to what it stored).
+    constexpr int BATCH = 4 / MB;   // slices per round trip: 4, 2 or 1
+    f32x16 total[MB];
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) total[mb][j] = 0.f;
-      for (int q = 0; q < n_slices; ++q) {
-        if (q == ks) {   // uniform over the wave
+      for (int j = 0; j < 16; ++j) total[mb][j] = 0.f;
+    for (int q0 = 0; q0 < n_slices; q0 += BATCH) {
+      f32x4 t[BATCH][MB][4];
+#pragma unroll
+      for (int i = 0; i < BATCH; ++i) {
+        const int q = q0 + i;
+        if (q < n_slices && q != ks) {   // uniform over the wave
+          const float* other = part + (long long)q * (MB * 16 * 64);
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1" : "=v"(t[i][mb][r]) : "v"(other + ((mb * 4 + r) * 64 + lane) * 4) : "memory");
+        } else {
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) t[i][mb][r] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int i = 0; i < BATCH; ++i)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+          asm volatile("" : "+v"(t[i][mb][0]), "+v"(t[i][mb][1]), "+v"(t[i][mb][2]), "+v"(t[i][mb][3])::"memory");
+#pragma unroll
+      for (int i = 0; i < BATCH; ++i) {
+        const int q = q0 + i;
+        if (q >= n_slices) break;
+        if (q == ks) {
 #pragma unroll
           for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int j = 0; j < 16; ++j) total[mb][j] += acc[mb][j];
-          continue;
+        } else {
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) total[mb][4 * r + e] += t[i][mb][r][e];
         }
-        const float* other = part + (long long)q * (MB * 16 * 64);
-        f32x4 t[MB][4];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1" : "=v"(t[mb][r]) : "v"(other + ((mb * 4 + r) * 64 + lane) * 4) : "memory");
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) asm volatile("" : "+v"(t[mb][0]), "+v"(t[mb][1]), "+v"(t[mb][2]), "+v"(t[mb][3])::"memory");
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) total[mb][4 * r + e] += t[mb][r][e];
       }
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) acc[mb] = total[mb];
-      if (lane == 0) __hip_atomic_store(&a.slice_counters[grp], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next pass
     }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[mb] = total[mb];
+    if (lane == 0) __hip_atomic_store(&a.slice_counters[grp], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next pass
   }
 
   // ---- epilogue.  The weight tile is the first operand of the products, so the
@@ -793,8 +820,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     // fixed-order reduction: lanes by xor-shuffle tree, then waves in order
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
-    if (KS > 1) {
-      // only wave 0 is left, and it holds the sum over this workgroup's chunks
+    if (NW == 1) {
+      // only one wave is left, and it holds the sum over this workgroup's chunks
       if (lane == 0) a.norm_partials[(long long)s * a.P + a.p_off + nt * n_slices + ks] = nrm;
     } else {
       __syncthreads();
@@ -825,29 +852,13 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
 
 int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
 
-// Workgroups per feature tile of a launch of one-wave tiles with K split over KS waves that runs the pass at x
-// or the candidates alone: as many as bring the launch to about one workgroup per compute unit, while every
-// wave keeps at least two chunks.
-inline int slices_for(const LayerArgs& a, int KS) {
-  if (KS <= 1 || a.slice_partials == nullptr || a.slice_counters == nullptr) return 1;
-  if ((a.has_base != 0) == (a.n_cand > 0)) return 1;   // both jobs in one launch (or none)
-  const LayerJob& j = a.has_base ? a.bj : a.cj;
-  const long long groups = (long long)job_tiles(j, 32) * (a.has_base ? 1 : a.n_cand);
-  const int n_chunks = j.Kp >> 6;
-  long long s = 256 / (groups > 0 ? groups : 1);
-  if (s > n_chunks / (2 * KS)) s = n_chunks / (2 * KS);
-  if (s > 8) s = 8;
-  while (s > 1 && groups * s > kMaxBaseSliceGroups) --s;
-  return s < 1 ? 1 : (int)s;
-}
-
 template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1>
 hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
   constexpr int BN = 32 * NW;
   if (shape != nullptr) {
     shape->waves = NW;
     shape->k_split = KS;
-    shape->k_slices = KS > 1 ? slices_for(a, KS) : 1;
+    shape->k_slices = NW == 1 && a.k_slices > 1 ? a.k_slices : 1;
     shape->streaming = NT ? 1 : 0;
     shape->row_blocks = MB;
   }
@@ -858,8 +869,10 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)
                             : hipSuccess;
   if (attr_err != hipSuccess) return attr_err;
-  a.k_slices = KS > 1 ? slices_for(a, KS) : 1;
-  a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) * (a.n_cand > 0 ? 1 : a.k_slices) + 7) / 8 * 8 : 0;
+  // K slices (one-wave tiles only) come with the caller's plan; they need the partial and counter buffers
+  if (NW != 1 || a.k_slices < 1) a.k_slices = 1;
+  if (a.k_slices > 1 && (a.slice_partials == nullptr || a.slice_counters == nullptr)) return hipErrorInvalidValue;
+  a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) * a.k_slices + 7) / 8 * 8 : 0;
   int cand_blocks = 0;
   if (a.n_cand > 0) {
     const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
@@ -872,31 +885,45 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
 }
 
 // Workgroups of this instantiation that fit on one compute unit (cached).
-template <bool BF16, bool DELTA, int MB, int NW>
+template <bool BF16, bool DELTA, int MB, int NW, int KS>
 int wgs_per_cu_inst() {
   static const int cached = [] {
-    constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL;
+    constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL * KS;
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, false, 1>),
-                                                     64 * NW, lds_bytes) != hipSuccess || n < 1)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, false, KS>),
+                                                     64 * NW * KS, lds_bytes) != hipSuccess || n < 1)
       n = 1;
     return n;
   }();
   return cached;
 }
 
+// Waves that share one feature tile and split K: four, or two where four private LDS layouts do not
+// fit into the 160 KB of a compute unit (0: the layout is single-buffered or too large even twice).
 template <bool BF16, bool DELTA, int MB>
-int wgs_per_cu_nw(int NW) {
-  if (NW == 8) return wgs_per_cu_inst<BF16, DELTA, MB, 8>();
-  if (NW == 4) return wgs_per_cu_inst<BF16, DELTA, MB, 4>();
-  return wgs_per_cu_inst<BF16, DELTA, MB, 1>();
+constexpr int split_k_waves() {
+  using L = Lds<BF16, DELTA, MB, 1>;
+  if (!L::DBUF) return 0;
+  return L::TOTAL * 4 <= 160 * 1024 ? 4 : L::TOTAL * 2 <= 160 * 1024 ? 2 : 0;
+}
+
+// k_waves > 1: the one-wave-tile instantiation whose workgroups split K over that many waves
+template <bool BF16, bool DELTA, int MB>
+int wgs_per_cu_nw(int NW, int k_waves) {
+  if (NW == 8) return wgs_per_cu_inst<BF16, DELTA, MB, 8, 1>();
+  if (NW == 4) return wgs_per_cu_inst<BF16, DELTA, MB, 4, 1>();
+  constexpr int KS = split_k_waves<BF16, DELTA, MB>();
+  if constexpr (KS > 1) {
+    if (k_waves == KS) return wgs_per_cu_inst<BF16, DELTA, MB, 1, KS>();
+  }
+  return wgs_per_cu_inst<BF16, DELTA, MB, 1, 1>();
 }
 
 template <bool BF16, bool DELTA>
-int wgs_per_cu_mb(int MB, int NW) {
-  if (MB == 1) return wgs_per_cu_nw<BF16, DELTA, 1>(NW);
-  if (MB == 2) return wgs_per_cu_nw<BF16, DELTA, 2>(NW);
-  return wgs_per_cu_nw<BF16, DELTA, 4>(NW);
+int wgs_per_cu_mb(int MB, int NW, int k_waves) {
+  if (MB == 1) return wgs_per_cu_nw<BF16, DELTA, 1>(NW, k_waves);
+  if (MB == 2) return wgs_per_cu_nw<BF16, DELTA, 2>(NW, k_waves);
+  return wgs_per_cu_nw<BF16, DELTA, 4>(NW, k_waves);
 }
 
 // Streaming loads are used when every row segment a load instruction covers
@@ -910,26 +937,26 @@ bool launch_lines_aligned(const LayerArgs& a) {
   return ok;
 }
 
-// Waves that share one feature tile and split K: four, or two where four private LDS layouts do not
-// fit into the 160 KB of a compute unit (0: the layout is single-buffered or too large even twice).
-template <bool BF16, bool DELTA, int MB>
-constexpr int split_k_waves() {
-  using L = Lds<BF16, DELTA, MB, 1>;
-  if (!L::DBUF) return 0;
-  return L::TOTAL * 4 <= 160 * 1024 ? 4 : L::TOTAL * 2 <= 160 * 1024 ? 2 : 0;
-}
-
 template <bool BF16, bool DELTA, int MB, int NW>
 hipError_t launch_nt(const LayerArgs& a, hipStream_t stream, LaunchShape* shape) {
-  // One-tile workgroups and every K of the launch long enough to split
+  // One-tile workgroups whose plan splits K over the waves of a workgroup (every K of the launch gives each
+  // wave at least two chunks: the planner's condition, checked again because a wave without chunks would
+  // start a copy beyond the operand)
   constexpr int KS = split_k_waves<BF16, DELTA, MB>();
-  if constexpr (NW == 1 && KS > 0) {
-    const bool base_ok = !a.has_base || (a.bj.Kp >> 6) >= 2 * KS;
-    const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * KS;
-    if ((a.has_base || a.n_cand > 0) && base_ok && cand_ok) {
+  if constexpr (NW == 1 && KS > 1) {
+    if (a.k_waves == KS) {
+      const int slices = a.k_slices > 1 ? a.k_slices : 1;
+      const bool base_ok = !a.has_base || (a.bj.Kp >> 6) >= 2 * KS * slices;
+      const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * KS * slices;
+      if (!((a.has_base || a.n_cand > 0) && base_ok && cand_ok)) return hipErrorInvalidValue;
       if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, KS>(a, stream, shape);
       return launch_inst<BF16, DELTA, MB, NW, false, KS>(a, stream, shape);
     }
+  }
+  if (NW == 1 && a.k_slices > 1) {
+    const bool base_ok = !a.has_base || (a.bj.Kp >> 6) >= 2 * a.k_slices;
+    const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * a.k_slices;
+    if (!(base_ok && cand_ok)) return hipErrorInvalidValue;
   }
   if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream, shape);
   return launch_inst<BF16, DELTA, MB, NW, false>(a, stream, shape);
@@ -978,7 +1005,9 @@ int launch_nw_for(const LayerArgs& a) {
                                  LaunchShape* shape) {                                            \
     return launch_mb<BF16, DELTA>(a, MB, NW, stream, shape);                                      \
   }                                                                                               \
-  int wgs_per_cu_##NAME(int MB, int NW) { return wgs_per_cu_mb<BF16, DELTA>(MB, NW); }            \
+  int wgs_per_cu_##NAME(int MB, int NW, int k_waves) {                                            \
+    return wgs_per_cu_mb<BF16, DELTA>(MB, NW, k_waves);                                           \
+  }                                                                                               \
   int ks_waves_##NAME(int MB) {                                                                   \
     return MB == 1 ? split_k_waves<BF16, DELTA, 1>() : MB == 2 ? split_k_waves<BF16, DELTA, 2>()  \
                                                                : split_k_waves<BF16, DELTA, 4>(); \
