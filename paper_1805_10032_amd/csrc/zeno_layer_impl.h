@@ -217,6 +217,55 @@ __device__ inline void stage_tile(const f32x4 (&u)[8], unsigned char* st, int la
   }
 }
 
+// Tiles of the shifted column grid (see RING below) whose first or last columns fall outside the row: the
+// lanes there read the row's first element instead (in bounds) and deliver zeros.  kfirst is the column of
+// the tile's first element, K a multiple of 4 like kfirst, so a lane's four columns are all inside or all outside.
+template <int MODE, bool NT>
+__device__ inline void load_tile_edge(f32x4 (&u)[8], const float* __restrict__ Urow0, int kfirst, int row0, int N, int K,
+                                      int lane) {
+  const int rsub = lane >> 4, k = kfirst + ((lane & 15) << 2);
+  const bool ok = k >= 0 && k < K;
+  const int kk = ok ? k : 0;
+  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int row = row0 + 4 * j + rsub;
+    const int rel = ((MODE == 2 && row >= N) ? N - 1 : row) - row0;
+    const float* p = Urow0 + (long long)rel * K + kk;
+    f32x4 v;
+    if (NT) {
+      v = load_stream4(p);
+    } else {
+      v = *reinterpret_cast<const f32x4_a4*>(p);
+    }
+    u[j] = ok ? v : zero;
+  }
+}
+
+// Staging ring of the shifted column grid (bf16): two staging tiles of the ordinary layout, the first for
+// the columns whose bit 6 is clear, the second for the others.  A tile of the shifted grid starts sigma
+// columns before a multiple of 64, so its first sigma columns go to one half and the rest to the other.
+// ring_w[i]: the lane's byte offset for row 4 i + lane / 16 of an EVEN tile; an odd tile flips the half.
+__device__ inline void ring_offsets(unsigned (&ring_w)[8], int lane, int sigma) {
+  const int rsub = lane >> 4, kq = lane & 15;
+  const int col = (4 * kq - sigma) & 63;            // column inside its block of 64
+  const int kp = col >> 2;
+  const unsigned half = 4 * kq < sigma ? 4096u : 0u;   // columns before the tile's own block of 64
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = 4 * i + rsub;
+    ring_w[i] = half + r * 128 + ((((kp >> 1) ^ (r >> 1)) & 7) << 4) + ((kp & 1) << 3);
+  }
+}
+template <bool ODD>
+__device__ inline void stage_ring(const f32x4 (&u)[8], unsigned char* st, const unsigned (&ring_w)[8]) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const bf16x4 h = __builtin_convertvector(u[i], bf16x4);
+    *reinterpret_cast<bf16x4*>(st + (ring_w[i] ^ (ODD ? 4096u : 0u))) = h;
+  }
+}
+
 // s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding: vmcnt in
 // bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
 template <int N>
@@ -250,12 +299,12 @@ __device__ inline void lds_dma16(const unsigned char* src, unsigned char* dst) {
 // LDS layout of a workgroup: [activation chunk buffers (one or two)] [one staging
 // tile per wave].  (Nothing else: with 4 row blocks, bf16 operands, the second product and
 // four waves the layout is exactly 80 KB, and two such workgroups share a compute unit.)
-template <bool BF16, bool DELTA, int MB, int NW>
+template <bool BF16, bool DELTA, int MB, int NW, bool RING = false>
 struct Lds {
   using T = Tr<BF16>;
   static constexpr int A_BYTES = MB * T::CH_BYTES;            // one operand, one chunk
   static constexpr int AD_BYTES = A_BYTES * (DELTA ? 2 : 1);  // H (and D), one chunk
-  static constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE;
+  static constexpr int STAGE_BYTES = 32 * 64 * T::ESIZE * (RING ? 2 : 1);   // RING: two tiles' worth of columns
   static constexpr bool DBUF = 2 * AD_BYTES + NW * STAGE_BYTES <= 128 * 1024;
   static constexpr int STAGE_OFF = AD_BYTES * (DBUF ? 2 : 1);
   static constexpr int TOTAL = STAGE_OFF + NW * STAGE_BYTES;
@@ -269,11 +318,21 @@ struct Lds {
 // layer (ten classes) only one tile per candidate: far too few single waves to keep
 // enough loads in flight, and each of them would walk all of K alone, one chunk's
 // latency after the other.  This multiplies the waves by KS and divides the walk.
-template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS>
+//
+// RING (bf16 operands, NW > 1): the shifted column grid for rows that do not start on 128-byte lines (a dense
+// G[m x d]).  With K a multiple of 64 and 16-byte aligned rows every row of a wave's tile starts the same
+// sigma columns (a multiple of 4) past a line.  A 64-column tile that starts at column 64 j would then cover
+// three lines per row and share the outer two with its neighbours: they would come from memory twice.  Here
+// tile j starts at column 64 j - sigma instead, on a line, so that every line is requested once (and can be
+// streamed); the tiles are staged into a ring of 128 columns at (column mod 128), one tile ahead of the
+// products, which read their 64 columns at the unshifted positions.  Nothing else knows of the shift.  The
+// first tile's columns before the row and the last (extra) tile's columns behind it are masked.
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS, bool RING = false>
 __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) {
   static_assert(KS == 1 || NW == 1, "K is only split in one-tile workgroups");
   using T = Tr<BF16>;
-  using LD = Lds<BF16, DELTA, MB, NW>;
+  using LD = Lds<BF16, DELTA, MB, NW, RING>;
+  static_assert(!RING || (BF16 && KS == 1 && NW > 1 && LD::DBUF), "the shifted grid exists for wide bf16 workgroups with double buffers");
   static_assert(KS == 1 || LD::DBUF, "the single-buffer loop has workgroup barriers, which waves with different K ranges cannot share");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
   constexpr int BN = 32 * NW;
@@ -335,6 +394,11 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   const float* __restrict__ Urow0 = P + J.w_off + (long long)row0 * K;  // wave-uniform
   const unsigned lane_off = (unsigned)(lane >> 4) * (unsigned)K + ((lane & 15) << 2);
   const bool full_rows = row0 + 32 <= N;
+  // RING: columns between the line a row starts in and the row's first element (the same for all rows of the tile)
+  const int sigma = RING ? __builtin_amdgcn_readfirstlane((int)((reinterpret_cast<uintptr_t>(Urow0) & 127) >> 2)) : 0;
+  const float* __restrict__ Uring = Urow0 - sigma;   // tile j of the shifted grid starts at Uring + 64 j
+  unsigned ring_w[8];
+  if constexpr (RING) ring_offsets(ring_w, lane, sigma);
 
   const unsigned char* Ag = reinterpret_cast<const unsigned char*>(J.A_base);
   // The pass at x has no second product: its D operand is a harmless alias of H
@@ -407,6 +471,38 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       w[r] = *reinterpret_cast<const f32x4*>(Wt_wave + ((long long)c * WREGS + r) * 1024);
   };
 
+  // A weight tile that has arrived in registers: rows beyond the matrix are discarded, its share of
+  // ||u||^2 is taken, and it is converted and staged (RING: as an even or odd tile of the shifted grid).
+  auto take_tile = [&](auto full_c, auto odd_c, f32x4 (&u)[8]) __attribute__((always_inline)) {
+    constexpr int MODE = decltype(full_c)::value;
+    if (MODE == 2) {
+      // rows beyond the matrix were read from row N-1: discard them
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) u[i] = (row0 + 4 * i + (lane >> 4) < N) ? u[i] : zero;
+    }
+    if (do_norm) {
+      float q = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) q += (u[i][0] * u[i][0] + u[i][1] * u[i][1]) + (u[i][2] * u[i][2] + u[i][3] * u[i][3]);
+      nrm += (double)q;
+    }
+    if constexpr (RING) {
+      stage_ring<decltype(odd_c)::value>(u, stU, ring_w);
+    } else {
+      stage_tile<BF16>(u, stU, lane);
+    }
+  };
+  // Tile j of the shifted grid (RING), j >= 1: the last one (j == n_chunks) lies partly behind the row.
+  auto load_ring = [&](auto full_c, f32x4 (&u)[8], int j) __attribute__((always_inline)) {
+    constexpr int MODE = decltype(full_c)::value;
+    if (j < n_chunks) {
+      load_tile<MODE, NT>(u, Uring + (j << 6), lane_off, row0, j << 6, N, K, lane);
+    } else {
+      load_tile_edge<MODE, NT>(u, Urow0, 64 * j - sigma, row0, N, K, lane);
+    }
+  };
+
   // One K chunk.  Its weight tile sits in registers u (loaded two chunks ago); its
   // activation operands were copied into LDS buffer c&1 during the previous chunk.
   // Issue order per chunk: copies(c+1), U(c+2), [matrix products of c], W(c+2).
@@ -415,27 +511,18 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // derives its wait counts from the worst path through the loop, and a path on
   // which the later tile was NOT requested makes it wait for all loads at the top
   // of every chunk, i.e. no tile would stay in flight across a chunk.
-  auto chunk = [&](auto full_c, auto base_c, auto steady_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c)
+  // odd_c (RING only): the parity of c, which selects the half of the staging ring at compile time.
+  auto chunk = [&](auto full_c, auto base_c, auto steady_c, auto odd_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c)
                    __attribute__((always_inline)) {
+    constexpr bool ODD = decltype(odd_c)::value;
     constexpr int MODE = decltype(full_c)::value;
     constexpr bool FULL = MODE != 0;
     constexpr bool BASE = decltype(base_c)::value;   // this workgroup runs the pass at x
     constexpr bool STEADY = decltype(steady_c)::value;
     constexpr bool SECOND = DELTA && !BASE;           // second product D W^T present
     const int buf = DBUF ? (c & 1) : 0;
-    if (MODE == 2) {
-      // rows beyond the matrix were read from row N-1: discard them
-      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int j = 0; j < 8; ++j) u[j] = (row0 + 4 * j + (lane >> 4) < N) ? u[j] : zero;
-    }
-    if (do_norm) {
-      float q = 0.f;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) q += (u[j][0] * u[j][0] + u[j][1] * u[j][1]) + (u[j][2] * u[j][2] + u[j][3] * u[j][3]);
-      nrm += (double)q;
-    }
-    stage_tile<BF16>(u, stU, lane);
+    // RING: u holds tile c + 1 of the shifted grid, staged one chunk ahead of the products
+    take_tile(full_c, std::integral_constant<bool, !ODD>{}, u);
     if (DBUF) {
       // copies(c) were issued before U(c+1) [8 loads] and W(c+1) [WREGS loads]; the
       // last chunk has no such loads behind its copies and waits for everything
@@ -465,7 +552,12 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       wait_vmcnt<0>();
       __syncthreads();
     }
-    if (STEADY || c + 2 < c_end) load_tile<MODE, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
+    if constexpr (RING) {
+      if (STEADY) load_tile<MODE, NT>(u, Uring + ((c + 3) << 6), lane_off, row0, (c + 3) << 6, N, K, lane);
+      else if (c + 3 <= n_chunks) load_ring(full_c, u, c + 3);
+    } else {
+      if (STEADY || c + 2 < c_end) load_tile<MODE, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
+    }
 
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(1);
@@ -485,6 +577,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
         fr[mb] = *reinterpret_cast<const f32x4*>((op ? bufD : bufA) + ((mb * KSTEPS + t) * 64 + lane) * 16);
     };
     auto read_b = [&](int t) __attribute__((always_inline)) {
+      if (RING) return *reinterpret_cast<const f32x4*>(stU + (ODD ? 4096 : 0) + n * 128 + ((((2 * t + h) ^ (n >> 1)) & 7) << 4));
       if (BF16) return *reinterpret_cast<const f32x4*>(stU + n * 128 + ((((2 * t + h) ^ (n >> 1)) & 7) << 4));
       return *reinterpret_cast<const f32x4*>(stU + n * 256 + ((((2 * t + h) ^ n) & 15) << 4));
     };
@@ -533,6 +626,26 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     __builtin_amdgcn_sched_barrier(0);
     int c = c_begin;
     const float* Ufirst = Urow0 + (c_begin << 6);
+    if constexpr (RING) {
+      // tiles 0 and 1 of the shifted grid; tile 0 is staged here, every chunk then stages the tile after its own
+      load_tile_edge<MODE, NT>(u0, Urow0, -sigma, row0, N, K, lane);
+      load_ring(full_c, u1, 1);
+      if (SECOND) {
+        load_W(w0, 0);
+        if (1 < c_end) load_W(w1, 1);
+      }
+      take_tile(full_c, std::false_type{}, u0);
+      if (2 <= n_chunks) load_ring(full_c, u0, 2);
+      // steady state: chunks whose tile three ahead lies fully inside the rows (c is even here)
+      for (; c + 4 < c_end; c += 2) {
+        chunk(full_c, base_c, std::true_type{}, std::false_type{}, u1, w0, c);
+        chunk(full_c, base_c, std::true_type{}, std::true_type{}, u0, w1, c + 1);
+      }
+      for (; c < c_end; c += 2) {
+        chunk(full_c, base_c, std::false_type{}, std::false_type{}, u1, w0, c);
+        if (c + 1 < c_end) chunk(full_c, base_c, std::false_type{}, std::true_type{}, u0, w1, c + 1);
+      }
+    } else {
     if (FULL && DBUF && c_end - c_begin >= 4) {
       // steady state: pairs of chunks whose loads (two chunks ahead) all exist
       load_tile<MODE, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
@@ -542,8 +655,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
         load_W(w1, c_begin + 1);
       }
       for (; c + 3 < c_end; c += 2) {
-        chunk(full_c, base_c, std::true_type{}, u0, w0, c);
-        chunk(full_c, base_c, std::true_type{}, u1, w1, c + 1);
+        chunk(full_c, base_c, std::true_type{}, std::false_type{}, u0, w0, c);
+        chunk(full_c, base_c, std::true_type{}, std::false_type{}, u1, w1, c + 1);
       }
     } else {
       if (c_begin < c_end) load_tile<MODE, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
@@ -555,21 +668,22 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     }
     // the last two or three chunks (all of them for a short K): every load is conditional
     for (; c < c_end; c += 2) {
-      chunk(full_c, base_c, std::false_type{}, u0, w0, c);
-      if (c + 1 < c_end) chunk(full_c, base_c, std::false_type{}, u1, w1, c + 1);
+      chunk(full_c, base_c, std::false_type{}, std::false_type{}, u0, w0, c);
+      if (c + 1 < c_end) chunk(full_c, base_c, std::false_type{}, std::false_type{}, u1, w1, c + 1);
     }
     if (KS > 1) wait_vmcnt<0>();  // a wave with an empty K range still has its first copy in flight
+    }
   };
   using M0 = std::integral_constant<int, 0>;
   using M1 = std::integral_constant<int, 1>;
   using M2 = std::integral_constant<int, 2>;
   if (is_base) {
     if (all_full && full_rows) run(M1{}, std::true_type{});
-    else if (all_full) run(M2{}, std::true_type{});
+    else if (all_full || RING) run(M2{}, std::true_type{});   // the shifted grid is only launched for K a multiple of 64
     else run(M0{}, std::true_type{});
   } else {
     if (all_full && full_rows) run(M1{}, std::false_type{});
-    else if (all_full) run(M2{}, std::false_type{});
+    else if (all_full || RING) run(M2{}, std::false_type{});
     else run(M0{}, std::false_type{});
   }
 
@@ -852,20 +966,20 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
 
 int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
 
-template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1>
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1, bool RING = false>
 hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
   constexpr int BN = 32 * NW;
   if (shape != nullptr) {
     shape->waves = NW;
     shape->k_split = KS;
     shape->k_slices = NW == 1 && a.k_slices > 1 ? a.k_slices : 1;
-    shape->streaming = NT ? 1 : 0;
+    shape->streaming = RING ? 2 : NT ? 1 : 0;
     shape->row_blocks = MB;
   }
-  constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW>::TOTAL * KS;
+  constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW, RING>::TOTAL * KS;
   // once per process and instantiation (initialisation of a local static is thread-safe)
   static const hipError_t attr_err =
-      lds_bytes > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT, KS>),
+      lds_bytes > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT, KS, RING>),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)
                             : hipSuccess;
   if (attr_err != hipSuccess) return attr_err;
@@ -879,7 +993,7 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
     const int units = job_tiles(a.cj, BN) * ((a.n_cand + cc - 1) / cc);
     cand_blocks = ((units + 7) / 8) * 8 * cc * a.k_slices;
   }
-  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW, NT, KS>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW * KS),
+  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW, NT, KS, RING>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW * KS),
                      lds_bytes, stream, a);
   return hipGetLastError();
 }
@@ -937,6 +1051,16 @@ bool launch_lines_aligned(const LayerArgs& a) {
   return ok;
 }
 
+// The shifted column grid serves rows that start 16-byte aligned but not on a line, all of them the same
+// distance past one: row lengths that are multiples of 64 columns, 16-byte aligned bases, pitches and blocks.
+bool job_ring_ok(const LayerJob& j) { return j.w_off % 4 == 0 && j.K % 64 == 0; }
+bool launch_ring_ok(const LayerArgs& a) {
+  bool ok = a.has_base || a.n_cand > 0;
+  if (a.n_cand > 0) ok = ok && reinterpret_cast<uintptr_t>(a.G) % 16 == 0 && a.ldg % 4 == 0 && job_ring_ok(a.cj);
+  if (a.has_base) ok = ok && reinterpret_cast<uintptr_t>(a.x) % 16 == 0 && job_ring_ok(a.bj);
+  return ok;
+}
+
 template <bool BF16, bool DELTA, int MB, int NW>
 hipError_t launch_nt(const LayerArgs& a, hipStream_t stream, LaunchShape* shape) {
   // One-tile workgroups whose plan splits K over the waves of a workgroup (every K of the launch gives each
@@ -959,6 +1083,9 @@ hipError_t launch_nt(const LayerArgs& a, hipStream_t stream, LaunchShape* shape)
     if (!(base_ok && cand_ok)) return hipErrorInvalidValue;
   }
   if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream, shape);
+  if constexpr (BF16 && NW > 1 && Lds<BF16, DELTA, MB, NW, true>::DBUF) {
+    if (launch_ring_ok(a)) return launch_inst<BF16, DELTA, MB, NW, true, 1, true>(a, stream, shape);
+  }
   return launch_inst<BF16, DELTA, MB, NW, false>(a, stream, shape);
 }
 

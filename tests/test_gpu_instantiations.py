@@ -1,8 +1,8 @@
 """Every instantiation of the streaming layer kernel that a caller can reach at scale is executed
 here at sizes the float64 oracle scores in seconds, ALL rows compared: four- and eight-wave
 workgroups in fp32 and bf16, with and without the second matrix product, one, two and four
-32-sample row blocks, densely packed rows (plain loads) and rows on 128-byte lines (streaming
-loads), ragged widths, and the pass at x riding in an eight-wave candidate launch.  Which launch
+32-sample row blocks, densely packed rows (plain loads, or the shifted column grid where rows are
+16-byte aligned) and rows on 128-byte lines (streaming loads), ragged widths, and the pass at x riding in an eight-wave candidate launch.  Which launch
 shapes really ran is read back from the library's per-launch records and asserted, so the
 coverage cannot silently move when the dispatch heuristics change."""
 import numpy as np
@@ -39,10 +39,17 @@ def _workload(key, dims, m, b, n_r, fwd, n_flip, n_noise):
     return _CACHE[key]
 
 
-def _run(B, w, s_ref, s_exact, scale, row_align):
+def _run(B, w, s_ref, s_exact, scale, row_align, offset_floats=0):
     dev = torch.device("cuda", 0)
     mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
-    G = rows_to_gpu(B, w.G, row_align, dev)
+    if offset_floats:
+        # densely packed rows that start offset_floats past the start of an allocation
+        m, d = w.G.shape
+        buf = torch.empty(m * d + offset_floats, dtype=torch.float32, device=dev)
+        G = buf[offset_floats:].view(m, d)
+        G.copy_(w.G)
+    else:
+        G = rows_to_gpu(B, w.G, row_align, dev)
     B.profile_enable(True)
     try:
         s = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
@@ -89,6 +96,37 @@ def test_wide_layers_all_rows(B, fwd, n_r, row_align):
     assert all(s[3] >= 4 for s in cand if s[1] < 2), cand                       # the wide layers run in wide workgroups
 
 
+# d mod 4 = 0 and widths that are multiples of 64: densely packed rows are 16-byte aligned and start
+# 0, 48, 96, 16, ... bytes past a 128-byte line, the case of the shifted column grid
+SHIFTED = [1024, 2048, 1024, 12]
+
+
+@pytest.mark.parametrize("offset_floats", [0, 4])
+@pytest.mark.parametrize("n_r", [32, 64, 128])
+def test_dense_rows_on_the_shifted_grid(B, n_r, offset_floats):
+    """bf16 forward on a dense G[m x d] whose rows are 16-byte aligned but not line-aligned: the wide layers
+    load their weight tiles on a column grid shifted to the lines of each candidate's rows (launch
+    records say streaming = 2), all rows compared.  With the whole matrix 16 bytes past the start of
+    its allocation the first candidate's rows are shifted too, and the columns in front of its first
+    row, which lie before the matrix, must not be read."""
+    assert WL.num_params(SHIFTED, True) % 4 == 0 and (4 * WL.num_params(SHIFTED, True)) % 128 not in (0, 64)
+    w, s_ref, s_exact, scale = _workload(("shifted", n_r), SHIFTED, 64, 20, n_r, "bf16", 12, 8)
+    shapes = _run(B, w, s_ref, s_exact, scale, 1, offset_floats)
+    print(f"\n  shifted grid n_r={n_r} offset={offset_floats}: {shapes}")
+    cand = [s for s in shapes if s[0] == "layer_cand" and s[3] >= 4]
+    assert cand and all(s[5] == 2 for s in cand), shapes
+
+
+def test_pass_at_x_rides_in_a_launch_on_the_shifted_grid(B):
+    """The merged launch of the test below with dense, 16-byte aligned rows: the pass at x (its own
+    parameter vector is line-aligned, shift 0) and the candidates (shifted) share a launch."""
+    w, s_ref, s_exact, scale = _workload(("merge8s",), [1024, 2048, 2048, 12], 60, 20, 64, "bf16", 12, 8)
+    shapes = _run(B, w, s_ref, s_exact, scale, 1)
+    print(f"\n  merge8 on the shifted grid: {shapes}")
+    merged = [s for s in shapes if s[0] == "layer_cand" and s[7] == 1]
+    assert any(s[3] == 8 and s[5] == 2 for s in merged), shapes
+
+
 @pytest.mark.parametrize("row_align", [1, 32])
 @pytest.mark.parametrize("fwd", ["fp32", "bf16"])
 def test_ragged_widths_in_wide_workgroups(B, fwd, row_align):
@@ -133,6 +171,10 @@ def test_zz_which_instantiations_ran(B):
                     missing.append((fwd, second, waves))
         if not any(s[0] == fwd and s[3] > 1 for s in SEEN):
             missing.append((fwd, "k_split"))
+    for second in (0, 1):      # the shifted column grid (bf16 only)
+        for mb in (1, 2, 4):
+            if not any(s[0] == "bf16" and s[1] == second and s[2] in (4, 8) and s[4] == 2 and s[5] == mb for s in SEEN):
+                missing.append(("bf16", second, "4|8 waves", "shifted grid", mb))
     print("\n  launch shapes seen:", sorted(SEEN))
     assert not missing, missing
 
