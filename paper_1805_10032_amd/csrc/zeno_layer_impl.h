@@ -218,14 +218,15 @@ __device__ inline void stage_tile(const f32x4 (&u)[8], unsigned char* st, int la
 }
 
 // Tiles of the shifted column grid (see RING below) whose first or last columns fall outside the row: the
-// lanes there read the row's first element instead (in bounds) and deliver zeros.  kfirst is the column of
-// the tile's first element, K a multiple of 4 like kfirst, so a lane's four columns are all inside or all outside.
+// lanes there read the row's first or last four elements instead (in bounds, and in a line that the tile's
+// valid columns need anyway) and deliver zeros.  kfirst is the column of the tile's first element, K a
+// multiple of 4 like kfirst, so a lane's four columns are all inside or all outside.
 template <int MODE, bool NT>
 __device__ inline void load_tile_edge(f32x4 (&u)[8], const float* __restrict__ Urow0, int kfirst, int row0, int N, int K,
                                       int lane) {
   const int rsub = lane >> 4, k = kfirst + ((lane & 15) << 2);
   const bool ok = k >= 0 && k < K;
-  const int kk = ok ? k : 0;
+  const int kk = k < 0 ? 0 : (k < K ? k : K - 4);
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -259,10 +260,14 @@ __device__ inline void ring_offsets(unsigned (&ring_w)[8], int lane, int sigma) 
 }
 template <bool ODD>
 __device__ inline void stage_ring(const f32x4 (&u)[8], unsigned char* st, const unsigned (&ring_w)[8]) {
+  // the flip is hidden from the optimiser, which would otherwise keep both sets of eight offsets in
+  // registers (the kernel has none to spare) instead of one set and eight exclusive-ors per tile
+  unsigned flip = ODD ? 4096u : 0u;
+  asm volatile("" : "+s"(flip));
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const bf16x4 h = __builtin_convertvector(u[i], bf16x4);
-    *reinterpret_cast<bf16x4*>(st + (ring_w[i] ^ (ODD ? 4096u : 0u))) = h;
+    *reinterpret_cast<bf16x4*>(st + (ring_w[i] ^ flip)) = h;
   }
 }
 
@@ -498,8 +503,13 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     constexpr int MODE = decltype(full_c)::value;
     if (j < n_chunks) {
       load_tile<MODE, NT>(u, Uring + (j << 6), lane_off, row0, j << 6, N, K, lane);
-    } else {
+    } else if (sigma > 0) {
       load_tile_edge<MODE, NT>(u, Urow0, 64 * j - sigma, row0, N, K, lane);
+    } else {
+      // rows that start on a line: the grid is not shifted and there is no tile behind the last chunk
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) u[i] = zero;
     }
   };
 
