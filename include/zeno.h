@@ -34,6 +34,10 @@
  *   instruction, the rows are streamed with loads that bypass cache retention,
  *   and the rows of different candidates start on different halves of a 256-byte
  *   span (an even multiple measures about 2 % slower on multi-gigabyte G).
+ *   A densely packed G whose rows are 16-byte aligned (G 16-byte aligned, d a
+ *   multiple of 4) comes within 4 % of that in zeno_score with the bf16 forward
+ *   pass on layers whose input width is a multiple of 64: their weight tiles
+ *   are loaded on a column grid shifted to the lines of each candidate's rows.
  * Errors.  Every call returns a zeno_status_t; nothing is thrown across the
  *   ABI.  Argument errors are detected on the host before anything is
  *   enqueued, so a failed call leaves the outputs untouched.
@@ -268,7 +272,9 @@ typedef struct {
   /* layer kernels only (else 0): the launch shape that ran */
   int32_t waves;      /* waves per workgroup that own different 32-feature tiles: 1, 4 or 8 */
   int32_t k_split;    /* waves that share one feature tile and split the input width: 1, 2 or 4 */
-  int32_t streaming;  /* 1: rows read with non-temporal loads (line-aligned layout), 0: plain loads */
+  int32_t streaming;  /* 1: rows read with non-temporal loads (line-aligned layout), 0: plain loads,
+                         2: non-temporal loads on a column grid shifted to the lines of each candidate's rows
+                            (16-byte aligned dense rows, bf16 forward) */
   int32_t row_blocks; /* 32-sample accumulator blocks per wave: 1, 2 or 4 */
   int32_t merged;     /* 1: the launch carries the candidates' layer AND the pass at x through another layer */
   int32_t second;     /* 1: candidates with the second matrix product (layers after the first) */

@@ -118,7 +118,7 @@ struct LaunchShape {
   int waves;       // waves per workgroup that own different feature tiles (1, 4 or 8)
   int k_split;     // waves that share one feature tile and split K (1, 2 or 4)
   int k_slices;    // workgroups that share one feature tile and split K (1 to 8)
-  int streaming;   // 1: rows read with non-temporal loads (line-aligned layout)
+  int streaming;   // 1: rows read with non-temporal loads (line-aligned layout), 2: the same on the shifted column grid
   int row_blocks;  // 32-sample accumulator blocks per wave (1, 2 or 4)
 };
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream,
