@@ -278,7 +278,7 @@ typedef struct {
   int32_t row_blocks; /* 32-sample accumulator blocks per wave: 1, 2 or 4 */
   int32_t merged;     /* 1: the launch carries the candidates' layer AND the pass at x through another layer */
   int32_t second;     /* 1: candidates with the second matrix product (layers after the first) */
-  int32_t k_slices;   /* workgroups that share one feature tile and split the input width (pass at x on its own): 1..8 */
+  int32_t k_slices;   /* workgroups that share one feature tile and split the input width (launches of one-wave tiles): 1..8 */
 } zeno_profile_record_t;
 
 zeno_status_t zeno_profile_enable(int32_t enable);
