@@ -91,7 +91,9 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
       p.sz_wt[l] = (size_t)p.wt_rows[l] * pad64(D.dims[l]) * p.esize;
       p.off_wt[l] = take(p.sz_wt[l]);
     }
-    p.P += norm_slots_bound(N, m, p.MB);   // upper bound on the partial-norm slots of this layer
+    // upper bound on the partial-norm slots of this layer: one launch over all candidates, or two launches
+    // (the second with few candidates, whose tiles may then split K more widely) with a range of slots each
+    p.P += norm_slots_bound(N, m, p.MB) + norm_slots_bound(N, 1, p.MB);
   }
   p.n_counters = kMaxSliceGroups;
   p.sz_slice_part = kSlicePartialBytes;
@@ -142,11 +144,12 @@ struct ProfScope {
     e.rec.ms = 0.f;
     e.rec.algorithmic_bytes = bytes;
     e.rec.waves = e.rec.k_split = e.rec.streaming = e.rec.row_blocks = e.rec.merged = e.rec.second = e.rec.k_slices = 0;
+    e.rec.first_candidate = e.rec.candidates = 0;
     (void)hipEventRecord(e.start, stream);
     g_prof.push_back(e);
     slot = (int)g_prof.size() - 1;
   }
-  void set_shape(const LaunchShape& s, bool merged, bool second) {
+  void set_shape(const LaunchShape& s, bool merged, bool second, int first_candidate, int candidates) {
     if (slot < 0) return;
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     if (slot >= (int)g_prof.size()) return;
@@ -158,6 +161,8 @@ struct ProfScope {
     r.merged = merged ? 1 : 0;
     r.second = second ? 1 : 0;
     r.k_slices = s.k_slices;
+    r.first_candidate = first_candidate;
+    r.candidates = candidates;
   }
   ~ProfScope() {
     if (slot < 0) return;
@@ -268,36 +273,53 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
       c.a.bj = make_job(0);
       c.base_layer = 0;
       c.bytes += layer_bytes(0);
-    } else {
-      c.a.D_cand = l == 0 ? nullptr : ws + p.off_dc[(l - 1) & 1];
-      c.a.A_stride = (long long)p.cand_stride;
-      c.a.Dl_cand = ws + p.off_dc[l & 1];
-      c.a.H_stride = (long long)p.cand_stride;
-      if (l + 1 < L) {
-        c.a.has_base = 1;
-        c.a.bj = make_job(l + 1);
-        if (!query_device || layer_merge_pays(c.a, bf16, l > 0, p.MB)) {
-          c.bytes += layer_bytes(l + 1);
-          c.wt_layer = l + 1;
-          c.base_layer = l + 1;
-        } else {
-          // the extra workgroups would cost a whole extra round: run the pass at x on its own first
-          Launch b;
-          b.a = common;
-          b.a.has_base = 1;
-          b.a.bj = c.a.bj;
-          b.delta = false;
-          b.kernel = ZENO_KERNEL_LAYER_BASE;
-          b.layer = l + 1;
-          b.bytes = layer_bytes(l + 1);
-          b.wt_layer = l + 1;
-          b.base_layer = l + 1;
-          seq.push_back(b);
-          c.a.has_base = 0;
-        }
+      seq.push_back(c);
+      continue;
+    }
+    c.a.D_cand = l == 0 ? nullptr : ws + p.off_dc[(l - 1) & 1];
+    c.a.A_stride = (long long)p.cand_stride;
+    c.a.Dl_cand = ws + p.off_dc[l & 1];
+    c.a.H_stride = (long long)p.cand_stride;
+    if (l + 1 < L) {
+      c.a.has_base = 1;
+      c.a.bj = make_job(l + 1);
+    }
+    // A launch whose last round of eight-wave workgroups would be mostly empty is cut in two: the candidates
+    // that fill whole rounds, then the few others as one-wave tiles (which also carry the pass at x).
+    const int n_main = query_device ? layer_split_point(c.a, bf16, l > 0, p.MB) : m;
+    Launch rest = c;
+    if (n_main < m) {
+      c.a.n_cand = n_main;
+      c.a.has_base = 0;
+      c.bytes = layer_bytes(l) * n_main;
+      rest.a.cand0 = n_main;
+      rest.a.n_cand = m - n_main;
+      rest.bytes = layer_bytes(l) * (m - n_main);
+    }
+    Launch& carrier = n_main < m ? rest : c;   // the launch that may carry the pass at x through layer l + 1
+    if (l + 1 < L) {
+      if (!query_device || layer_merge_pays(carrier.a, bf16, l > 0, p.MB)) {
+        carrier.bytes += layer_bytes(l + 1);
+        carrier.wt_layer = l + 1;
+        carrier.base_layer = l + 1;
+      } else {
+        // the extra workgroups would cost a whole extra round: run the pass at x on its own first
+        Launch b;
+        b.a = common;
+        b.a.has_base = 1;
+        b.a.bj = carrier.a.bj;
+        b.delta = false;
+        b.kernel = ZENO_KERNEL_LAYER_BASE;
+        b.layer = l + 1;
+        b.bytes = layer_bytes(l + 1);
+        b.wt_layer = l + 1;
+        b.base_layer = l + 1;
+        seq.push_back(b);
+        carrier.a.has_base = 0;
       }
     }
     seq.push_back(c);
+    if (n_main < m) seq.push_back(rest);
   }
   // Partial-norm slots of the candidate launches, now that it is known which of them also carry the pass at x
   // (that changes how a launch of one-wave tiles splits K): a launch gets feature tiles x K slices slots.
@@ -351,13 +373,14 @@ zeno_status_t score_enqueue(const zeno_model* model, const Plan& p, const float*
       ProfScope ps(ZENO_KERNEL_PACK, 0, 4.0 * rows * D.dims[0], stream);
       ZENO_TRY(launch_pack_features(batch->features + (size_t)begin * D.dims[0], rows, D.dims[0], pad64(D.dims[0]),
                                     p.MB, bf16, ws + p.off_feat,
-                                    reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt), p.n_counters, stream));
+                                    reinterpret_cast<unsigned int*>(ws + p.off_slice_cnt), p.n_counters,
+                                    begin == 0 ? norm_partials : nullptr, begin == 0 ? (long long)m * P : 0, stream));
     }
     for (const Launch& l : seq) {
       ProfScope ps(l.kernel, l.layer, l.bytes, stream);
       LaunchShape shape;
       ZENO_TRY(launch_layer(l.a, bf16, l.delta, p.MB, stream, &shape));
-      ps.set_shape(shape, l.a.n_cand > 0 && l.a.has_base, l.a.n_cand > 0 && l.delta);
+      ps.set_shape(shape, l.a.n_cand > 0 && l.a.has_base, l.a.n_cand > 0 && l.delta, l.a.cand0, l.a.n_cand);
     }
     ProfScope ps(ZENO_KERNEL_LOSS, 0, 4.0 * (m + 1) * rows * C, stream);
     ZENO_TRY(launch_loss(reinterpret_cast<const float*>(ws + p.off_z0[L - 1]), dZ, batch->labels, batch->targets,

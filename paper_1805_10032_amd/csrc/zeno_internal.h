@@ -69,7 +69,9 @@ struct LayerArgs {
   const float* G;       // [m x d]
   const float* x;       // [d]
   long long ldg;        // floats between consecutive rows of G
-  int n_cand;           // candidates in this launch (0 or m)
+  int n_cand;           // candidates in this launch (0, m, or a part of them)
+  int cand0;            // host side only: index of the launch's first candidate.  launch_layer moves the per-candidate
+                        // pointers (G, D_cand, dZ, Dl_cand, norm_partials) there, the kernel numbers its candidates from 0
   int has_base;         // 1: the launch also runs the pass at x through bj
   int base_blocks;      // leading block indices reserved for the pass at x (multiple of 8)
   int n_r;              // valid samples (rows) in this pass
@@ -99,8 +101,10 @@ struct LayerArgs {
 
 // Launchers.  Each returns the hipError_t of its launches.
 // also clears the n_counters workgroup-arrival counters of the pass (may be 0)
+// ... and n_zero doubles at `zero` (the candidates' partial-norm slots; may be 0)
 hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, int MB, bool bf16,
-                                void* tiled, unsigned int* counters, int n_counters, hipStream_t stream);
+                                void* tiled, unsigned int* counters, int n_counters, double* zero, long long n_zero,
+                                hipStream_t stream);
 // Limits of a launch whose K is split over workgroups: bytes of partial accumulators (tiles x slices x row
 // blocks x 4 KB) and tiles (= arrival counters).  One buffer of each serves all launches of a pass, which run
 // one after the other and leave the counters at zero.
@@ -124,6 +128,7 @@ struct LaunchShape {
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream,
                         LaunchShape* shape = nullptr);
 bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB);  // run a.bj inside the candidates' launch?
+int layer_split_point(const LayerArgs& a, bool bf16, bool delta, int MB);   // candidates of the first of two launches, or n_cand
 int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB);   // partial-norm slots per candidate the launch fills
 int layer_nw(const LayerArgs& a, bool bf16, bool delta, int MB);     // waves per workgroup the launch will use
 // Extents a launch with NW waves per workgroup writes (bytes / floats / slots, counted from the start of each buffer).

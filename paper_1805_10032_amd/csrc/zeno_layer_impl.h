@@ -963,10 +963,13 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
 
 template <bool BF16>
 __global__ void pack_features_kernel(const float* __restrict__ features, int n_r, int K, int Kp, int n_pad,
-                                     void* __restrict__ tiled, unsigned int* __restrict__ counters, int n_counters) {
+                                     void* __restrict__ tiled, unsigned int* __restrict__ counters, int n_counters,
+                                     double* __restrict__ zero, long long n_zero) {
   const long long total = (long long)n_pad * Kp;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n_counters; i += (long long)gridDim.x * blockDim.x)
     counters[i] = 0u;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n_zero; i += (long long)gridDim.x * blockDim.x)
+    zero[i] = 0.0;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
     const int r = (int)(i / Kp), k = (int)(i % Kp);
     const float v = (r < n_r && k < K) ? features[(long long)r * K + k] : 0.f;

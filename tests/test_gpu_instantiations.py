@@ -62,7 +62,7 @@ def _run(B, w, s_ref, s_exact, scale, row_align, offset_floats=0):
         if r["kernel"] in ("layer_base", "layer_cand"):
             shape = (w.fwd, r["second"], r["waves"], r["k_split"], r["streaming"], r["row_blocks"], r["merged"])
             SEEN.add(shape)
-            shapes.append((r["kernel"], r["layer"]) + shape[1:])
+            shapes.append((r["kernel"], r["layer"]) + shape[1:] + (r["first_candidate"], r["candidates"]))
     tol = SCORE_TOL[w.fwd]
     err = score_error(npy(s), s_ref, scale)
     assert np.all(err <= tol), (w.name, row_align, float(err.max()), int(err.argmax()), shapes)
@@ -150,6 +150,22 @@ def test_pass_at_x_rides_in_an_eight_wave_launch(B, fwd):
     print(f"\n  merge8 {fwd}: {shapes}")
     merged = [s for s in shapes if s[0] == "layer_cand" and s[7] == 1]
     assert any(s[3] == 8 for s in merged), shapes
+
+
+@pytest.mark.parametrize("row_align", [32, 1])
+@pytest.mark.parametrize("fwd,n_r", [("bf16", 64), ("bf16", 128), ("fp32", 32)])
+def test_last_round_of_a_launch_as_one_wave_tiles(B, fwd, n_r, row_align):
+    """36 candidates on 2048-wide layers are 288 eight-wave workgroups: one full round of 256 and a round that
+    would be one-eighth full.  The launch of such a layer is cut in two: candidates 0..31 in eight-wave
+    workgroups, candidates 32..35 as one-wave tiles (with the pass at x through the next layer), each half
+    with its own range of partial-norm slots.  All rows compared; the launch records must show both halves."""
+    w, s_ref, s_exact, scale = _workload(("split", fwd, n_r), [1024, 2048, 2048, 10], 36, 10, n_r, fwd, 6, 4)
+    shapes = _run(B, w, s_ref, s_exact, scale, row_align)
+    print(f"\n  split {fwd} n_r={n_r} align={row_align}: {shapes}")
+    for layer in (0, 1):
+        halves = [s for s in shapes if s[0] == "layer_cand" and s[1] == layer]
+        assert [(s[8], s[9], s[3]) for s in halves] == [(0, 32, 8), (32, 4, 1)], shapes
+    assert [(s[8], s[9]) for s in shapes if s[0] == "layer_cand" and s[1] == 2] == [(0, 36)], shapes
 
 
 def test_zz_which_instantiations_ran(B):
