@@ -97,6 +97,12 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
   }
   p.n_counters = kMaxSliceGroups;
   p.sz_slice_part = kSlicePartialBytes;
+  // a layer wide enough for eight-wave workgroups may run the tiles of its last candidates in K slices
+  for (int l = 0; l < p.L; ++l) {
+    const int cover = l + 1 == p.L ? D.dims[l + 1] : pad64(D.dims[l + 1]);
+    if ((long long)((cover + kMaxTileRows - 1) / kMaxTileRows) * m >= 256 && tail_partial_bytes(p.MB) > p.sz_slice_part)
+      p.sz_slice_part = tail_partial_bytes(p.MB);
+  }
   p.off_slice_part = take(p.sz_slice_part);
   p.off_slice_cnt = take((size_t)p.n_counters * sizeof(unsigned int));
   p.cand_stride = align_up((size_t)p.n_pad * max_np * p.esize, 256);
@@ -144,12 +150,12 @@ struct ProfScope {
     e.rec.ms = 0.f;
     e.rec.algorithmic_bytes = bytes;
     e.rec.waves = e.rec.k_split = e.rec.streaming = e.rec.row_blocks = e.rec.merged = e.rec.second = e.rec.k_slices = 0;
-    e.rec.first_candidate = e.rec.candidates = 0;
+    e.rec.first_candidate = e.rec.candidates = e.rec.tail_candidates = 0;
     (void)hipEventRecord(e.start, stream);
     g_prof.push_back(e);
     slot = (int)g_prof.size() - 1;
   }
-  void set_shape(const LaunchShape& s, bool merged, bool second, int first_candidate, int candidates) {
+  void set_shape(const LaunchShape& s, bool merged, bool second, int first_candidate, int candidates, int tail) {
     if (slot < 0) return;
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     if (slot >= (int)g_prof.size()) return;
@@ -163,6 +169,7 @@ struct ProfScope {
     r.k_slices = s.k_slices;
     r.first_candidate = first_candidate;
     r.candidates = candidates;
+    r.tail_candidates = tail;
   }
   ~ProfScope() {
     if (slot < 0) return;
@@ -284,7 +291,22 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
       c.a.has_base = 1;
       c.a.bj = make_job(l + 1);
     }
-    // A launch whose last round of eight-wave workgroups would be mostly empty is cut in two: the candidates
+    // A launch whose last round of eight-wave workgroups would be partly empty runs the tiles of that round's
+    // candidates, and the pass at x, in K slices at its end.
+    int tail_main = m;
+    const int tail_slices = query_device ? layer_tail_slices(c.a, bf16, l > 0, p.MB, &tail_main) : 0;
+    if (tail_slices >= 2) {
+      c.a.tail_cand = m - tail_main;
+      c.a.tail_slices = tail_slices;
+      if (l + 1 < L) {
+        c.bytes += layer_bytes(l + 1);
+        c.wt_layer = l + 1;
+        c.base_layer = l + 1;
+      }
+      seq.push_back(c);
+      continue;
+    }
+    // Where that is not possible and the round would be mostly empty the launch is cut in two: the candidates
     // that fill whole rounds, then the few others as one-wave tiles (which also carry the pass at x).
     const int n_main = query_device ? layer_split_point(c.a, bf16, l > 0, p.MB) : m;
     Launch rest = c;
@@ -327,6 +349,7 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
   for (Launch& c : seq) {
     if (c.a.n_cand <= 0) continue;
     c.a.p_off = P;
+    if (c.a.tail_cand > 0) c.a.tail_p_off = P + (pad64(D.dims[c.layer + 1]) + kMaxTileRows - 1) / kMaxTileRows;
     P += query_device ? layer_tiles(c.a, bf16, c.delta, p.MB) : norm_slots_bound(D.dims[c.layer + 1], m, p.MB);
   }
   for (Launch& c : seq)
@@ -380,7 +403,7 @@ zeno_status_t score_enqueue(const zeno_model* model, const Plan& p, const float*
       ProfScope ps(l.kernel, l.layer, l.bytes, stream);
       LaunchShape shape;
       ZENO_TRY(launch_layer(l.a, bf16, l.delta, p.MB, stream, &shape));
-      ps.set_shape(shape, l.a.n_cand > 0 && l.a.has_base, l.a.n_cand > 0 && l.delta, l.a.cand0, l.a.n_cand);
+      ps.set_shape(shape, l.a.n_cand > 0 && l.a.has_base, l.a.n_cand > 0 && l.delta, l.a.cand0, l.a.n_cand, l.a.tail_cand);
     }
     ProfScope ps(ZENO_KERNEL_LOSS, 0, 4.0 * (m + 1) * rows * C, stream);
     ZENO_TRY(launch_loss(reinterpret_cast<const float*>(ws + p.off_z0[L - 1]), dZ, batch->labels, batch->targets,

@@ -97,6 +97,14 @@ struct LayerArgs {
   unsigned int* slice_counters;
   int P;                // partial slots per candidate
   int p_off;            // first slot of this layer
+  // Sliced tail of a launch of eight-wave workgroups (see layer_tail_slices): the tiles of the last tail_cand
+  // candidates, and of the pass at x if the launch carries it, run as tail_slices K slices each, in the blocks
+  // from main_blocks on.  Their partial accumulators go through slice_partials / slice_counters as well; their
+  // partial norms to the slots tail_p_off + tile * tail_slices + slice.
+  int tail_cand;
+  int tail_slices;
+  int tail_p_off;
+  int main_blocks;      // filled in by the launcher
 };
 
 // Launchers.  Each returns the hipError_t of its launches.
@@ -110,6 +118,9 @@ hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, i
 // one after the other and leave the counters at zero.
 constexpr size_t kSlicePartialBytes = size_t(8) << 20;
 constexpr int kMaxSliceGroups = 2048;
+// Sliced tails: at most this many eight-wave workgroups (tiles x slices), each handing over 8 x row blocks x 4 KB
+constexpr int kMaxTailWorkgroups = 256;
+inline size_t tail_partial_bytes(int MB) { return (size_t)kMaxTailWorkgroups * 8 * MB * 16 * 64 * sizeof(float); }
 struct KPlan {
   int k_waves;    // waves of a workgroup that share a feature tile and split K
   int k_slices;   // workgroups per feature tile
@@ -129,6 +140,8 @@ hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipSt
                         LaunchShape* shape = nullptr);
 bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB);  // run a.bj inside the candidates' launch?
 int layer_split_point(const LayerArgs& a, bool bf16, bool delta, int MB);   // candidates of the first of two launches, or n_cand
+// K slices for the tiles of the last (n_cand - *n_main) candidates of an eight-wave launch, or 0: no sliced tail
+int layer_tail_slices(const LayerArgs& a, bool bf16, bool delta, int MB, int* n_main);
 int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB);   // partial-norm slots per candidate the launch fills
 int layer_nw(const LayerArgs& a, bool bf16, bool delta, int MB);     // waves per workgroup the launch will use
 // Extents a launch with NW waves per workgroup writes (bytes / floats / slots, counted from the start of each buffer).

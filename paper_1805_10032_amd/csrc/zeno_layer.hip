@@ -49,6 +49,7 @@ static int ks_waves(bool bf16, bool delta, int MB) {
 // are 3.1 rounds, four waves gain 2-4 % per layer; workload 5: 1024 are exactly four rounds and
 // eight waves, which copy the activations once per 256 features instead of once per 128, win).
 static int nw_for(const LayerArgs& a, bool bf16, bool delta, int MB) {
+  if (a.tail_cand > 0) return 8;   // planned with a sliced tail, which exists for eight-wave workgroups
   const int nw = launch_nw_for(a);
   if (nw != 8 || a.n_cand <= 0) return nw;
   if (wgs_per_cu(bf16, delta, MB, 4) < 2) return 8;
@@ -143,6 +144,12 @@ LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, in
     e.slice_counters = (int)groups;
     if (a.n_cand > 0) e.norm_slots *= kp.k_slices;
   }
+  if (a.tail_cand > 0 && NW == 8) {
+    const long long tiles = (a.has_base ? job_tiles(a.bj, 256) : 0) + (long long)job_tiles(a.cj, 256) * a.tail_cand;
+    e.slice_bytes = tiles * a.tail_slices * 8 * MB * 16 * 64 * (long long)sizeof(float);
+    e.slice_counters = (int)tiles;
+    e.norm_slots = a.tail_p_off - a.p_off + job_tiles(a.cj, 256) * a.tail_slices;   // both ranges, counted from p_off
+  }
   return e;
 }
 
@@ -171,9 +178,50 @@ int layer_split_point(const LayerArgs& a, bool bf16, bool delta, int MB) {
   return n_main;
 }
 
+// Does the eight-wave workgroup of this kind double-buffer its activation chunks (the sliced tail needs it)?
+static bool wide_double_buffered(bool bf16, bool delta, int MB) {
+  auto pick = [&](auto mb) {
+    constexpr int M = decltype(mb)::value;
+    return bf16 ? (delta ? Lds<true, true, M, 8>::DBUF : Lds<true, false, M, 8>::DBUF)
+                : (delta ? Lds<false, true, M, 8>::DBUF : Lds<false, false, M, 8>::DBUF);
+  };
+  return MB == 1 ? pick(std::integral_constant<int, 1>{}) : MB == 2 ? pick(std::integral_constant<int, 2>{})
+                                                                     : pick(std::integral_constant<int, 4>{});
+}
+
+// Sliced tail of a candidate launch of eight-wave workgroups.  When the workgroups of the launch do not fill their
+// last round of resident slots, the candidates of that round (and the pass at x, if the launch carries it) are cut
+// into K slices, as many as bring their workgroups to about one round: the round then lasts a fraction of a whole
+// tile's time, and the slices start as soon as slots free up behind the whole tiles.  Workload 4's 2048-wide layers
+// (100 candidates x 8 tiles = 3.125 rounds of 256): candidates 96..99 and the pass at x are 40 tiles, cut six ways.
+// Not for launches on the shifted column grid (its tiles are staged one ahead from column 0) and not where the
+// workgroup is single-buffered; those fall back to layer_split_point.
+int layer_tail_slices(const LayerArgs& a, bool bf16, bool delta, int MB, int* n_main_out) {
+  *n_main_out = a.n_cand;
+  if (a.n_cand <= 0 || launch_nw_for(a) != 8 || a.slice_partials == nullptr || a.slice_counters == nullptr) return 0;
+  if (!wide_double_buffered(bf16, delta, MB)) return 0;
+  if (bf16 && !launch_lines_aligned(a) && launch_ring_ok(a)) return 0;   // this launch takes the shifted grid
+  const long long slots = (long long)compute_units() * wgs_per_cu(bf16, delta, MB, 8);
+  const int tiles8 = job_tiles(a.cj, 256);
+  const long long full = (long long)tiles8 * a.n_cand / slots * slots;
+  const int n_main = (int)(full / tiles8), rest = a.n_cand - n_main;
+  if (n_main <= 0 || rest <= 0 || full % tiles8 != 0) return 0;
+  const long long tail_tiles = (long long)rest * tiles8 + (a.has_base ? job_tiles(a.bj, 256) : 0);
+  int min_chunks = a.cj.Kp >> 6;
+  if (a.has_base && (a.bj.Kp >> 6) < min_chunks) min_chunks = a.bj.Kp >> 6;
+  long long S = slots / tail_tiles;
+  if (S > kMaxTailWorkgroups / tail_tiles) S = kMaxTailWorkgroups / tail_tiles;
+  if (S > min_chunks / 4) S = min_chunks / 4;
+  if (S > 8) S = 8;
+  if (S < 2) return 0;
+  *n_main_out = n_main;
+  return (int)S;
+}
+
 int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB) {
   const int NW = nw_for(a, bf16, delta, MB);
-  return job_tiles(a.cj, 32 * NW) * layer_k_plan(a, bf16, delta, MB, NW, true).k_slices;
+  const int tail = a.tail_cand > 0 ? job_tiles(a.cj, 256) * a.tail_slices : 0;
+  return job_tiles(a.cj, 32 * NW) * layer_k_plan(a, bf16, delta, MB, NW, true).k_slices + tail;
 }
 
 // Should the pass at x (a.bj) ride in the candidates' launch?  Workgroups run in

@@ -332,11 +332,18 @@ struct Lds {
 // streamed); the tiles are staged into a ring of 128 columns at (column mod 128), one tile ahead of the
 // products, which read their 64 columns at the unshifted positions.  Nothing else knows of the shift.  The
 // first tile's columns before the row and the last (extra) tile's columns behind it are masked.
-template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS, bool RING = false>
+//
+// TAIL (eight-wave workgroups): the launch ends with the tiles of its last a.tail_cand candidates (and of the pass
+// at x, if it rides along) cut into a.tail_slices K slices each.  A launch whose workgroups do not fill their last
+// round of resident slots would run that round at a fraction of the chip; cut into slices the same tiles are
+// several times as many workgroups, each a fraction as long.  The slices of a tile hand their partial accumulators
+// over through memory as the K slices of one-wave tiles do (last workgroup to arrive adds them in slice order).
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS, bool RING = false, bool TAIL = false>
 __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) {
   static_assert(KS == 1 || NW == 1, "K is only split in one-tile workgroups");
   using T = Tr<BF16>;
   using LD = Lds<BF16, DELTA, MB, NW, RING>;
+  static_assert(!TAIL || (NW == 8 && KS == 1 && !RING && LD::DBUF), "sliced tails exist for eight-wave workgroups on the plain column grid");
   static_assert(!RING || (BF16 && KS == 1 && NW > 1 && LD::DBUF), "the shifted grid exists for wide bf16 workgroups with double buffers");
   static_assert(KS == 1 || LD::DBUF, "the single-buffer loop has workgroup barriers, which waves with different K ranges cannot share");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
@@ -367,7 +374,18 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // on an XCD therefore stream the SAME rows of W (second product) at about the
   // same time and share them through that L2, while everything that is private to
   // a candidate (its activations) is reused inside the workgroup through LDS.
-  const bool is_base = (int)blockIdx.x < a.base_blocks;
+  // TAIL: the block indices from a.main_blocks on are the sliced tiles, numbered [tiles of the pass at x]
+  // [tail candidates x tiles], a.tail_slices consecutive blocks per tile; the pass at x has no leading blocks then.
+  bool is_base = (int)blockIdx.x < a.base_blocks;
+  int tail_tile = -1;   // >= 0: this workgroup runs one K slice of that tile of the tail
+  int tail_base_tiles = 0;
+  if constexpr (TAIL) {
+    if ((int)blockIdx.x >= a.main_blocks) {
+      tail_tile = ((int)blockIdx.x - a.main_blocks) / a.tail_slices;
+      tail_base_tiles = a.has_base ? (cover_rows(a.bj.N, a.bj.last) + BN - 1) / BN : 0;
+      is_base = tail_tile < tail_base_tiles;
+    }
+  }
   const LayerJob& J = is_base ? a.bj : a.cj;
   const int N = J.N, K = J.K, last = J.last, Np = J.Np;
   const int n_chunks = J.Kp >> 6;
@@ -376,8 +394,19 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // K slice of this workgroup: a launch of one-wave tiles whose tiles do not fill the chip well splits K
   // over k_slices workgroups per tile (on top of, or instead of, the split over the KS waves of a workgroup)
   int ks = 0;
-  const int n_slices = (NW == 1 && a.k_slices > 1) ? a.k_slices : 1;
-  if (is_base) {
+  const int n_slices = (TAIL && tail_tile >= 0) ? a.tail_slices : (NW == 1 && a.k_slices > 1) ? a.k_slices : 1;
+  const int n_main = TAIL ? a.n_cand - a.tail_cand : a.n_cand;   // candidates whose tiles run whole
+  if (TAIL && tail_tile >= 0) {
+    ks = ((int)blockIdx.x - a.main_blocks) % n_slices;
+    if (is_base) {
+      nt = tail_tile;
+    } else {
+      const int g = tail_tile - tail_base_tiles;
+      nt = g % n_tiles;
+      s = n_main + g / n_tiles;
+      if (s >= a.n_cand) return;
+    }
+  } else if (is_base) {
     nt = blockIdx.x / n_slices;
     ks = blockIdx.x % n_slices;
     if (nt >= n_tiles) return;
@@ -385,14 +414,14 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     int bid = blockIdx.x - a.base_blocks;
     ks = bid % n_slices;
     bid /= n_slices;
-    const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
-    const int n_cchunks = (a.n_cand + cc - 1) / cc;
+    const int cc = n_main < kSrcChunk ? n_main : kSrcChunk;
+    const int n_cchunks = (n_main + cc - 1) / cc;
     const int xcd = bid & 7, slot = bid >> 3;
     const int unit = (slot / cc) * 8 + xcd;
     if (unit >= n_tiles * n_cchunks) return;
     nt = unit / n_cchunks;
     s = (unit % n_cchunks) * cc + slot % cc;
-    if (s >= a.n_cand) return;
+    if (s >= n_main) return;
   }
   const float* __restrict__ P = is_base ? a.x : a.G + (long long)s * a.ldg;
   const int row0 = nt * BN + wave * 32;
@@ -420,8 +449,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // candidate.
   const bool all_full = (K & 63) == 0;
   const int cs0 = n_chunks * ks / n_slices, cs1 = n_chunks * (ks + 1) / n_slices;   // this workgroup's chunks
-  const int c_begin = NW == 1 ? cs0 + (cs1 - cs0) * kw / KS : 0;
-  const int c_end = NW == 1 ? cs0 + (cs1 - cs0) * (kw + 1) / KS : n_chunks;
+  const int c_begin = NW == 1 ? cs0 + (cs1 - cs0) * kw / KS : TAIL ? cs0 : 0;
+  const int c_end = NW == 1 ? cs0 + (cs1 - cs0) * (kw + 1) / KS : TAIL ? cs1 : n_chunks;
 
   f32x16 acc[MB];
 #pragma unroll
@@ -732,8 +761,9 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     }
     if (kw != 0) return;
   }
-  if (NW == 1 && n_slices > 1) {
-    if (KS == 1 && do_norm) {
+  bool finish = true;   // this workgroup completes the tile: epilogue and results
+  if ((NW == 1 || TAIL) && n_slices > 1) {
+    if (NW == 1 && KS == 1 && do_norm) {
       // one wave per workgroup: bring its share of ||u||^2 to lane 0, as the K split over waves does
 #pragma unroll
       for (int off = 32; off > 0; off >>= 1) nrm += __shfl_xor(nrm, off, 64);
@@ -741,10 +771,13 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     }
     // K was also split over workgroups: publish this workgroup's partial accumulators, and let the last
     // workgroup of the tile to arrive add all of them, in slice order whoever it is, and finish the tile
-    // layout: per slice MB*4 pieces of 64 lanes x 16 bytes (accumulator registers 4q..4q+3 of block mb)
-    const long long grp = is_base ? nt : a.slice_group0 + (long long)s * n_tiles + nt;   // the tile this workgroup shares
-    float* part = a.slice_partials + grp * n_slices * (MB * 16 * 64);
-    float* mine = part + (long long)ks * (MB * 16 * 64);
+    // layout: per slice and wave MB*4 pieces of 64 lanes x 16 bytes (accumulator registers 4q..4q+3 of block mb)
+    constexpr int WAVE_FLOATS = MB * 16 * 64;
+    const long long slice_stride = (long long)NW * WAVE_FLOATS;
+    // the tile this workgroup shares (TAIL: the sliced tiles are numbered as their blocks are)
+    const long long grp = TAIL ? tail_tile : is_base ? nt : a.slice_group0 + (long long)s * n_tiles + nt;
+    float* part = a.slice_partials + grp * n_slices * slice_stride + wave * WAVE_FLOATS;   // this wave's features
+    float* mine = part + ks * slice_stride;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -756,20 +789,33 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partials have reached memory before the arrival is counted
     unsigned arrived = 0;
-    if (lane == 0) arrived = __hip_atomic_fetch_add(&a.slice_counters[grp], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if constexpr (NW == 1) {
+      if (lane == 0) arrived = __hip_atomic_fetch_add(&a.slice_counters[grp], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      // one arrival per workgroup, counted when the partials of all its waves are out; the count reaches the
+      // other waves through LDS (the activation buffers are idle: every wave has left the loop by the barrier)
+      __syncthreads();
+      unsigned* flag = reinterpret_cast<unsigned*>(lds_all);
+      if (tid == 0) *flag = __hip_atomic_fetch_add(&a.slice_counters[grp], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __syncthreads();
+      arrived = *flag;
+    }
     arrived = __builtin_amdgcn_readfirstlane(arrived);
     if (arrived != (unsigned)(n_slices - 1)) {
-      // not the last one: only this slice's share of ||u||^2 is left to deliver (lane 0 holds it)
-      if (do_norm && lane == 0) a.norm_partials[(long long)s * a.P + a.p_off + nt * n_slices + ks] = nrm;
-      return;
-    }
+      if constexpr (NW == 1) {
+        // not the last one: only this slice's share of ||u||^2 is left to deliver (lane 0 holds it)
+        if (do_norm && lane == 0) a.norm_partials[(long long)s * a.P + a.p_off + nt * n_slices + ks] = nrm;
+        return;
+      }
+      finish = false;   // wide workgroups: the waves still add up their share of ||u||^2 below
+    } else {
     // The other workgroups' partials are read with system-scope loads (they bypass the caches on the way,
     // as the stores did, so no cache has to be written back or invalidated).  A round trip to memory is
     // long while other workgroups stream at full rate, so the loads of several slices (up to 64 registers'
     // worth) are issued together and completed by one wait; the wait statements name the loaded registers
     // as operands so that no use of them can be scheduled ahead of it.  The sum is taken in slice order
     // whoever adds it; this workgroup's own slice comes from its registers (bit-identical to what it stored).
-    constexpr int BATCH = 4 / MB;   // slices per round trip: 4, 2 or 1
+    constexpr int BATCH = (TAIL ? 8 : 4) / MB;   // slices per round trip: 4, 2 or 1 (sliced tails: 8, 4 or 2)
     f32x16 total[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -781,7 +827,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       for (int i = 0; i < BATCH; ++i) {
         const int q = q0 + i;
         if (q < n_slices && q != ks) {   // uniform over the wave
-          const float* other = part + (long long)q * (MB * 16 * 64);
+          const float* other = part + q * slice_stride;
 #pragma unroll
           for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -821,7 +867,9 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[mb] = total[mb];
-    if (lane == 0) __hip_atomic_store(&a.slice_counters[grp], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next pass
+    if (NW == 1 ? lane == 0 : tid == 0)
+      __hip_atomic_store(&a.slice_counters[grp], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next pass
+    }
   }
 
   // ---- epilogue.  The weight tile is the first operand of the products, so the
@@ -830,6 +878,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // row0 + 8 (j/4) + 4 h + j%4.  Four consecutive features of one sample are
   // adjacent in the tiled operand of the next layer, so a lane stores them as one
   // piece and a wave's store instruction covers one contiguous 512 B / 1 KB run.
+  if (finish) {
   const int n = lane & 31, h = lane >> 5;
   f32x4 bias[4];
 #pragma unroll
@@ -940,6 +989,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     }
   }
 
+  }   // finish
+
   if (do_norm) {
     // fixed-order reduction: lanes by xor-shuffle tree, then waves in order
 #pragma unroll
@@ -955,7 +1006,9 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       if (tid == 0) {
         double t = 0.0;
         for (int wv = 0; wv < NW; ++wv) t += red[wv];
-        a.norm_partials[(long long)s * a.P + a.p_off + nt] = t;
+        // the sliced tiles of a launch's tail have a range of slots of their own, one per (tile, slice)
+        const int slot = (TAIL && tail_tile >= 0) ? a.tail_p_off + nt * n_slices + ks : a.p_off + nt;
+        a.norm_partials[(long long)s * a.P + slot] = t;
       }
     }
   }
@@ -979,35 +1032,51 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
 
 int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
 
-template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1, bool RING = false>
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1, bool RING = false, bool TAIL = false>
 hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
   constexpr int BN = 32 * NW;
   if (shape != nullptr) {
     shape->waves = NW;
     shape->k_split = KS;
-    shape->k_slices = NW == 1 && a.k_slices > 1 ? a.k_slices : 1;
+    shape->k_slices = TAIL ? a.tail_slices : NW == 1 && a.k_slices > 1 ? a.k_slices : 1;
     shape->streaming = RING ? 2 : NT ? 1 : 0;
     shape->row_blocks = MB;
   }
   constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW, RING>::TOTAL * KS;
   // once per process and instantiation (initialisation of a local static is thread-safe)
   static const hipError_t attr_err =
-      lds_bytes > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT, KS, RING>),
+      lds_bytes > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<BF16, DELTA, MB, NW, NT, KS, RING, TAIL>),
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes)
                             : hipSuccess;
   if (attr_err != hipSuccess) return attr_err;
   // K slices (one-wave tiles only) come with the caller's plan; they need the partial and counter buffers
   if (NW != 1 || a.k_slices < 1) a.k_slices = 1;
   if (a.k_slices > 1 && (a.slice_partials == nullptr || a.slice_counters == nullptr)) return hipErrorInvalidValue;
-  a.base_blocks = a.has_base ? (job_tiles(a.bj, BN) * a.k_slices + 7) / 8 * 8 : 0;
+  if (!TAIL) a.tail_cand = a.tail_slices = 0;
+  if (TAIL && (a.tail_cand < 1 || a.tail_cand >= a.n_cand || a.tail_slices < 2 || a.slice_partials == nullptr ||
+               a.slice_counters == nullptr))
+    return hipErrorInvalidValue;
+  // TAIL: the pass at x has no leading blocks, its tiles are sliced like the tail candidates'
+  a.base_blocks = (a.has_base && !TAIL) ? (job_tiles(a.bj, BN) * a.k_slices + 7) / 8 * 8 : 0;
+  const int n_main = a.n_cand - a.tail_cand;
   int cand_blocks = 0;
-  if (a.n_cand > 0) {
-    const int cc = a.n_cand < kSrcChunk ? a.n_cand : kSrcChunk;
-    const int units = job_tiles(a.cj, BN) * ((a.n_cand + cc - 1) / cc);
+  if (n_main > 0) {
+    const int cc = n_main < kSrcChunk ? n_main : kSrcChunk;
+    const int units = job_tiles(a.cj, BN) * ((n_main + cc - 1) / cc);
     cand_blocks = ((units + 7) / 8) * 8 * cc * a.k_slices;
   }
-  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW, NT, KS, RING>), dim3(a.base_blocks + cand_blocks), dim3(64 * NW * KS),
-                     lds_bytes, stream, a);
+  a.main_blocks = a.base_blocks + cand_blocks;
+  int tail_blocks = 0;
+  if (TAIL) {
+    const long long tiles = (a.has_base ? job_tiles(a.bj, BN) : 0) + (long long)job_tiles(a.cj, BN) * a.tail_cand;
+    // every slice keeps at least two chunks of every job; the hand-over buffers hold all sliced tiles
+    if ((a.cj.Kp >> 6) < 2 * a.tail_slices || (a.has_base && (a.bj.Kp >> 6) < 2 * a.tail_slices) ||
+        tiles * a.tail_slices > kMaxTailWorkgroups || tiles > kMaxSliceGroups)
+      return hipErrorInvalidValue;
+    tail_blocks = (int)tiles * a.tail_slices;
+  }
+  hipLaunchKernelGGL((layer_kernel<BF16, DELTA, MB, NW, NT, KS, RING, TAIL>), dim3(a.main_blocks + tail_blocks),
+                     dim3(64 * NW * KS), lds_bytes, stream, a);
   return hipGetLastError();
 }
 
@@ -1095,6 +1164,13 @@ hipError_t launch_nt(const LayerArgs& a, hipStream_t stream, LaunchShape* shape)
     const bool cand_ok = a.n_cand == 0 || (a.cj.Kp >> 6) >= 2 * a.k_slices;
     if (!(base_ok && cand_ok)) return hipErrorInvalidValue;
   }
+  if constexpr (NW == 8 && Lds<BF16, DELTA, MB, NW>::DBUF) {
+    if (a.tail_cand > 0) {
+      if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, 1, false, true>(a, stream, shape);
+      return launch_inst<BF16, DELTA, MB, NW, false, 1, false, true>(a, stream, shape);
+    }
+  }
+  if (a.tail_cand > 0) return hipErrorInvalidValue;   // planned for a launch shape that has no sliced tail
   if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream, shape);
   if constexpr (BF16 && NW > 1 && Lds<BF16, DELTA, MB, NW, true>::DBUF) {
     if (launch_ring_ok(a)) return launch_inst<BF16, DELTA, MB, NW, true, 1, true>(a, stream, shape);

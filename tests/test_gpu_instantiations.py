@@ -62,7 +62,8 @@ def _run(B, w, s_ref, s_exact, scale, row_align, offset_floats=0):
         if r["kernel"] in ("layer_base", "layer_cand"):
             shape = (w.fwd, r["second"], r["waves"], r["k_split"], r["streaming"], r["row_blocks"], r["merged"])
             SEEN.add(shape)
-            shapes.append((r["kernel"], r["layer"]) + shape[1:] + (r["first_candidate"], r["candidates"]))
+            shapes.append((r["kernel"], r["layer"]) + shape[1:] + (r["first_candidate"], r["candidates"],
+                                                                    r["tail_candidates"], r["k_slices"]))
     tol = SCORE_TOL[w.fwd]
     err = score_error(npy(s), s_ref, scale)
     assert np.all(err <= tol), (w.name, row_align, float(err.max()), int(err.argmax()), shapes)
@@ -153,18 +154,40 @@ def test_pass_at_x_rides_in_an_eight_wave_launch(B, fwd):
 
 
 @pytest.mark.parametrize("row_align", [32, 1])
-@pytest.mark.parametrize("fwd,n_r", [("bf16", 64), ("bf16", 128), ("fp32", 32)])
-def test_last_round_of_a_launch_as_one_wave_tiles(B, fwd, n_r, row_align):
+@pytest.mark.parametrize("fwd,n_r", [("bf16", 64), ("bf16", 128), ("bf16", 32), ("fp32", 32), ("fp32", 64)])
+def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align):
     """36 candidates on 2048-wide layers are 288 eight-wave workgroups: one full round of 256 and a round that
-    would be one-eighth full.  The launch of such a layer is cut in two: candidates 0..31 in eight-wave
-    workgroups, candidates 32..35 as one-wave tiles (with the pass at x through the next layer), each half
-    with its own range of partial-norm slots.  All rows compared; the launch records must show both halves."""
-    w, s_ref, s_exact, scale = _workload(("split", fwd, n_r), [1024, 2048, 2048, 10], 36, 10, n_r, fwd, 6, 4)
+    would be one-eighth full.  The tiles of candidates 32..35 and of the pass at x through the next layer run
+    as K slices at the end of the launch (partial accumulators handed over through memory, partial norms in a
+    range of slots of their own).  All rows compared; the launch records must name the sliced tail.
+    d mod 4 = 2: the dense rows are 8-byte aligned and take plain loads."""
+    w, s_ref, s_exact, scale = _workload(("tail", fwd, n_r), [1024, 2048, 2048, 10], 36, 10, n_r, fwd, 6, 4)
     shapes = _run(B, w, s_ref, s_exact, scale, row_align)
-    print(f"\n  split {fwd} n_r={n_r} align={row_align}: {shapes}")
+    print(f"\n  sliced tail {fwd} n_r={n_r} align={row_align}: {shapes}")
     for layer in (0, 1):
-        halves = [s for s in shapes if s[0] == "layer_cand" and s[1] == layer]
-        assert [(s[8], s[9], s[3]) for s in halves] == [(0, 32, 8), (32, 4, 1)], shapes
+        launches = [s for s in shapes if s[0] == "layer_cand" and s[1] == layer]
+        assert len(launches) == 1 and launches[0][3] == 8 and launches[0][7] == 1, shapes          # eight waves, merged
+        assert launches[0][8:11] == (0, 36, 4) and launches[0][11] >= 2, shapes                    # tail of 4, sliced
+    assert [s[8:11] for s in shapes if s[0] == "layer_cand" and s[1] == 2] == [(0, 36, 0)], shapes
+    # same scores from run to run: the slices are added in slice order whoever arrives last
+    dev = torch.device("cuda", 0)
+    mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
+    G = rows_to_gpu(B, w.G, row_align, dev)
+    a = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
+    b = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("fwd,n_r,dims", [("bf16", 64, [1024, 2048, 2048, 12]), ("bf16", 128, [1024, 2048, 2048, 12])])
+def test_last_round_of_a_launch_as_one_wave_tiles(B, fwd, n_r, dims):
+    """Where the eight-wave workgroups cannot slice their tail (dense 16-byte aligned rows on the shifted column
+    grid) the launch of such a layer is cut in two: candidates 0..31 in eight-wave workgroups, candidates 32..35 as one-wave tiles (with the pass
+    at x through the next layer), each half with its own range of partial-norm slots."""
+    w, s_ref, s_exact, scale = _workload(("split", fwd, n_r), dims, 36, 10, n_r, fwd, 6, 4)
+    shapes = _run(B, w, s_ref, s_exact, scale, 1)
+    print(f"\n  split {fwd} n_r={n_r}: {shapes}")
+    halves = [s for s in shapes if s[0] == "layer_cand" and s[1] == 1]
+    assert [(s[8], s[9], s[3]) for s in halves] == [(0, 32, 8), (32, 4, 1)], shapes
     assert [(s[8], s[9]) for s in shapes if s[0] == "layer_cand" and s[1] == 2] == [(0, 36)], shapes
 
 
