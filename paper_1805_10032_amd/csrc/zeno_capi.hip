@@ -349,7 +349,7 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
   for (Launch& c : seq) {
     if (c.a.n_cand <= 0) continue;
     c.a.p_off = P;
-    if (c.a.tail_cand > 0) c.a.tail_p_off = P + (pad64(D.dims[c.layer + 1]) + kMaxTileRows - 1) / kMaxTileRows;
+    if (c.a.tail_slices >= 2) c.a.tail_p_off = P + (pad64(D.dims[c.layer + 1]) + kMaxTileRows - 1) / kMaxTileRows;
     P += query_device ? layer_tiles(c.a, bf16, c.delta, p.MB) : norm_slots_bound(D.dims[c.layer + 1], m, p.MB);
   }
   for (Launch& c : seq)

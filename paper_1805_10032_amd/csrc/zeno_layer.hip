@@ -49,7 +49,7 @@ static int ks_waves(bool bf16, bool delta, int MB) {
 // are 3.1 rounds, four waves gain 2-4 % per layer; workload 5: 1024 are exactly four rounds and
 // eight waves, which copy the activations once per 256 features instead of once per 128, win).
 static int nw_for(const LayerArgs& a, bool bf16, bool delta, int MB) {
-  if (a.tail_cand > 0) return 8;   // planned with a sliced tail, which exists for eight-wave workgroups
+  if (a.tail_slices >= 2) return 8;   // planned with a sliced tail, which exists for eight-wave workgroups
   const int nw = launch_nw_for(a);
   if (nw != 8 || a.n_cand <= 0) return nw;
   if (wgs_per_cu(bf16, delta, MB, 4) < 2) return 8;
@@ -144,7 +144,7 @@ LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, in
     e.slice_counters = (int)groups;
     if (a.n_cand > 0) e.norm_slots *= kp.k_slices;
   }
-  if (a.tail_cand > 0 && NW == 8) {
+  if (a.tail_slices >= 2 && NW == 8) {
     const long long tiles = (a.has_base ? job_tiles(a.bj, 256) : 0) + (long long)job_tiles(a.cj, 256) * a.tail_cand;
     e.slice_bytes = tiles * a.tail_slices * 8 * MB * 16 * 64 * (long long)sizeof(float);
     e.slice_counters = (int)tiles;
@@ -205,6 +205,9 @@ int layer_tail_slices(const LayerArgs& a, bool bf16, bool delta, int MB, int* n_
   const int tiles8 = job_tiles(a.cj, 256);
   const long long full = (long long)tiles8 * a.n_cand / slots * slots;
   const int n_main = (int)(full / tiles8), rest = a.n_cand - n_main;
+  // (candidates that fill their rounds exactly leave the pass at x to a launch of its own: as a sliced tail of 16
+  // tiles x 8 slices behind workload 5's 4096-wide layers it took 60 us, twice what the launch of one-wave tiles
+  // with K split over waves and workgroups takes; with four row blocks the hand-over alone is seven round trips)
   if (n_main <= 0 || rest <= 0 || full % tiles8 != 0) return 0;
   const long long tail_tiles = (long long)rest * tiles8 + (a.has_base ? job_tiles(a.bj, 256) : 0);
   int min_chunks = a.cj.Kp >> 6;
@@ -220,7 +223,7 @@ int layer_tail_slices(const LayerArgs& a, bool bf16, bool delta, int MB, int* n_
 
 int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB) {
   const int NW = nw_for(a, bf16, delta, MB);
-  const int tail = a.tail_cand > 0 ? job_tiles(a.cj, 256) * a.tail_slices : 0;
+  const int tail = a.tail_slices >= 2 ? job_tiles(a.cj, 256) * a.tail_slices : 0;
   return job_tiles(a.cj, 32 * NW) * layer_k_plan(a, bf16, delta, MB, NW, true).k_slices + tail;
 }
 

@@ -333,8 +333,8 @@ struct Lds {
 // products, which read their 64 columns at the unshifted positions.  Nothing else knows of the shift.  The
 // first tile's columns before the row and the last (extra) tile's columns behind it are masked.
 //
-// TAIL (eight-wave workgroups): the launch ends with the tiles of its last a.tail_cand candidates (and of the pass
-// at x, if it rides along) cut into a.tail_slices K slices each.  A launch whose workgroups do not fill their last
+// TAIL (eight-wave workgroups): the launch ends with the tiles of its last a.tail_cand candidates (may be none) and
+// of the pass at x, if it rides along, cut into a.tail_slices K slices each.  A launch whose workgroups do not fill their last
 // round of resident slots would run that round at a fraction of the chip; cut into slices the same tiles are
 // several times as many workgroups, each a fraction as long.  The slices of a tile hand their partial accumulators
 // over through memory as the K slices of one-wave tiles do (last workgroup to arrive adds them in slice order).
@@ -448,7 +448,9 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // loads lets a chunk wait for exactly its own activation copies) / ragged in K, and BASE (pass at x: no second product, writes W in operand order) or
   // candidate.
   const bool all_full = (K & 63) == 0;
-  const int cs0 = n_chunks * ks / n_slices, cs1 = n_chunks * (ks + 1) / n_slices;   // this workgroup's chunks
+  // this workgroup's chunks (slices of wide workgroups start at even chunks)
+  const int cs0 = (n_chunks * ks / n_slices) & (NW > 1 ? ~1 : ~0);
+  const int cs1 = ks + 1 == n_slices ? n_chunks : (n_chunks * (ks + 1) / n_slices) & (NW > 1 ? ~1 : ~0);
   const int c_begin = NW == 1 ? cs0 + (cs1 - cs0) * kw / KS : TAIL ? cs0 : 0;
   const int c_end = NW == 1 ? cs0 + (cs1 - cs0) * (kw + 1) / KS : TAIL ? cs1 : n_chunks;
 
@@ -550,7 +552,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // derives its wait counts from the worst path through the loop, and a path on
   // which the later tile was NOT requested makes it wait for all loads at the top
   // of every chunk, i.e. no tile would stay in flight across a chunk.
-  // odd_c (RING only): the parity of c, which selects the half of the staging ring at compile time.
+  // odd_c: the parity of c in wide workgroups (selects the activation buffer, and with RING the half of the staging ring, at compile time).
   auto chunk = [&](auto full_c, auto base_c, auto steady_c, auto odd_c, f32x4 (&u)[8], f32x4 (&w)[WREGS], int c)
                    __attribute__((always_inline)) {
     constexpr bool ODD = decltype(odd_c)::value;
@@ -559,7 +561,9 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     constexpr bool BASE = decltype(base_c)::value;   // this workgroup runs the pass at x
     constexpr bool STEADY = decltype(steady_c)::value;
     constexpr bool SECOND = DELTA && !BASE;           // second product D W^T present
-    const int buf = DBUF ? (c & 1) : 0;
+    // wide workgroups start at an even chunk, so the parity of c, and with it every LDS address of the chunk,
+    // is a compile-time constant; waves that split K may start anywhere
+    const int buf = DBUF ? (NW > 1 ? (ODD ? 1 : 0) : (c & 1)) : 0;
     // RING: u holds tile c + 1 of the shifted grid, staged one chunk ahead of the products
     take_tile(full_c, std::integral_constant<bool, !ODD>{}, u);
     if (DBUF) {
@@ -661,7 +665,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     // so that the epilogue does not start with a round trip to memory.
     if (J.b_off >= 0 && lane < 32 && row0 + lane < N) bias_lane = P[J.b_off + row0 + lane];
     __builtin_amdgcn_sched_barrier(0);
-    if (DBUF) copy_AD(c_begin, c_begin & 1);
+    if (DBUF) copy_AD(c_begin, NW > 1 ? 0 : c_begin & 1);
     __builtin_amdgcn_sched_barrier(0);
     int c = c_begin;
     const float* Ufirst = Urow0 + (c_begin << 6);
@@ -695,7 +699,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       }
       for (; c + 3 < c_end; c += 2) {
         chunk(full_c, base_c, std::true_type{}, std::false_type{}, u0, w0, c);
-        chunk(full_c, base_c, std::true_type{}, std::false_type{}, u1, w1, c + 1);
+        chunk(full_c, base_c, std::true_type{}, std::true_type{}, u1, w1, c + 1);
       }
     } else {
       if (c_begin < c_end) load_tile<MODE, NT>(u0, Ufirst, lane_off, row0, c_begin << 6, N, K, lane);
@@ -708,7 +712,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     // the last two or three chunks (all of them for a short K): every load is conditional
     for (; c < c_end; c += 2) {
       chunk(full_c, base_c, std::false_type{}, std::false_type{}, u0, w0, c);
-      if (c + 1 < c_end) chunk(full_c, base_c, std::false_type{}, std::false_type{}, u1, w1, c + 1);
+      if (c + 1 < c_end) chunk(full_c, base_c, std::false_type{}, std::true_type{}, u1, w1, c + 1);
     }
     if (KS > 1) wait_vmcnt<0>();  // a wave with an empty K range still has its first copy in flight
     }
@@ -815,7 +819,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     // worth) are issued together and completed by one wait; the wait statements name the loaded registers
     // as operands so that no use of them can be scheduled ahead of it.  The sum is taken in slice order
     // whoever adds it; this workgroup's own slice comes from its registers (bit-identical to what it stored).
-    constexpr int BATCH = (TAIL ? 8 : 4) / MB;   // slices per round trip: 4, 2 or 1 (sliced tails: 8, 4 or 2)
+    // slices per round trip: 4, 2 or 1; sliced tails with one or two row blocks have the registers for 8 or 4
+    constexpr int BATCH = (TAIL && MB < 4 ? 8 : 4) / MB;
     f32x16 total[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -1053,8 +1058,8 @@ hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
   if (NW != 1 || a.k_slices < 1) a.k_slices = 1;
   if (a.k_slices > 1 && (a.slice_partials == nullptr || a.slice_counters == nullptr)) return hipErrorInvalidValue;
   if (!TAIL) a.tail_cand = a.tail_slices = 0;
-  if (TAIL && (a.tail_cand < 1 || a.tail_cand >= a.n_cand || a.tail_slices < 2 || a.slice_partials == nullptr ||
-               a.slice_counters == nullptr))
+  if (TAIL && (a.tail_cand < 0 || a.tail_cand >= a.n_cand || (a.tail_cand == 0 && !a.has_base) || a.tail_slices < 2 ||
+               a.slice_partials == nullptr || a.slice_counters == nullptr))
     return hipErrorInvalidValue;
   // TAIL: the pass at x has no leading blocks, its tiles are sliced like the tail candidates'
   a.base_blocks = (a.has_base && !TAIL) ? (job_tiles(a.bj, BN) * a.k_slices + 7) / 8 * 8 : 0;
@@ -1165,12 +1170,12 @@ hipError_t launch_nt(const LayerArgs& a, hipStream_t stream, LaunchShape* shape)
     if (!(base_ok && cand_ok)) return hipErrorInvalidValue;
   }
   if constexpr (NW == 8 && Lds<BF16, DELTA, MB, NW>::DBUF) {
-    if (a.tail_cand > 0) {
+    if (a.tail_slices >= 2) {
       if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, 1, false, true>(a, stream, shape);
       return launch_inst<BF16, DELTA, MB, NW, false, 1, false, true>(a, stream, shape);
     }
   }
-  if (a.tail_cand > 0) return hipErrorInvalidValue;   // planned for a launch shape that has no sliced tail
+  if (a.tail_slices >= 2) return hipErrorInvalidValue;   // planned for a launch shape that has no sliced tail
   if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream, shape);
   if constexpr (BF16 && NW > 1 && Lds<BF16, DELTA, MB, NW, true>::DBUF) {
     if (launch_ring_ok(a)) return launch_inst<BF16, DELTA, MB, NW, true, 1, true>(a, stream, shape);
