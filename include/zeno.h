@@ -274,7 +274,8 @@ typedef struct {
   int32_t k_split;    /* waves that share one feature tile and split the input width: 1, 2 or 4 */
   int32_t streaming;  /* 1: rows read with non-temporal loads (line-aligned layout), 0: plain loads,
                          2: non-temporal loads on a column grid shifted to the lines of each candidate's rows
-                            (16-byte aligned dense rows, bf16 forward) */
+                            (16-byte aligned dense rows, bf16 forward), 3: the same for rows that are only 8-byte
+                            aligned (d mod 4 = 2) */
   int32_t row_blocks; /* 32-sample accumulator blocks per wave: 1, 2 or 4 */
   int32_t merged;     /* 1: the launch carries the candidates' layer AND the pass at x through another layer */
   int32_t second;     /* 1: candidates with the second matrix product (layers after the first) */

@@ -200,7 +200,7 @@ int layer_tail_slices(const LayerArgs& a, bool bf16, bool delta, int MB, int* n_
   *n_main_out = a.n_cand;
   if (a.n_cand <= 0 || launch_nw_for(a) != 8 || a.slice_partials == nullptr || a.slice_counters == nullptr) return 0;
   if (!wide_double_buffered(bf16, delta, MB)) return 0;
-  if (bf16 && !launch_lines_aligned(a) && launch_ring_ok(a)) return 0;   // this launch takes the shifted grid
+  if (bf16 && !launch_lines_aligned(a) && launch_ring_kind(a) != 0) return 0;   // this launch takes the shifted grid
   const long long slots = (long long)compute_units() * wgs_per_cu(bf16, delta, MB, 8);
   const int tiles8 = job_tiles(a.cj, 256);
   const long long full = (long long)tiles8 * a.n_cand / slots * slots;

@@ -243,6 +243,38 @@ __device__ inline void load_tile_edge(f32x4 (&u)[8], const float* __restrict__ U
   }
 }
 
+// The same for rows that are only 8-byte aligned (the shift sigma and K are even): a lane's four columns may be
+// half inside the row, so each half is loaded (64 bits) and masked on its own; a half that lies outside reads
+// the row's first or last two elements instead.
+template <int MODE, bool NT>
+__device__ inline void load_tile_edge2(f32x4 (&u)[8], const float* __restrict__ Urow0, int kfirst, int row0, int N, int K,
+                                       int lane) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef f32x2 f32x2_a4 __attribute__((aligned(4)));
+  const int rsub = lane >> 4, k = kfirst + ((lane & 15) << 2);
+  const bool ok0 = k >= 0 && k < K, ok1 = k + 2 >= 0 && k + 2 < K;
+  const int k0 = k < 0 ? 0 : (k < K ? k : K - 2);
+  const int k1 = k + 2 < 0 ? 0 : (k + 2 < K ? k + 2 : K - 2);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int row = row0 + 4 * j + rsub;
+    const int rel = ((MODE == 2 && row >= N) ? N - 1 : row) - row0;
+    const float* p = Urow0 + (long long)rel * K;
+    f32x2 a, b;
+    if (NT) {
+      a = __builtin_nontemporal_load(reinterpret_cast<const f32x2_a4*>(p + k0));
+      b = __builtin_nontemporal_load(reinterpret_cast<const f32x2_a4*>(p + k1));
+    } else {
+      a = *reinterpret_cast<const f32x2_a4*>(p + k0);
+      b = *reinterpret_cast<const f32x2_a4*>(p + k1);
+    }
+    u[j][0] = ok0 ? a[0] : 0.f;
+    u[j][1] = ok0 ? a[1] : 0.f;
+    u[j][2] = ok1 ? b[0] : 0.f;
+    u[j][3] = ok1 ? b[1] : 0.f;
+  }
+}
+
 // Staging ring of the shifted column grid (bf16): two staging tiles of the ordinary layout, the first for
 // the columns whose bit 6 is clear, the second for the others.  A tile of the shifted grid starts sigma
 // columns before a multiple of 64, so its first sigma columns go to one half and the rest to the other.
@@ -268,6 +300,36 @@ __device__ inline void stage_ring(const f32x4 (&u)[8], unsigned char* st, const 
   for (int i = 0; i < 8; ++i) {
     const bf16x4 h = __builtin_convertvector(u[i], bf16x4);
     *reinterpret_cast<bf16x4*>(st + (ring_w[i] ^ flip)) = h;
+  }
+}
+
+// Rows that are only 8-byte aligned: sigma is even, so the two column pairs of a lane's four may fall into
+// different 8-byte pieces, 16-byte segments or halves of the ring; each pair is written on its own (32 bits).
+// The byte offset of a pair for row 4 i + lane / 16 is its offset for row lane / 16 exclusive-or a constant:
+// the row bits (i * 512) and the swizzle bits ((2 i mod 8) * 16) of i touch no bit that the lane's part sets
+// differently, so two registers hold the offsets of all eight rows.
+__device__ inline void ring_offsets2(unsigned (&ring_p)[2], int lane, int sigma) {
+  const int rsub = lane >> 4, kq = lane & 15;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int t = 4 * kq + 2 * p;                       // first column of the pair inside the tile
+    const int col = (t - sigma) & 63;                   // column inside its block of 64
+    const unsigned half = t < sigma ? 4096u : 0u;       // columns before the tile's own block of 64
+    ring_p[p] = half + rsub * 128 + ((((col >> 3) ^ (rsub >> 1)) & 7) << 4) + ((col & 7) << 1);
+  }
+}
+template <bool ODD>
+__device__ inline void stage_ring2(const f32x4 (&u)[8], unsigned char* st, const unsigned (&ring_p)[2]) {
+  unsigned flip = ODD ? 4096u : 0u;
+  asm volatile("" : "+s"(flip));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const bf16x4 h = __builtin_convertvector(u[i], bf16x4);
+    const unsigned ci = (unsigned)(i * 512) | (unsigned)(((2 * i) & 7) << 4);
+    const bf16x2 lo = {h[0], h[1]}, hi = {h[2], h[3]};
+    *reinterpret_cast<bf16x2*>(st + (ring_p[0] ^ ci ^ flip)) = lo;
+    *reinterpret_cast<bf16x2*>(st + (ring_p[1] ^ ci ^ flip)) = hi;
   }
 }
 
@@ -304,7 +366,7 @@ __device__ inline void lds_dma16(const unsigned char* src, unsigned char* dst) {
 // LDS layout of a workgroup: [activation chunk buffers (one or two)] [one staging
 // tile per wave].  (Nothing else: with 4 row blocks, bf16 operands, the second product and
 // four waves the layout is exactly 80 KB, and two such workgroups share a compute unit.)
-template <bool BF16, bool DELTA, int MB, int NW, bool RING = false>
+template <bool BF16, bool DELTA, int MB, int NW, int RING = 0>
 struct Lds {
   using T = Tr<BF16>;
   static constexpr int A_BYTES = MB * T::CH_BYTES;            // one operand, one chunk
@@ -338,7 +400,7 @@ struct Lds {
 // round of resident slots would run that round at a fraction of the chip; cut into slices the same tiles are
 // several times as many workgroups, each a fraction as long.  The slices of a tile hand their partial accumulators
 // over through memory as the K slices of one-wave tiles do (last workgroup to arrive adds them in slice order).
-template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS, bool RING = false, bool TAIL = false>
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS, int RING = 0, bool TAIL = false>
 __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) {
   static_assert(KS == 1 || NW == 1, "K is only split in one-tile workgroups");
   using T = Tr<BF16>;
@@ -431,8 +493,9 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // RING: columns between the line a row starts in and the row's first element (the same for all rows of the tile)
   const int sigma = RING ? __builtin_amdgcn_readfirstlane((int)((reinterpret_cast<uintptr_t>(Urow0) & 127) >> 2)) : 0;
   const float* __restrict__ Uring = Urow0 - sigma;   // tile j of the shifted grid starts at Uring + 64 j
-  unsigned ring_w[8];
-  if constexpr (RING) ring_offsets(ring_w, lane, sigma);
+  unsigned ring_w[RING == 1 ? 8 : 1], ring_p[2];
+  if constexpr (RING == 1) ring_offsets(ring_w, lane, sigma);
+  if constexpr (RING == 2) ring_offsets2(ring_p, lane, sigma);
 
   const unsigned char* Ag = reinterpret_cast<const unsigned char*>(J.A_base);
   // The pass at x has no second product: its D operand is a harmless alias of H
@@ -523,8 +586,10 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
       for (int i = 0; i < 8; ++i) q += (u[i][0] * u[i][0] + u[i][1] * u[i][1]) + (u[i][2] * u[i][2] + u[i][3] * u[i][3]);
       nrm += (double)q;
     }
-    if constexpr (RING) {
+    if constexpr (RING == 1) {
       stage_ring<decltype(odd_c)::value>(u, stU, ring_w);
+    } else if constexpr (RING == 2) {
+      stage_ring2<decltype(odd_c)::value>(u, stU, ring_p);
     } else {
       stage_tile<BF16>(u, stU, lane);
     }
@@ -535,7 +600,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     if (j < n_chunks) {
       load_tile<MODE, NT>(u, Uring + (j << 6), lane_off, row0, j << 6, N, K, lane);
     } else if (sigma > 0) {
-      load_tile_edge<MODE, NT>(u, Urow0, 64 * j - sigma, row0, N, K, lane);
+      if constexpr (RING == 2) load_tile_edge2<MODE, NT>(u, Urow0, 64 * j - sigma, row0, N, K, lane);
+      else load_tile_edge<MODE, NT>(u, Urow0, 64 * j - sigma, row0, N, K, lane);
     } else {
       // rows that start on a line: the grid is not shifted and there is no tile behind the last chunk
       const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -671,7 +737,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     const float* Ufirst = Urow0 + (c_begin << 6);
     if constexpr (RING) {
       // tiles 0 and 1 of the shifted grid; tile 0 is staged here, every chunk then stages the tile after its own
-      load_tile_edge<MODE, NT>(u0, Urow0, -sigma, row0, N, K, lane);
+      if constexpr (RING == 2) load_tile_edge2<MODE, NT>(u0, Urow0, -sigma, row0, N, K, lane);
+      else load_tile_edge<MODE, NT>(u0, Urow0, -sigma, row0, N, K, lane);
       load_ring(full_c, u1, 1);
       if (SECOND) {
         load_W(w0, 0);
@@ -1037,14 +1104,14 @@ __global__ void pack_features_kernel(const float* __restrict__ features, int n_r
 
 int job_tiles(const LayerJob& j, int BN) { return (cover_rows(j.N, j.last) + BN - 1) / BN; }
 
-template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1, bool RING = false, bool TAIL = false>
+template <bool BF16, bool DELTA, int MB, int NW, bool NT, int KS = 1, int RING = 0, bool TAIL = false>
 hipError_t launch_inst(LayerArgs a, hipStream_t stream, LaunchShape* shape) {
   constexpr int BN = 32 * NW;
   if (shape != nullptr) {
     shape->waves = NW;
     shape->k_split = KS;
     shape->k_slices = TAIL ? a.tail_slices : NW == 1 && a.k_slices > 1 ? a.k_slices : 1;
-    shape->streaming = RING ? 2 : NT ? 1 : 0;
+    shape->streaming = RING ? 1 + RING : NT ? 1 : 0;
     shape->row_blocks = MB;
   }
   constexpr int lds_bytes = Lds<BF16, DELTA, MB, NW, RING>::TOTAL * KS;
@@ -1140,12 +1207,28 @@ bool launch_lines_aligned(const LayerArgs& a) {
 
 // The shifted column grid serves rows that start 16-byte aligned but not on a line, all of them the same
 // distance past one: row lengths that are multiples of 64 columns, 16-byte aligned bases, pitches and blocks.
-bool job_ring_ok(const LayerJob& j) { return j.w_off % 4 == 0 && j.K % 64 == 0; }
-bool launch_ring_ok(const LayerArgs& a) {
-  bool ok = a.has_base || a.n_cand > 0;
-  if (a.n_cand > 0) ok = ok && reinterpret_cast<uintptr_t>(a.G) % 16 == 0 && a.ldg % 4 == 0 && job_ring_ok(a.cj);
-  if (a.has_base) ok = ok && reinterpret_cast<uintptr_t>(a.x) % 16 == 0 && job_ring_ok(a.bj);
-  return ok;
+// Returns 1 for that case, 2 where bases, pitches and blocks are only 8-byte aligned (d mod 4 = 2: every other row of
+// a dense G[m x d]; the staging then writes column pairs), 0 where neither holds.
+int launch_ring_kind(const LayerArgs& a) {
+  if (!a.has_base && a.n_cand <= 0) return 0;
+  auto kind = [](uintptr_t base, long long pitch, const LayerJob& j) {
+    if (j.K % 64 != 0) return 0;
+    if (base % 16 == 0 && pitch % 4 == 0 && j.w_off % 4 == 0) return 1;
+    if (base % 8 == 0 && pitch % 2 == 0 && j.w_off % 2 == 0) return 2;
+    return 0;
+  };
+  int k = 1;
+  if (a.n_cand > 0) {
+    const int kc = kind(reinterpret_cast<uintptr_t>(a.G), a.ldg, a.cj);
+    if (kc == 0) return 0;
+    if (kc > k) k = kc;
+  }
+  if (a.has_base) {
+    const int kb = kind(reinterpret_cast<uintptr_t>(a.x), 0, a.bj);
+    if (kb == 0) return 0;
+    if (kb > k) k = kb;
+  }
+  return k;
 }
 
 template <bool BF16, bool DELTA, int MB, int NW>
@@ -1177,8 +1260,10 @@ hipError_t launch_nt(const LayerArgs& a, hipStream_t stream, LaunchShape* shape)
   }
   if (a.tail_slices >= 2) return hipErrorInvalidValue;   // planned for a launch shape that has no sliced tail
   if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true>(a, stream, shape);
-  if constexpr (BF16 && NW > 1 && Lds<BF16, DELTA, MB, NW, true>::DBUF) {
-    if (launch_ring_ok(a)) return launch_inst<BF16, DELTA, MB, NW, true, 1, true>(a, stream, shape);
+  if constexpr (BF16 && NW > 1 && Lds<BF16, DELTA, MB, NW, 1>::DBUF) {
+    const int ring = launch_ring_kind(a);
+    if (ring == 1) return launch_inst<BF16, DELTA, MB, NW, true, 1, 1>(a, stream, shape);
+    if (ring == 2) return launch_inst<BF16, DELTA, MB, NW, true, 1, 2>(a, stream, shape);
   }
   return launch_inst<BF16, DELTA, MB, NW, false>(a, stream, shape);
 }

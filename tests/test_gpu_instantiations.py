@@ -92,7 +92,10 @@ def test_wide_layers_all_rows(B, fwd, n_r, row_align):
     shapes = _run(B, w, s_ref, s_exact, scale, row_align)
     print(f"\n  wide {fwd} n_r={n_r} align={row_align}: {shapes}")
     cand = [s for s in shapes if s[0] == "layer_cand"]
-    assert all(s[5] == (row_align == 32) for s in cand)                         # streaming loads iff line-aligned
+    # streaming loads on line-aligned rows; dense rows (8-byte aligned here) take the shifted column grid in the
+    # wide bf16 workgroups and plain loads elsewhere
+    for s in cand:
+        assert s[5] == (1 if row_align == 32 else 3 if (fwd == "bf16" and s[3] >= 4) else 0), cand
     assert all(s[6] == {32: 1, 64: 2, 128: 4}[n_r] for s in cand)
     assert all(s[3] >= 4 for s in cand if s[1] < 2), cand                       # the wide layers run in wide workgroups
 
@@ -116,6 +119,36 @@ def test_dense_rows_on_the_shifted_grid(B, n_r, offset_floats):
     print(f"\n  shifted grid n_r={n_r} offset={offset_floats}: {shapes}")
     cand = [s for s in shapes if s[0] == "layer_cand" and s[3] >= 4]
     assert cand and all(s[5] == 2 for s in cand), shapes
+
+
+@pytest.mark.parametrize("offset_floats", [0, 2])
+@pytest.mark.parametrize("n_r", [32, 64, 128])
+def test_dense_rows_eight_byte_aligned_on_the_shifted_grid(B, n_r, offset_floats):
+    """d mod 4 = 2: every other row of a dense G[m x d] is only 8-byte aligned.  The shifted column grid then
+    stages a lane's four columns as two pairs, and the tiles at the ends of a row are loaded and masked in
+    halves.  With the matrix 8 bytes past the start of its allocation it is the even rows, the first
+    candidate's included, that are 8-byte aligned."""
+    assert WL.num_params(WIDE, True) % 4 == 2
+    w, s_ref, s_exact, scale = _workload(("wide", "bf16", n_r), WIDE, 64, 20, n_r, "bf16", 12, 8)
+    shapes = _run(B, w, s_ref, s_exact, scale, 1, offset_floats)
+    print(f"\n  shifted grid, 8-byte rows, n_r={n_r} offset={offset_floats}: {shapes}")
+    cand = [s for s in shapes if s[0] == "layer_cand" and s[3] >= 4]
+    assert cand and all(s[5] == 3 for s in cand), shapes
+
+
+ODD_D = [1024, 2048, 1024, 11]
+
+
+@pytest.mark.parametrize("n_r", [32, 64, 128])
+def test_dense_rows_four_byte_aligned(B, n_r):
+    """d odd: the rows of a dense G[m x d] are only 4-byte aligned, no column grid lines up with the memory
+    lines and the wide bf16 workgroups read them with plain 128-bit loads."""
+    assert WL.num_params(ODD_D, True) % 2 == 1
+    w, s_ref, s_exact, scale = _workload(("odd", n_r), ODD_D, 64, 20, n_r, "bf16", 12, 8)
+    shapes = _run(B, w, s_ref, s_exact, scale, 1)
+    print(f"\n  four-byte aligned rows n_r={n_r}: {shapes}")
+    cand = [s for s in shapes if s[0] == "layer_cand" and s[3] >= 4]
+    assert cand and all(s[5] == 0 for s in cand), shapes
 
 
 def test_pass_at_x_rides_in_a_launch_on_the_shifted_grid(B):
@@ -153,14 +186,14 @@ def test_pass_at_x_rides_in_an_eight_wave_launch(B, fwd):
     assert any(s[3] == 8 for s in merged), shapes
 
 
-@pytest.mark.parametrize("row_align", [32, 1])
-@pytest.mark.parametrize("fwd,n_r", [("bf16", 64), ("bf16", 128), ("bf16", 32), ("fp32", 32), ("fp32", 64)])
+@pytest.mark.parametrize("fwd,n_r,row_align", [("bf16", 64, 32), ("bf16", 128, 32), ("bf16", 32, 32), ("fp32", 32, 32),
+                                               ("fp32", 32, 1), ("fp32", 64, 32), ("fp32", 64, 1)])
 def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align):
     """36 candidates on 2048-wide layers are 288 eight-wave workgroups: one full round of 256 and a round that
     would be one-eighth full.  The tiles of candidates 32..35 and of the pass at x through the next layer run
     as K slices at the end of the launch (partial accumulators handed over through memory, partial norms in a
     range of slots of their own).  All rows compared; the launch records must name the sliced tail.
-    d mod 4 = 2: the dense rows are 8-byte aligned and take plain loads."""
+    (Dense rows: fp32 only, which reads them with plain loads; dense bf16 rows take the shifted column grid.)"""
     w, s_ref, s_exact, scale = _workload(("tail", fwd, n_r), [1024, 2048, 2048, 10], 36, 10, n_r, fwd, 6, 4)
     shapes = _run(B, w, s_ref, s_exact, scale, row_align)
     print(f"\n  sliced tail {fwd} n_r={n_r} align={row_align}: {shapes}")
@@ -178,12 +211,13 @@ def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align):
     assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("fwd,n_r,dims", [("bf16", 64, [1024, 2048, 2048, 12]), ("bf16", 128, [1024, 2048, 2048, 12])])
+@pytest.mark.parametrize("fwd,n_r,dims", [("bf16", 64, [1024, 2048, 2048, 12]), ("bf16", 128, [1024, 2048, 2048, 12]),
+                                          ("bf16", 64, [1024, 2048, 2048, 10])])
 def test_last_round_of_a_launch_as_one_wave_tiles(B, fwd, n_r, dims):
     """Where the eight-wave workgroups cannot slice their tail (dense 16-byte aligned rows on the shifted column
     grid) the launch of such a layer is cut in two: candidates 0..31 in eight-wave workgroups, candidates 32..35 as one-wave tiles (with the pass
     at x through the next layer), each half with its own range of partial-norm slots."""
-    w, s_ref, s_exact, scale = _workload(("split", fwd, n_r), dims, 36, 10, n_r, fwd, 6, 4)
+    w, s_ref, s_exact, scale = _workload(("split", fwd, n_r, dims[-1]), dims, 36, 10, n_r, fwd, 6, 4)
     shapes = _run(B, w, s_ref, s_exact, scale, 1)
     print(f"\n  split {fwd} n_r={n_r}: {shapes}")
     halves = [s for s in shapes if s[0] == "layer_cand" and s[1] == 1]
@@ -210,10 +244,11 @@ def test_zz_which_instantiations_ran(B):
                     missing.append((fwd, second, waves))
         if not any(s[0] == fwd and s[3] > 1 for s in SEEN):
             missing.append((fwd, "k_split"))
-    for second in (0, 1):      # the shifted column grid (bf16 only)
+    for second in (0, 1):      # the shifted column grid (bf16 only): 16-byte aligned rows (2), 8-byte aligned rows (3)
         for mb in (1, 2, 4):
-            if not any(s[0] == "bf16" and s[1] == second and s[2] in (4, 8) and s[4] == 2 and s[5] == mb for s in SEEN):
-                missing.append(("bf16", second, "4|8 waves", "shifted grid", mb))
+            for kind in (2, 3):
+                if not any(s[0] == "bf16" and s[1] == second and s[2] in (4, 8) and s[4] == kind and s[5] == mb for s in SEEN):
+                    missing.append(("bf16", second, "4|8 waves", "shifted grid", kind, mb))
     print("\n  launch shapes seen:", sorted(SEEN))
     assert not missing, missing
 
