@@ -195,8 +195,7 @@ class Runner:
         per, per_layer = {}, {}
         for r in recs:
             if r["kernel"].startswith("layer"):
-                # a layer whose candidates go in two launches (whole rounds of wide workgroups, then the few others)
-                key = f"{r['kernel']}[{r['layer']}]" + (f"+{r['first_candidate']}" if r["first_candidate"] else "")
+                key = f"{r['kernel']}[{r['layer']}]"
                 e = per_layer.setdefault(key, [0, 0.0, 0.0, r])
                 e[0] += 1
                 e[1] += r["ms"]
@@ -242,7 +241,7 @@ def describe(cfg, w):
 
 def layer_table(per_layer):
     return {k: {"avg_ms": v[1] / v[0], "algorithmic_GBps": v[2] / v[1] / 1e6,
-                "shape": {key: v[3][key] for key in ("waves", "k_split", "k_slices", "streaming", "row_blocks", "merged", "second", "candidates")}}
+                "shape": {key: v[3][key] for key in ("waves", "k_split", "k_slices", "streaming", "row_blocks", "merged", "second", "tail_candidates")}}
             for k, v in per_layer.items()}
 
 

@@ -58,7 +58,7 @@ class _ProfileRecord(ctypes.Structure):
                 ("algorithmic_bytes", ctypes.c_double), ("waves", ctypes.c_int32), ("k_split", ctypes.c_int32),
                 ("streaming", ctypes.c_int32), ("row_blocks", ctypes.c_int32), ("merged", ctypes.c_int32),
                 ("second", ctypes.c_int32), ("k_slices", ctypes.c_int32),
-                ("first_candidate", ctypes.c_int32), ("candidates", ctypes.c_int32),
+                ("candidates", ctypes.c_int32),
                 ("tail_candidates", ctypes.c_int32)]
 
 
@@ -409,7 +409,7 @@ def profile_collect(max_records: int = 4096, detail: bool = False):
         return [dict(kernel=KERNEL_NAMES[r.kernel], layer=int(r.layer), ms=float(r.ms), bytes=float(r.algorithmic_bytes),
                      waves=int(r.waves), k_split=int(r.k_split), streaming=int(r.streaming),
                      row_blocks=int(r.row_blocks), merged=int(r.merged), second=int(r.second), k_slices=int(r.k_slices),
-                     first_candidate=int(r.first_candidate), candidates=int(r.candidates),
+                     candidates=int(r.candidates),
                      tail_candidates=int(r.tail_candidates))
                 for r in (buf[i] for i in range(n))]
     return [(KERNEL_NAMES[buf[i].kernel], int(buf[i].layer), float(buf[i].ms), float(buf[i].algorithmic_bytes))

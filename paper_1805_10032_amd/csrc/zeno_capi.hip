@@ -150,12 +150,12 @@ struct ProfScope {
     e.rec.ms = 0.f;
     e.rec.algorithmic_bytes = bytes;
     e.rec.waves = e.rec.k_split = e.rec.streaming = e.rec.row_blocks = e.rec.merged = e.rec.second = e.rec.k_slices = 0;
-    e.rec.first_candidate = e.rec.candidates = e.rec.tail_candidates = 0;
+    e.rec.candidates = e.rec.tail_candidates = 0;
     (void)hipEventRecord(e.start, stream);
     g_prof.push_back(e);
     slot = (int)g_prof.size() - 1;
   }
-  void set_shape(const LaunchShape& s, bool merged, bool second, int first_candidate, int candidates, int tail) {
+  void set_shape(const LaunchShape& s, bool merged, bool second, int candidates, int tail) {
     if (slot < 0) return;
     std::lock_guard<std::mutex> lock(g_prof_mutex);
     if (slot >= (int)g_prof.size()) return;
@@ -167,7 +167,6 @@ struct ProfScope {
     r.merged = merged ? 1 : 0;
     r.second = second ? 1 : 0;
     r.k_slices = s.k_slices;
-    r.first_candidate = first_candidate;
     r.candidates = candidates;
     r.tail_candidates = tail;
   }
@@ -306,30 +305,17 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
       seq.push_back(c);
       continue;
     }
-    // Where that is not possible and the round would be mostly empty the launch is cut in two: the candidates
-    // that fill whole rounds, then the few others as one-wave tiles (which also carry the pass at x).
-    const int n_main = query_device ? layer_split_point(c.a, bf16, l > 0, p.MB) : m;
-    Launch rest = c;
-    if (n_main < m) {
-      c.a.n_cand = n_main;
-      c.a.has_base = 0;
-      c.bytes = layer_bytes(l) * n_main;
-      rest.a.cand0 = n_main;
-      rest.a.n_cand = m - n_main;
-      rest.bytes = layer_bytes(l) * (m - n_main);
-    }
-    Launch& carrier = n_main < m ? rest : c;   // the launch that may carry the pass at x through layer l + 1
     if (l + 1 < L) {
-      if (!query_device || layer_merge_pays(carrier.a, bf16, l > 0, p.MB)) {
-        carrier.bytes += layer_bytes(l + 1);
-        carrier.wt_layer = l + 1;
-        carrier.base_layer = l + 1;
+      if (!query_device || layer_merge_pays(c.a, bf16, l > 0, p.MB)) {
+        c.bytes += layer_bytes(l + 1);
+        c.wt_layer = l + 1;
+        c.base_layer = l + 1;
       } else {
         // the extra workgroups would cost a whole extra round: run the pass at x on its own first
         Launch b;
         b.a = common;
         b.a.has_base = 1;
-        b.a.bj = carrier.a.bj;
+        b.a.bj = c.a.bj;
         b.delta = false;
         b.kernel = ZENO_KERNEL_LAYER_BASE;
         b.layer = l + 1;
@@ -337,11 +323,10 @@ std::vector<Launch> layer_sequence(const zeno_model* model, const Plan& p, const
         b.wt_layer = l + 1;
         b.base_layer = l + 1;
         seq.push_back(b);
-        carrier.a.has_base = 0;
+        c.a.has_base = 0;
       }
     }
     seq.push_back(c);
-    if (n_main < m) seq.push_back(rest);
   }
   // Partial-norm slots of the candidate launches, now that it is known which of them also carry the pass at x
   // (that changes how a launch of one-wave tiles splits K): a launch gets feature tiles x K slices slots.
@@ -403,7 +388,7 @@ zeno_status_t score_enqueue(const zeno_model* model, const Plan& p, const float*
       ProfScope ps(l.kernel, l.layer, l.bytes, stream);
       LaunchShape shape;
       ZENO_TRY(launch_layer(l.a, bf16, l.delta, p.MB, stream, &shape));
-      ps.set_shape(shape, l.a.n_cand > 0 && l.a.has_base, l.a.n_cand > 0 && l.delta, l.a.cand0, l.a.n_cand, l.a.tail_cand);
+      ps.set_shape(shape, l.a.n_cand > 0 && l.a.has_base, l.a.n_cand > 0 && l.delta, l.a.n_cand, l.a.tail_cand);
     }
     ProfScope ps(ZENO_KERNEL_LOSS, 0, 4.0 * (m + 1) * rows * C, stream);
     ZENO_TRY(launch_loss(reinterpret_cast<const float*>(ws + p.off_z0[L - 1]), dZ, batch->labels, batch->targets,

@@ -69,9 +69,7 @@ struct LayerArgs {
   const float* G;       // [m x d]
   const float* x;       // [d]
   long long ldg;        // floats between consecutive rows of G
-  int n_cand;           // candidates in this launch (0, m, or a part of them)
-  int cand0;            // host side only: index of the launch's first candidate.  launch_layer moves the per-candidate
-                        // pointers (G, D_cand, dZ, Dl_cand, norm_partials) there, the kernel numbers its candidates from 0
+  int n_cand;           // candidates in this launch (0 or m)
   int has_base;         // 1: the launch also runs the pass at x through bj
   int base_blocks;      // leading block indices reserved for the pass at x (multiple of 8)
   int n_r;              // valid samples (rows) in this pass
@@ -139,7 +137,6 @@ struct LaunchShape {
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream,
                         LaunchShape* shape = nullptr);
 bool layer_merge_pays(const LayerArgs& a, bool bf16, bool delta, int MB);  // run a.bj inside the candidates' launch?
-int layer_split_point(const LayerArgs& a, bool bf16, bool delta, int MB);   // candidates of the first of two launches, or n_cand
 // K slices for the tiles of the last (n_cand - *n_main) candidates of an eight-wave launch, or 0: no sliced tail
 int layer_tail_slices(const LayerArgs& a, bool bf16, bool delta, int MB, int* n_main);
 int layer_tiles(const LayerArgs& a, bool bf16, bool delta, int MB);   // partial-norm slots per candidate the launch fills

@@ -132,7 +132,7 @@ LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, in
   }
   if (a.n_cand > 0) {
     const LayerJob& j = a.cj;
-    if (j.last) e.dz_floats = (long long)(a.cand0 + a.n_cand) * a.n_r * j.N;
+    if (j.last) e.dz_floats = (long long)a.n_cand * a.n_r * j.N;
     else e.d_bytes_per_cand = tiled_bytes(j.Np);
     e.norm_slots = job_tiles(j, 32 * NW);
   }
@@ -153,31 +153,6 @@ LayerExtents layer_extents(const LayerArgs& a, bool bf16, bool delta, int MB, in
   return e;
 }
 
-// Candidates of a launch that should go first, in a launch of their own, so that its eight-wave workgroups fill
-// every round of resident slots exactly; the others follow in a second launch of one-wave tiles with K split over
-// the waves (and carry the pass at x, if the launch has one).  Returns a.n_cand when the launch stays whole.
-// A candidate launch whose last round is mostly empty runs that round at a fraction of the chip: workload 4's
-// 2048-wide layers (100 candidates x 8 tiles = 3.125 rounds of 256) take 3.47 us per candidate either way (eight
-// waves, or four waves at 3.125 rounds of 512), against 3.0 us for 96 or 128 candidates.  The few candidates of
-// the last round cost far less as one-wave tiles spread over all compute units (4 candidates: 38 us, against
-// 58 us for what they add to the whole launch), but only while those tiles are a single round themselves
-// (8 candidates, two rounds of four-wave K-split workgroups: 66 us, no gain).
-int layer_split_point(const LayerArgs& a, bool bf16, bool delta, int MB) {
-  if (a.n_cand <= 0 || launch_nw_for(a) != 8) return a.n_cand;
-  const long long slots = (long long)compute_units() * wgs_per_cu(bf16, delta, MB, 8);
-  const int tiles8 = job_tiles(a.cj, 256);
-  const long long wgs = (long long)tiles8 * a.n_cand;
-  const long long full = wgs / slots * slots;
-  const int n_main = (int)(full / tiles8), rest = a.n_cand - n_main;
-  if (n_main <= 0 || rest <= 0 || full % tiles8 != 0) return a.n_cand;
-  // the rest as one-wave tiles with K split over the waves of a workgroup: one round of them at most
-  const int kw = ks_waves(bf16, delta, MB);
-  if (kw < 2 || (a.cj.Kp >> 6) < 2 * kw || (a.has_base && (a.bj.Kp >> 6) < 2 * kw)) return a.n_cand;
-  const long long rest_wgs = (long long)job_tiles(a.cj, 32) * rest;
-  if (rest_wgs > (long long)compute_units() * wgs_per_cu(bf16, delta, MB, 1, kw)) return a.n_cand;
-  return n_main;
-}
-
 // Does the eight-wave workgroup of this kind double-buffer its activation chunks (the sliced tail needs it)?
 static bool wide_double_buffered(bool bf16, bool delta, int MB) {
   auto pick = [&](auto mb) {
@@ -194,13 +169,11 @@ static bool wide_double_buffered(bool bf16, bool delta, int MB) {
 // into K slices, as many as bring their workgroups to about one round: the round then lasts a fraction of a whole
 // tile's time, and the slices start as soon as slots free up behind the whole tiles.  Workload 4's 2048-wide layers
 // (100 candidates x 8 tiles = 3.125 rounds of 256): candidates 96..99 and the pass at x are 40 tiles, cut six ways.
-// Not for launches on the shifted column grid (its tiles are staged one ahead from column 0) and not where the
-// workgroup is single-buffered; those fall back to layer_split_point.
+// Not where the workgroup is single-buffered.
 int layer_tail_slices(const LayerArgs& a, bool bf16, bool delta, int MB, int* n_main_out) {
   *n_main_out = a.n_cand;
   if (a.n_cand <= 0 || launch_nw_for(a) != 8 || a.slice_partials == nullptr || a.slice_counters == nullptr) return 0;
   if (!wide_double_buffered(bf16, delta, MB)) return 0;
-  if (bf16 && !launch_lines_aligned(a) && launch_ring_kind(a) != 0) return 0;   // this launch takes the shifted grid
   const long long slots = (long long)compute_units() * wgs_per_cu(bf16, delta, MB, 8);
   const int tiles8 = job_tiles(a.cj, 256);
   const long long full = (long long)tiles8 * a.n_cand / slots * slots;
@@ -262,16 +235,6 @@ hipError_t launch_pack_features(const float* features, int n_r, int K, int Kp, i
 hipError_t launch_layer(const LayerArgs& a, bool bf16, bool delta, int MB, hipStream_t stream, LaunchShape* shape) {
   const int NW = nw_for(a, bf16, delta, MB);
   LayerArgs b = a;
-  if (a.cand0 > 0) {
-    // a launch over candidates cand0 .. cand0 + n_cand - 1: everything the kernel indexes by candidate moves there
-    const long long c0 = a.cand0;
-    b.G = a.G + c0 * a.ldg;
-    if (a.D_cand != nullptr) b.D_cand = reinterpret_cast<const unsigned char*>(a.D_cand) + c0 * a.A_stride;
-    if (a.Dl_cand != nullptr) b.Dl_cand = reinterpret_cast<unsigned char*>(a.Dl_cand) + c0 * a.H_stride;
-    if (a.dZ != nullptr) b.dZ = a.dZ + c0 * a.n_r * a.cj.N;
-    if (a.norm_partials != nullptr) b.norm_partials = a.norm_partials + c0 * a.P;
-    b.cand0 = 0;
-  }
   const KPlan kp = layer_k_plan(a, bf16, delta, MB, NW, true);
   b.k_waves = kp.k_waves;
   b.k_slices = kp.k_slices;

@@ -405,7 +405,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   static_assert(KS == 1 || NW == 1, "K is only split in one-tile workgroups");
   using T = Tr<BF16>;
   using LD = Lds<BF16, DELTA, MB, NW, RING>;
-  static_assert(!TAIL || (NW == 8 && KS == 1 && !RING && LD::DBUF), "sliced tails exist for eight-wave workgroups on the plain column grid");
+  static_assert(!TAIL || (NW == 8 && KS == 1 && LD::DBUF), "sliced tails exist for double-buffered eight-wave workgroups");
   static_assert(!RING || (BF16 && KS == 1 && NW > 1 && LD::DBUF), "the shifted grid exists for wide bf16 workgroups with double buffers");
   static_assert(KS == 1 || LD::DBUF, "the single-buffer loop has workgroup barriers, which waves with different K ranges cannot share");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];
@@ -572,7 +572,9 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
 
   // A weight tile that has arrived in registers: rows beyond the matrix are discarded, its share of
   // ||u||^2 is taken, and it is converted and staged (RING: as an even or odd tile of the shifted grid).
-  auto take_tile = [&](auto full_c, auto odd_c, f32x4 (&u)[8]) __attribute__((always_inline)) {
+  // count: the tile's share of ||u||^2 belongs to this workgroup (a K slice on the shifted grid also stages the
+  // first tile of the next slice, which that slice counts).
+  auto take_tile = [&](auto full_c, auto odd_c, f32x4 (&u)[8], bool count) __attribute__((always_inline)) {
     constexpr int MODE = decltype(full_c)::value;
     if (MODE == 2) {
       // rows beyond the matrix were read from row N-1: discard them
@@ -580,7 +582,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
 #pragma unroll
       for (int i = 0; i < 8; ++i) u[i] = (row0 + 4 * i + (lane >> 4) < N) ? u[i] : zero;
     }
-    if (do_norm) {
+    if (do_norm && count) {
       float q = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) q += (u[i][0] * u[i][0] + u[i][1] * u[i][1]) + (u[i][2] * u[i][2] + u[i][3] * u[i][3]);
@@ -631,13 +633,15 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     // is a compile-time constant; waves that split K may start anywhere
     const int buf = DBUF ? (NW > 1 ? (ODD ? 1 : 0) : (c & 1)) : 0;
     // RING: u holds tile c + 1 of the shifted grid, staged one chunk ahead of the products
-    take_tile(full_c, std::integral_constant<bool, !ODD>{}, u);
+    take_tile(full_c, std::integral_constant<bool, !ODD>{}, u, !(RING && TAIL) || c + 1 < c_end || c_end == n_chunks);
     if (DBUF) {
       // copies(c) were issued before U(c+1) [8 loads] and W(c+1) [WREGS loads]; the
       // last chunk has no such loads behind its copies and waits for everything
       // (the stores of the pass at x, which writes W in operand order, share the counter;
       // they can only make this wait longer, never let it pass early)
-      if (FULL && (STEADY || c + 1 < c_end)) {
+      // (shifted grid: the tile requested behind copies(c) is tile c + 2, which is not requested at all where it
+      // would lie wholly behind rows that start on a line; then the copies are the newest but WREGS loads)
+      if (FULL && (STEADY || (c + 1 < c_end && (!RING || c + 2 < n_chunks || sigma > 0)))) {
         wait_vmcnt<8 + (SECOND ? WREGS : 0)>();
       } else {
         wait_vmcnt<0>();
@@ -663,7 +667,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     }
     if constexpr (RING) {
       if (STEADY) load_tile<MODE, NT>(u, Uring + ((c + 3) << 6), lane_off, row0, (c + 3) << 6, N, K, lane);
-      else if (c + 3 <= n_chunks) load_ring(full_c, u, c + 3);
+      else if (c + 3 <= c_end) load_ring(full_c, u, c + 3);
     } else {
       if (STEADY || c + 2 < c_end) load_tile<MODE, NT>(u, Urow0 + ((c + 2) << 6), lane_off, row0, (c + 2) << 6, N, K, lane);
     }
@@ -736,16 +740,19 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     int c = c_begin;
     const float* Ufirst = Urow0 + (c_begin << 6);
     if constexpr (RING) {
-      // tiles 0 and 1 of the shifted grid; tile 0 is staged here, every chunk then stages the tile after its own
-      if constexpr (RING == 2) load_tile_edge2<MODE, NT>(u0, Urow0, -sigma, row0, N, K, lane);
+      // the first two tiles of the shifted grid (c is even: wide workgroups and their K slices start at even chunks);
+      // the first is staged here, every chunk then stages the tile after its own.  The products of chunk j read
+      // tiles j and j + 1, so a K slice that ends before the row does still needs tile c_end.
+      if (c > 0) load_tile<MODE, NT>(u0, Uring + (c << 6), lane_off, row0, c << 6, N, K, lane);
+      else if constexpr (RING == 2) load_tile_edge2<MODE, NT>(u0, Urow0, -sigma, row0, N, K, lane);
       else load_tile_edge<MODE, NT>(u0, Urow0, -sigma, row0, N, K, lane);
-      load_ring(full_c, u1, 1);
+      load_ring(full_c, u1, c + 1);
       if (SECOND) {
-        load_W(w0, 0);
-        if (1 < c_end) load_W(w1, 1);
+        load_W(w0, c);
+        if (c + 1 < c_end) load_W(w1, c + 1);
       }
-      take_tile(full_c, std::false_type{}, u0);
-      if (2 <= n_chunks) load_ring(full_c, u0, 2);
+      take_tile(full_c, std::false_type{}, u0, true);
+      if (c + 2 <= c_end) load_ring(full_c, u0, c + 2);
       // steady state: chunks whose tile three ahead lies fully inside the rows (c is even here)
       for (; c + 4 < c_end; c += 2) {
         chunk(full_c, base_c, std::true_type{}, std::false_type{}, u1, w0, c);
@@ -1254,8 +1261,13 @@ hipError_t launch_nt(const LayerArgs& a, hipStream_t stream, LaunchShape* shape)
   }
   if constexpr (NW == 8 && Lds<BF16, DELTA, MB, NW>::DBUF) {
     if (a.tail_slices >= 2) {
-      if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, 1, false, true>(a, stream, shape);
-      return launch_inst<BF16, DELTA, MB, NW, false, 1, false, true>(a, stream, shape);
+      if (launch_lines_aligned(a)) return launch_inst<BF16, DELTA, MB, NW, true, 1, 0, true>(a, stream, shape);
+      if constexpr (BF16 && Lds<BF16, DELTA, MB, NW, 1>::DBUF) {
+        const int ring = launch_ring_kind(a);
+        if (ring == 1) return launch_inst<BF16, DELTA, MB, NW, true, 1, 1, true>(a, stream, shape);
+        if (ring == 2) return launch_inst<BF16, DELTA, MB, NW, true, 1, 2, true>(a, stream, shape);
+      }
+      return launch_inst<BF16, DELTA, MB, NW, false, 1, 0, true>(a, stream, shape);
     }
   }
   if (a.tail_slices >= 2) return hipErrorInvalidValue;   // planned for a launch shape that has no sliced tail

@@ -62,8 +62,7 @@ def _run(B, w, s_ref, s_exact, scale, row_align, offset_floats=0):
         if r["kernel"] in ("layer_base", "layer_cand"):
             shape = (w.fwd, r["second"], r["waves"], r["k_split"], r["streaming"], r["row_blocks"], r["merged"])
             SEEN.add(shape)
-            shapes.append((r["kernel"], r["layer"]) + shape[1:] + (r["first_candidate"], r["candidates"],
-                                                                    r["tail_candidates"], r["k_slices"]))
+            shapes.append((r["kernel"], r["layer"]) + shape[1:] + (r["candidates"], r["tail_candidates"], r["k_slices"]))
     tol = SCORE_TOL[w.fwd]
     err = score_error(npy(s), s_ref, scale)
     assert np.all(err <= tol), (w.name, row_align, float(err.max()), int(err.argmax()), shapes)
@@ -186,22 +185,29 @@ def test_pass_at_x_rides_in_an_eight_wave_launch(B, fwd):
     assert any(s[3] == 8 for s in merged), shapes
 
 
-@pytest.mark.parametrize("fwd,n_r,row_align", [("bf16", 64, 32), ("bf16", 128, 32), ("bf16", 32, 32), ("fp32", 32, 32),
-                                               ("fp32", 32, 1), ("fp32", 64, 32), ("fp32", 64, 1)])
-def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align):
+TAIL_DIMS = {10: [1024, 2048, 2048, 10], 12: [1024, 2048, 2048, 12]}
+
+
+@pytest.mark.parametrize("fwd,n_r,row_align,classes", [
+    ("bf16", 64, 32, 10), ("bf16", 128, 32, 10), ("bf16", 32, 32, 10), ("fp32", 32, 32, 10), ("fp32", 32, 1, 10),
+    ("fp32", 64, 32, 10), ("fp32", 64, 1, 10),
+    # dense bf16 rows: the sliced tail on the shifted column grid, 8-byte (d mod 4 = 2) and 16-byte aligned rows
+    ("bf16", 32, 1, 10), ("bf16", 64, 1, 10), ("bf16", 128, 1, 10), ("bf16", 64, 1, 12), ("bf16", 128, 1, 12)])
+def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align, classes):
     """36 candidates on 2048-wide layers are 288 eight-wave workgroups: one full round of 256 and a round that
     would be one-eighth full.  The tiles of candidates 32..35 and of the pass at x through the next layer run
     as K slices at the end of the launch (partial accumulators handed over through memory, partial norms in a
-    range of slots of their own).  All rows compared; the launch records must name the sliced tail.
-    (Dense rows: fp32 only, which reads them with plain loads; dense bf16 rows take the shifted column grid.)"""
-    w, s_ref, s_exact, scale = _workload(("tail", fwd, n_r), [1024, 2048, 2048, 10], 36, 10, n_r, fwd, 6, 4)
+    range of slots of their own).  All rows compared; the launch records must name the sliced tail."""
+    w, s_ref, s_exact, scale = _workload(("tail", fwd, n_r, classes), TAIL_DIMS[classes], 36, 10, n_r, fwd, 6, 4)
     shapes = _run(B, w, s_ref, s_exact, scale, row_align)
     print(f"\n  sliced tail {fwd} n_r={n_r} align={row_align}: {shapes}")
     for layer in (0, 1):
         launches = [s for s in shapes if s[0] == "layer_cand" and s[1] == layer]
         assert len(launches) == 1 and launches[0][3] == 8 and launches[0][7] == 1, shapes          # eight waves, merged
-        assert launches[0][8:11] == (0, 36, 4) and launches[0][11] >= 2, shapes                    # tail of 4, sliced
-    assert [s[8:11] for s in shapes if s[0] == "layer_cand" and s[1] == 2] == [(0, 36, 0)], shapes
+        assert launches[0][8:10] == (36, 4) and launches[0][10] >= 2, shapes                       # tail of 4, sliced
+        if fwd == "bf16" and row_align == 1:
+            assert launches[0][5] == (3 if classes == 10 else 2), shapes                           # shifted grid
+    assert [s[8:10] for s in shapes if s[0] == "layer_cand" and s[1] == 2] == [(36, 0)], shapes
     # same scores from run to run: the slices are added in slice order whoever arrives last
     dev = torch.device("cuda", 0)
     mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
@@ -209,20 +215,6 @@ def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align):
     a = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
     b = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
     assert torch.equal(a, b)
-
-
-@pytest.mark.parametrize("fwd,n_r,dims", [("bf16", 64, [1024, 2048, 2048, 12]), ("bf16", 128, [1024, 2048, 2048, 12]),
-                                          ("bf16", 64, [1024, 2048, 2048, 10])])
-def test_last_round_of_a_launch_as_one_wave_tiles(B, fwd, n_r, dims):
-    """Where the eight-wave workgroups cannot slice their tail (dense 16-byte aligned rows on the shifted column
-    grid) the launch of such a layer is cut in two: candidates 0..31 in eight-wave workgroups, candidates 32..35 as one-wave tiles (with the pass
-    at x through the next layer), each half with its own range of partial-norm slots."""
-    w, s_ref, s_exact, scale = _workload(("split", fwd, n_r, dims[-1]), dims, 36, 10, n_r, fwd, 6, 4)
-    shapes = _run(B, w, s_ref, s_exact, scale, 1)
-    print(f"\n  split {fwd} n_r={n_r}: {shapes}")
-    halves = [s for s in shapes if s[0] == "layer_cand" and s[1] == 1]
-    assert [(s[8], s[9], s[3]) for s in halves] == [(0, 32, 8), (32, 4, 1)], shapes
-    assert [(s[8], s[9]) for s in shapes if s[0] == "layer_cand" and s[1] == 2] == [(0, 36)], shapes
 
 
 def test_zz_which_instantiations_ran(B):
