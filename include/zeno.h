@@ -204,7 +204,10 @@ zeno_status_t zeno_aggregate_update(const float* G, int64_t ldg, const float* sc
 zeno_status_t zeno_mean(const float* G, int64_t ldg, int32_t m, int64_t d, float* out, void* stream);
 
 /* Marginal median (Definition 4): out[j] = median_i G[i][j]; for even m the
- * midpoint of the two middle values.  UNSUPPORTED for m > 128. */
+ * midpoint of the two middle values (formed in float64, rounded once).  NaN entries
+ * sort above +inf.  Up to m = 128 the values of a column are sorted in registers; for
+ * 128 < m <= 1024 the median is found by rank selection on keys kept in LDS, which is
+ * several times slower per byte of G. */
 zeno_status_t zeno_median(const float* G, int64_t ldg, int32_t m, int64_t d, float* out, void* stream);
 
 /* Krum_b (Definition 5, the paper's main baseline): out = the row of G whose sum of squared

@@ -19,7 +19,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 
 SOURCES = ["zeno_capi.hip", "zeno_layer.hip", "zeno_layer_bf16_delta.hip", "zeno_layer_bf16_first.hip",
            "zeno_layer_f32_delta.hip", "zeno_layer_f32_first.hip", "zeno_loss.hip", "zeno_aggregate.hip",
-           "zeno_median.hip", "zeno_krum.hip", "zeno_conv.hip"]
+           "zeno_median.hip", "zeno_median_select.hip", "zeno_krum.hip", "zeno_conv.hip"]
 
 # Packed-fp32 instruction selection is switched off for all device code.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -837,8 +837,12 @@ zeno_status_t zeno_median(const float* G, int64_t ldg, int32_t m, int64_t d, flo
   if (G == nullptr || out == nullptr) return ZENO_ERR_INVALID_ARG;
   if (m < 1 || m > ZENO_MAX_CANDIDATES || d < 1 || ldg < d) return ZENO_ERR_INVALID_ARG;
   if (!aligned(G, 4) || !aligned(out, 4)) return ZENO_ERR_INVALID_ARG;
-  if (m > 128) return ZENO_ERR_UNSUPPORTED;
   ProfScope ps(ZENO_KERNEL_MEDIAN, 0, 4.0 * (double)d * (m + 1), reinterpret_cast<hipStream_t>(stream));
+  if (m > 128) {
+    // more rows than the sorting networks in registers hold: rank selection on keys kept in LDS
+    ZENO_TRY(launch_median_select(G, ldg, m, d, out, reinterpret_cast<hipStream_t>(stream)));
+    return ZENO_OK;
+  }
   ZENO_TRY(launch_median(G, ldg, m, d, out, reinterpret_cast<hipStream_t>(stream)));
   return ZENO_OK;
 }

@@ -168,7 +168,8 @@ hipError_t launch_masked_average(const float* G, long long ldg, const float* sco
 size_t krum_workspace_bytes(int m);
 hipError_t launch_krum(const float* G, long long ldg, int m, long long d, int b, float* out, int32_t* chosen,
                        float* scores_out, void* workspace, hipStream_t stream);
-hipError_t launch_median(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream);
+hipError_t launch_median(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream);          // m <= 128
+hipError_t launch_median_select(const float* G, long long ldg, int m, long long d, float* out, hipStream_t stream);   // m <= 1024
 
 // ---- convolutional models (zeno_conv.hip)
 // One 3 x 3 convolution (zero padding 1) as the kernel sees it.

@@ -90,7 +90,10 @@ def test_rows_only_four_byte_aligned(B):
 
 
 @pytest.mark.parametrize("m,d", [(1, 7), (2, 9), (3, 100), (4, 5), (7, 4099), (8, 64), (20, 7850), (21, 1000),
-                                 (33, 2049), (64, 3001), (100, 5002), (127, 300), (128, 515)])
+                                 (33, 2049), (64, 3001), (100, 5002), (127, 300), (128, 515),
+                                 # more than 128 rows: the median by rank selection in LDS
+                                 (129, 300), (130, 31), (200, 1000), (255, 64), (256, 4099), (513, 777), (1000, 2049),
+                                 (1023, 33), (1024, 130)])
 def test_mean_and_median_bit_exact(B, m, d):
     G = _rand_G(m, d, 31 * m + d, scale=3.0)
     Gd = G.cuda()
@@ -118,6 +121,31 @@ def test_median_every_m(B, row_align):
         assert np.array_equal(med[ok], ref[ok]), m
 
 
+@pytest.mark.parametrize("row_align", [1, 32])
+@pytest.mark.parametrize("m", [129, 192, 500, 1024])
+def test_median_by_selection_with_ties_and_nonfinite_entries(B, m, row_align):
+    """m > 128: ties (few distinct values, so the two middle keys are often equal), columns of one value,
+    NaN, +inf and -inf entries, a column that is NaN in more than half of its rows; dense and line-aligned rows."""
+    from tests._util import rows_to_gpu
+    d = 333
+    g = torch.Generator().manual_seed(7000 + m)
+    G = torch.randint(-3, 4, (m, d), generator=g).to(torch.float32) * 0.5
+    G[:, 1::4] = _rand_G(m, d, 7100 + m)[:, 1::4]
+    G[:, 2] = 1.25
+    G[m // 3, ::13] = float("inf")
+    G[m // 2, 4::17] = float("-inf")
+    G[1, 6::19] = float("nan")
+    G[: m // 2 + 2, 8] = float("nan")
+    G[: m // 2 + 2, 9] = float("inf")
+    G[: m // 2, 10] = float("-inf")
+    G[m // 2:, 10] = float("inf")
+    med = B.zeno_median(rows_to_gpu(B, G, row_align)).cpu().numpy()
+    ref = O.median(G.numpy()).astype(np.float32)
+    assert np.array_equal(np.isnan(med), np.isnan(ref))
+    ok = ~np.isnan(ref)
+    assert np.array_equal(med[ok], ref[ok])
+
+
 def test_median_with_nonfinite_entries(B):
     m, d = 6, 200
     G = _rand_G(m, d, 9)
@@ -140,9 +168,9 @@ def test_error_codes(B):
         with pytest.raises(B.ZenoError) as e:
             B.zeno_aggregate(G, s, bad_b, want_selected=False)
         assert e.value.status == 1
-    big = torch.zeros(129, 8, device="cuda")
+    big = torch.zeros(1025, 8, device="cuda")     # more candidates than any call accepts
     with pytest.raises(B.ZenoError) as e:
         B.zeno_median(big)
-    assert e.value.status == 2
+    assert e.value.status == 1
     with pytest.raises(ValueError):
         B.zeno_mean(torch.zeros(4, 8))          # host tensor: no silent CPU path
