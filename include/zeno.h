@@ -282,7 +282,8 @@ typedef struct {
   int32_t row_blocks; /* 32-sample accumulator blocks per wave: 1, 2 or 4 */
   int32_t merged;     /* 1: the launch carries the candidates' layer AND the pass at x through another layer */
   int32_t second;     /* 1: candidates with the second matrix product (layers after the first) */
-  int32_t k_slices;   /* workgroups that share one feature tile and split the input width (launches of one-wave tiles): 1..8 */
+  int32_t k_slices;   /* workgroups that share one feature tile and split the input width: 1..8 (launches of one-wave
+                         tiles: every tile; eight-wave launches: the tiles of the sliced tail, see tail_candidates) */
   int32_t candidates;      /* candidate launches: the rows of G the launch streams */
   int32_t tail_candidates; /* eight-wave launches: the last so many candidates' tiles (and the pass at x, if merged)
                               ran as k_slices K slices each at the end of the launch; 0: none */

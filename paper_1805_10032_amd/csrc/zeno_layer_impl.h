@@ -317,19 +317,29 @@ __device__ inline void ring_offsets2(unsigned (&ring_p)[2], int lane, int sigma)
     const unsigned half = t < sigma ? 4096u : 0u;       // columns before the tile's own block of 64
     ring_p[p] = half + rsub * 128 + ((((col >> 3) ^ (rsub >> 1)) & 7) << 4) + ((col & 7) << 1);
   }
+  // A 32-bit write is served 32 lanes at a time, i.e. two rows of the staging tile, and two adjacent rows (128 bytes
+  // apart, same swizzle) fall on the same banks when they write the same pair (same position inside the 16-byte
+  // segments).  The lanes of the odd rows therefore write their pairs in the other order (stage_ring2 swaps the
+  // data the same way): the two rows of a half-instruction then use different 4-byte positions of every segment.
+  if (rsub & 1) {
+    const unsigned t = ring_p[0];
+    ring_p[0] = ring_p[1];
+    ring_p[1] = t;
+  }
 }
 template <bool ODD>
-__device__ inline void stage_ring2(const f32x4 (&u)[8], unsigned char* st, const unsigned (&ring_p)[2]) {
+__device__ inline void stage_ring2(const f32x4 (&u)[8], unsigned char* st, const unsigned (&ring_p)[2], bool swap) {
   unsigned flip = ODD ? 4096u : 0u;
   asm volatile("" : "+s"(flip));
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const bf16x4 h = __builtin_convertvector(u[i], bf16x4);
     const unsigned ci = (unsigned)(i * 512) | (unsigned)(((2 * i) & 7) << 4);
-    const bf16x2 lo = {h[0], h[1]}, hi = {h[2], h[3]};
-    *reinterpret_cast<bf16x2*>(st + (ring_p[0] ^ ci ^ flip)) = lo;
-    *reinterpret_cast<bf16x2*>(st + (ring_p[1] ^ ci ^ flip)) = hi;
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 w = __builtin_bit_cast(u32x2, h);   // w[0]: columns 0, 1 of the lane's four; w[1]: columns 2, 3
+    // swap (the lanes of the odd rows): ring_p[0] is the offset of the second pair, ring_p[1] of the first
+    *reinterpret_cast<unsigned*>(st + (ring_p[0] ^ ci ^ flip)) = swap ? w[1] : w[0];
+    *reinterpret_cast<unsigned*>(st + (ring_p[1] ^ ci ^ flip)) = swap ? w[0] : w[1];
   }
 }
 
@@ -591,7 +601,7 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
     if constexpr (RING == 1) {
       stage_ring<decltype(odd_c)::value>(u, stU, ring_w);
     } else if constexpr (RING == 2) {
-      stage_ring2<decltype(odd_c)::value>(u, stU, ring_p);
+      stage_ring2<decltype(odd_c)::value>(u, stU, ring_p, (lane & 16) != 0);
     } else {
       stage_tile<BF16>(u, stU, lane);
     }

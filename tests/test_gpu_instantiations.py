@@ -191,6 +191,7 @@ TAIL_DIMS = {10: [1024, 2048, 2048, 10], 12: [1024, 2048, 2048, 12]}
 @pytest.mark.parametrize("fwd,n_r,row_align,classes", [
     ("bf16", 64, 32, 10), ("bf16", 128, 32, 10), ("bf16", 32, 32, 10), ("fp32", 32, 32, 10), ("fp32", 32, 1, 10),
     ("fp32", 64, 32, 10), ("fp32", 64, 1, 10),
+    ("bf16", 160, 32, 10),     # two passes over G (128 + 32 samples): the second finds the arrival counters at zero
     # dense bf16 rows: the sliced tail on the shifted column grid, 8-byte (d mod 4 = 2) and 16-byte aligned rows
     ("bf16", 32, 1, 10), ("bf16", 64, 1, 10), ("bf16", 128, 1, 10), ("bf16", 64, 1, 12), ("bf16", 128, 1, 12)])
 def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align, classes):
@@ -201,13 +202,16 @@ def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align, classes):
     w, s_ref, s_exact, scale = _workload(("tail", fwd, n_r, classes), TAIL_DIMS[classes], 36, 10, n_r, fwd, 6, 4)
     shapes = _run(B, w, s_ref, s_exact, scale, row_align)
     print(f"\n  sliced tail {fwd} n_r={n_r} align={row_align}: {shapes}")
+    passes = (n_r + 127) // 128
     for layer in (0, 1):
         launches = [s for s in shapes if s[0] == "layer_cand" and s[1] == layer]
-        assert len(launches) == 1 and launches[0][3] == 8 and launches[0][7] == 1, shapes          # eight waves, merged
-        assert launches[0][8:10] == (36, 4) and launches[0][10] >= 2, shapes                       # tail of 4, sliced
-        if fwd == "bf16" and row_align == 1:
-            assert launches[0][5] == (3 if classes == 10 else 2), shapes                           # shifted grid
-    assert [s[8:10] for s in shapes if s[0] == "layer_cand" and s[1] == 2] == [(36, 0)], shapes
+        assert len(launches) == passes, shapes
+        for one in launches:
+            assert one[3] == 8 and one[7] == 1, shapes                                             # eight waves, merged
+            assert one[8:10] == (36, 4) and one[10] >= 2, shapes                                   # tail of 4, sliced
+            if fwd == "bf16" and row_align == 1:
+                assert one[5] == (3 if classes == 10 else 2), shapes                               # shifted grid
+    assert [s[8:10] for s in shapes if s[0] == "layer_cand" and s[1] == 2] == [(36, 0)] * passes, shapes
     # same scores from run to run: the slices are added in slice order whoever arrives last
     dev = torch.device("cuda", 0)
     mdl = B.ZenoModel(w.dims, w.has_bias, w.loss, w.fwd)
@@ -215,6 +219,18 @@ def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align, classes):
     a = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
     b = B.zeno_score(mdl, w.x.to(dev), G, w.features.to(dev), w.gamma, w.rho, labels=w.labels.to(dev))
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("fwd,n_r,row_align", [("bf16", 64, 32), ("bf16", 64, 1), ("fp32", 32, 32)])
+def test_sliced_tail_on_a_wide_output_layer(B, fwd, n_r, row_align):
+    """A 2048-class output layer with 36 candidates: its launch has a sliced tail but carries no pass at x, and the
+    slices' last workgroups write the change of the logits instead of activations.  1100 inputs: the first layer's
+    K is ragged (no shifted grid there), the output layer's is not."""
+    w, s_ref, s_exact, scale = _workload(("tailout", fwd, n_r), [1100, 2048, 2048], 36, 10, n_r, fwd, 6, 4)
+    shapes = _run(B, w, s_ref, s_exact, scale, row_align)
+    print(f"\n  sliced tail, wide output layer {fwd} n_r={n_r} align={row_align}: {shapes}")
+    out = [s for s in shapes if s[0] == "layer_cand" and s[1] == 1]
+    assert len(out) == 1 and out[0][3] == 8 and out[0][7] == 0 and out[0][8:10] == (36, 4) and out[0][10] >= 2, shapes
 
 
 def test_zz_which_instantiations_ran(B):
