@@ -18,7 +18,8 @@
 // have norms of the size of their distances.  The second pass is decided on the device (a
 // flag in the workspace) and its kernels return at once when it is not needed.
 //
-// krum_gram_kernel<RB>: the m <= 32 RB rows are cut into RB row blocks.  A wave owns a
+// krum_gram_kernel<RB> (one or two row blocks, m <= 64; three and four row blocks: krum_gram_shared_kernel
+// below): the m <= 32 RB rows are cut into RB row blocks.  A wave owns a
 // contiguous range of 64-column chunks; per chunk it loads the RB tiles of 32 rows x 64
 // columns with coalesced 128-bit loads (rows at or beyond m read row m-1 and are
 // zeroed), passes each through its wave-private XOR-swizzled LDS tile to reach operand
@@ -41,17 +42,36 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 // h = bf16(x), m = bf16(x - h), l = bf16(x - h - m), round to nearest even each time;
 // both subtractions are exact.
 __device__ inline void split3(const f32x4& v0, const f32x4& v1, bf16x8& h, bf16x8& m, bf16x8& l) {
-  const f32x8 x = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-  h = __builtin_convertvector(x, bf16x8);
-  const f32x8 r1 = x - __builtin_convertvector(h, f32x8);
-  m = __builtin_convertvector(r1, bf16x8);
-  const f32x8 r2 = r1 - __builtin_convertvector(m, f32x8);
-  l = __builtin_convertvector(r2, bf16x8);
+  // Two floats at a time: one packed conversion gives both bf16 pieces in one register, and the pieces' float values
+  // (needed for the exact remainders) are that register shifted and masked, not converted a second time.
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const float x[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+  u32x4 hu, mu, lu;
+  auto pack = [](float a, float b) {
+    const f32x2 t = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
+  };
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float a = x[2 * i], b = x[2 * i + 1];
+    const unsigned hp = pack(a, b);
+    const float ra = a - __uint_as_float(hp << 16), rb = b - __uint_as_float(hp & 0xffff0000u);
+    const unsigned mp = pack(ra, rb);
+    const float sa = ra - __uint_as_float(mp << 16), sb = rb - __uint_as_float(mp & 0xffff0000u);
+    hu[i] = hp;
+    mu[i] = mp;
+    lu[i] = pack(sa, sb);
+  }
+  h = __builtin_bit_cast(bf16x8, hu);
+  m = __builtin_bit_cast(bf16x8, mu);
+  l = __builtin_bit_cast(bf16x8, lu);
 }
 
 // CENTER: second pass; runs only if *run_flag != 0 and subtracts row *center from every row.
 template <int RB, bool CENTER>
-__global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) void krum_gram_kernel(const float* __restrict__ G, long long ldg,
+__global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : 2) void krum_gram_kernel(const float* __restrict__ G, long long ldg,
                                                                     int m, long long d, float* __restrict__ partial,
                                                                     const int32_t* __restrict__ center,
                                                                     const int32_t* __restrict__ run_flag) {
@@ -137,7 +157,8 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) voi
     }
   };
 
-  if (RB <= 3) {
+  static_assert(RB <= 2, "three and four row blocks run krum_gram_shared_kernel");
+  {
     // one chunk ahead in registers: the loads of chunk c+1 fly while chunk c is multiplied
     if (c_begin < c_end) {
       f32x4 u0[RB][8], u1[RB][8];
@@ -154,12 +175,6 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) voi
         load_chunk(u1, c + 1);
         products(u1);
       }
-    }
-  } else {
-    for (long long c = c_begin; c < c_end; ++c) {
-      f32x4 u[RB][8];
-      load_chunk(u, c);
-      products(u);
     }
   }
 
@@ -182,6 +197,217 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : RB == 2 ? 2 : 1) voi
     }
   }
   if (wave == 0) {
+    // accumulator element j of lane (n, h): row 8 (j/4) + 4 h + j%4 of block a, column n of block b
+    float* out = partial + (long long)blockIdx.x * PAIRS * 1024;
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) out[p * 1024 + (8 * (j >> 2) + 4 * h + (j & 3)) * 32 + n] = acc[p][j];
+  }
+}
+
+// The Gram kernel for three and four row blocks (64 < m <= 128).  With every wave loading, staging, splitting and
+// multiplying its own chunks, and holding all RB (RB + 1) / 2 block products (up to 160 accumulator registers), only
+// one wave fits a SIMD and nothing overlaps its vector work and its matrix instructions.  Here the eight waves of a
+// workgroup work on ONE chunk at a time, in two roles, one wave of each role per SIMD:
+//  * waves 0..3 stage: wave t takes tile t of the chunk (the coalesced loads of krum_gram_kernel, requested four
+//    chunks ahead), brings it into operand order through its private swizzled tile, splits every float into its
+//    three bf16 pieces and writes the pieces, in operand order, to the chunk's shared buffer
+//    ([tile][piece][16-column step][64 lanes x 16 bytes], double-buffered: one barrier per chunk);
+//  * waves 4..7 multiply: wave 4 + s takes the 16-column step s of the chunk, reads the 3 RB operand fragments of
+//    that step once and issues the six matrix instructions of every block pair.
+// The vector ALU work of the staging wave and the matrix instructions of the multiplying wave of a SIMD run side by
+// side; each fragment crosses LDS once per chunk.  The four multiplying waves add their accumulators through LDS
+// at the end, in the fixed tree (0+2)+(1+3), and write the workgroup's partial Gram in the layout of krum_gram_kernel.
+// Two things in the staging waves matter as much as the split of roles: the loaded values are first touched when
+// their tile is staged (zeroing the rows beyond m right behind the load made every wave wait for the load it had
+// just requested), and the steady-state loop has no branch between requesting a tile and staging it four chunks
+// later (where paths with different numbers of loads meet, the compiler waits for all of them).
+// Measured (MI355X, d = 14.7 M): m = 72 / 96 / 100 / 128: 1.28 / 1.43 / 1.75 / 1.97 ms per Krum call, against
+// 1.91 / 1.95 / 2.0 / 2.5 ms with krum_gram_kernel<3 or 4>; staging alone runs at the memory's pace (1.35 ms for
+// m = 128, 5.6 TB/s), the products alone take 1.04 ms, and the barrier per chunk lets them overlap only in part.
+constexpr int kSharedWaves = 8;
+
+template <int RB>
+struct SharedGram {
+  static constexpr int PAIRS = RB * (RB + 1) / 2;
+  static constexpr int BUF_BYTES = RB * 3 * 4 * 1024;           // the pieces of one chunk
+  static constexpr int STAGE_OFF = 2 * BUF_BYTES;
+  static constexpr int TILE_BYTES = 32 * 64 * 4;
+  static constexpr int LDS_BYTES = STAGE_OFF + 4 * TILE_BYTES;
+  static_assert(2 * PAIRS * 16 * 64 * 4 <= LDS_BYTES, "the final reduction fits the buffers");
+};
+
+template <int RB, bool CENTER>
+__global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(const float* __restrict__ G, long long ldg, int m,
+                                                                             long long d, float* __restrict__ partial,
+                                                                             const int32_t* __restrict__ center,
+                                                                             const int32_t* __restrict__ run_flag) {
+  using SG = SharedGram<RB>;
+  constexpr int PAIRS = SG::PAIRS;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  if (CENTER && *run_flag == 0) return;   // uniform over the launch
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // The 64-column chunks are dealt round-robin to the workgroups: workgroups run at about the same pace, so at any
+  // time the chip reads a few contiguous stretches of every row (here c counts the chunks of this workgroup).
+  const long long n_chunks = (d + 63) / 64;
+  const long long c_end = (n_chunks - blockIdx.x + gridDim.x - 1) / gridDim.x;
+  const int n = lane & 31, h = lane >> 5;
+
+  // Both roles pass the same barriers: one after the first chunk is staged, one per chunk in the loop, five in the
+  // final reduction.
+  if (wave < 4) {
+    // ---- staging waves
+    const int t = wave;
+    const bool active = t < RB && c_end > 0;
+    const float* __restrict__ crow = CENTER ? G + (long long)(*center) * ldg : G;
+    unsigned char* st = lds + SG::STAGE_OFF + t * SG::TILE_BYTES;
+    const int rsub = lane >> 4, kq = (lane & 15) << 2;
+    // FULL: the caller knows that the chunk is complete (no branch on the way to the loads: the compiler counts
+    // the loads in flight exactly only along straight-line code, and waits for all of them wherever paths with
+    // different numbers of loads meet)
+    // (the loaded values are not touched here: rows at or beyond m, which read row m-1, are zeroed and the centre
+    // row is subtracted when the tile is staged, so that nothing waits for a load that has just been requested)
+    auto load_tile_rows = [&](auto full_c, f32x4 (&u)[8], f32x4& cv, long long c) __attribute__((always_inline)) {
+      const long long k0 = (blockIdx.x + c * gridDim.x) * 64;
+      const bool k_full = decltype(full_c)::value || k0 + 64 <= d;  // wave-uniform
+      if (CENTER) {
+        if (k_full) cv = *reinterpret_cast<const f32x4_a4*>(crow + k0 + kq);
+        else cv = load4_masked(crow + k0, kq, (int)(d - k0), true);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int row = 32 * t + 4 * j + rsub;
+        const int rc = row < m ? row : m - 1;
+        const float* p = G + (long long)rc * ldg + k0;
+        if (k_full) u[j] = load_stream4(p + kq);
+        else u[j] = load4_masked(p, kq, (int)(d - k0), true);
+      }
+    };
+    auto stage = [&](f32x4 (&u)[8], const f32x4& cv, int buf) __attribute__((always_inline)) {
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 8; ++j) u[j] = (32 * t + 4 * j + rsub < m) ? (CENTER ? u[j] - cv : u[j]) : zero;
+      stage_tile<false>(u, st, lane);
+      // per 16-column step s, lane (n, h) reads row n, columns 16 s + 8 h .. + 7 and splits them
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const unsigned char* row = st + n * 256;
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(row + ((((4 * s + 2 * h) ^ n) & 15) << 4));
+        const f32x4 v1 = *reinterpret_cast<const f32x4*>(row + ((((4 * s + 2 * h + 1) ^ n) & 15) << 4));
+        bf16x8 fh, fm, fl;
+        split3(v0, v1, fh, fm, fl);
+        unsigned char* dst = lds + buf * SG::BUF_BYTES + (t * 3 * 4 + s) * 1024 + lane * 16;
+        *reinterpret_cast<bf16x8*>(dst) = fh;
+        *reinterpret_cast<bf16x8*>(dst + 4 * 1024) = fm;
+        *reinterpret_cast<bf16x8*>(dst + 8 * 1024) = fl;
+      }
+    };
+    // four register sets: chunk c sits in set c % 4 and is requested four chunks ahead (four staging waves per compute
+    // unit, 8 KB per tile: 128 KB in flight, what it takes to keep the memory system busy at its loaded latency)
+    f32x4 u[4][8], cvs[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) cvs[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+    using Any = std::false_type;
+    using Full = std::true_type;
+    if (active) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (k < c_end) load_tile_rows(Any{}, u[k], cvs[k], k);
+      stage(u[0], cvs[0], 0);
+      if (4 < c_end) load_tile_rows(Any{}, u[0], cvs[0], 4);
+    }
+    __syncthreads();
+    // four chunks: while the other waves multiply chunk c + k, chunk c + k + 1 is staged and chunk c + k + 5 requested.
+    // STEADY: all of those exist and are complete, so nothing in the body branches.
+    auto quad = [&](auto steady_c, long long c) __attribute__((always_inline)) {
+      constexpr bool STEADY = decltype(steady_c)::value;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (STEADY || c + k < c_end) {
+          if (STEADY || (active && c + k + 1 < c_end)) {
+            stage(u[(k + 1) & 3], cvs[(k + 1) & 3], (k + 1) & 1);
+            if (STEADY) load_tile_rows(Full{}, u[(k + 1) & 3], cvs[(k + 1) & 3], c + k + 5);
+            else if (c + k + 5 < c_end) load_tile_rows(Any{}, u[(k + 1) & 3], cvs[(k + 1) & 3], c + k + 5);
+          }
+          __syncthreads();
+        }
+      }
+    };
+    // this workgroup's chunks that are complete (only the last chunk of the matrix can be ragged)
+    const long long g_full = d / 64;
+    const long long c_full = g_full > blockIdx.x ? (g_full - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+    long long c = 0;
+    if (active) {
+      for (; c + 8 < c_full; c += 4) quad(Full{}, c);
+    } else {
+      // a staging wave without a tile (three row blocks): it only keeps the barriers company
+      for (; c + 8 < c_full; c += 4)
+        for (int k = 0; k < 4; ++k) __syncthreads();
+    }
+    for (; c < c_end; c += 4) quad(Any{}, c);
+    for (int i = 0; i < 5; ++i) __syncthreads();
+    return;
+  }
+
+  // ---- multiplying waves
+  const int ks = wave - 4;   // 16-column step of every chunk
+  f32x16 acc[PAIRS];
+#pragma unroll
+  for (int p = 0; p < PAIRS; ++p)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[p][j] = 0.f;
+  auto multiply = [&](int buf) __attribute__((always_inline)) {
+    bf16x8 fh[RB], fm[RB], fl[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const unsigned char* src = lds + buf * SG::BUF_BYTES + (rb * 3 * 4 + ks) * 1024 + lane * 16;
+      fh[rb] = *reinterpret_cast<const bf16x8*>(src);
+      fm[rb] = *reinterpret_cast<const bf16x8*>(src + 4 * 1024);
+      fl[rb] = *reinterpret_cast<const bf16x8*>(src + 8 * 1024);
+    }
+    // The six piece products of a block pair go to its accumulator in the same order as in krum_gram_kernel
+    // (smallest first), but product kind by product kind over all pairs: consecutive matrix instructions then
+    // write different accumulators and none waits for the result of the one before it.
+#pragma unroll
+    for (int kind = 0; kind < 6; ++kind) {
+      int p = 0;
+#pragma unroll
+      for (int a = 0; a < RB; ++a)
+#pragma unroll
+        for (int b = a; b < RB; ++b, ++p) {
+          const bf16x8 x = kind == 0 ? fl[a] : (kind == 2 || kind == 3) ? fm[a] : fh[a];
+          const bf16x8 y = kind == 1 ? fl[b] : (kind == 2 || kind == 4) ? fm[b] : fh[b];
+          acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[p], 0, 0, 0);
+        }
+    }
+  };
+  __syncthreads();
+  for (long long c = 0; c < c_end; ++c) {
+    multiply((int)(c & 1));
+    __syncthreads();
+  }
+  // sum the four accumulators in a fixed tree, (0+2)+(1+3), through LDS
+  float* red = reinterpret_cast<float*>(lds);
+  __syncthreads();   // everybody is done with the buffers
+  for (int step = 2; step >= 1; step >>= 1) {
+    if (ks >= step && ks < 2 * step) {
+#pragma unroll
+      for (int p = 0; p < PAIRS; ++p)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) red[(((ks - step) * PAIRS + p) * 16 + j) * 64 + lane] = acc[p][j];
+    }
+    __syncthreads();
+    if (ks < step) {
+#pragma unroll
+      for (int p = 0; p < PAIRS; ++p)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[p][j] += red[((ks * PAIRS + p) * 16 + j) * 64 + lane];
+    }
+    __syncthreads();
+  }
+  if (ks == 0) {
     // accumulator element j of lane (n, h): row 8 (j/4) + 4 h + j%4 of block a, column n of block b
     float* out = partial + (long long)blockIdx.x * PAIRS * 1024;
 #pragma unroll
@@ -298,9 +524,30 @@ int gram_resident() {
   return cached;
 }
 
-// workgroups of the Gram launch: as many as the chip holds at once
-int gram_grid(int rb) {
-  return rb == 1 ? gram_resident<1>() : rb == 2 ? gram_resident<2>() : rb == 3 ? gram_resident<3>() : gram_resident<4>();
+int compute_units() {
+  static const int n_cu = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+      v = 256;
+    return v;
+  }();
+  return n_cu;
+}
+
+// workgroups of the Gram launch: as many as the chip holds at once (three and four row blocks: the eight-wave
+// workgroups that share a chunk through LDS, one per compute unit)
+int gram_grid(int rb) { return rb == 1 ? gram_resident<1>() : rb == 2 ? gram_resident<2>() : compute_units(); }
+
+template <int RB, bool CENTER>
+hipError_t launch_gram_shared(const float* G, long long ldg, int m, long long d, float* partial, int grid, const int32_t* center,
+                              const int32_t* run_flag, hipStream_t stream) {
+  constexpr int lds = SharedGram<RB>::LDS_BYTES;
+  static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_shared_kernel<RB, CENTER>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (attr_err != hipSuccess) return attr_err;
+  hipLaunchKernelGGL((krum_gram_shared_kernel<RB, CENTER>), dim3(grid), dim3(64 * kSharedWaves), lds, stream, G, ldg, m, d,
+                     partial, center, run_flag);
+  return hipGetLastError();
 }
 
 template <int RB, bool CENTER>
@@ -322,8 +569,8 @@ hipError_t launch_gram_rb(int rb, const float* G, long long ldg, int m, long lon
                           const int32_t* center, const int32_t* run_flag, hipStream_t stream) {
   if (rb == 1) return launch_gram<1, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
   if (rb == 2) return launch_gram<2, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
-  if (rb == 3) return launch_gram<3, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
-  return launch_gram<4, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  if (rb == 3) return launch_gram_shared<3, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  return launch_gram_shared<4, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
 }
 
 }  // namespace
