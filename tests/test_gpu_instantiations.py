@@ -15,6 +15,7 @@ from tests._util import SCORE_TOL, check_selection, exact_terms, npy, oracle_ter
 pytestmark = pytest.mark.gpu
 
 SEEN = set()     # (fwd, second product, waves, k_split, streaming, row_blocks, merged) of every layer launch
+TAILS = set()    # (fwd, second product, streaming, row_blocks) of every launch with a sliced tail
 
 
 @pytest.fixture(scope="module")
@@ -62,6 +63,8 @@ def _run(B, w, s_ref, s_exact, scale, row_align, offset_floats=0):
         if r["kernel"] in ("layer_base", "layer_cand"):
             shape = (w.fwd, r["second"], r["waves"], r["k_split"], r["streaming"], r["row_blocks"], r["merged"])
             SEEN.add(shape)
+            if r["tail_candidates"] > 0:
+                TAILS.add((w.fwd, r["second"], r["streaming"], r["row_blocks"]))
             shapes.append((r["kernel"], r["layer"]) + shape[1:] + (r["candidates"], r["tail_candidates"], r["k_slices"]))
     tol = SCORE_TOL[w.fwd]
     err = score_error(npy(s), s_ref, scale)
@@ -193,7 +196,9 @@ TAIL_DIMS = {10: [1024, 2048, 2048, 10], 12: [1024, 2048, 2048, 12]}
     ("fp32", 64, 32, 10), ("fp32", 64, 1, 10),
     ("bf16", 160, 32, 10),     # two passes over G (128 + 32 samples): the second finds the arrival counters at zero
     # dense bf16 rows: the sliced tail on the shifted column grid, 8-byte (d mod 4 = 2) and 16-byte aligned rows
-    ("bf16", 32, 1, 10), ("bf16", 64, 1, 10), ("bf16", 128, 1, 10), ("bf16", 64, 1, 12), ("bf16", 128, 1, 12)])
+    ("bf16", 32, 1, 10), ("bf16", 64, 1, 10), ("bf16", 128, 1, 10), ("bf16", 32, 1, 12), ("bf16", 64, 1, 12), ("bf16", 128, 1, 12),
+    # fp32 with four row blocks: the layer with the second product is single-buffered and keeps its whole tiles
+    ("fp32", 128, 32, 10)])
 def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align, classes):
     """36 candidates on 2048-wide layers are 288 eight-wave workgroups: one full round of 256 and a round that
     would be one-eighth full.  The tiles of candidates 32..35 and of the pass at x through the next layer run
@@ -206,6 +211,9 @@ def test_last_round_of_a_launch_in_k_slices(B, fwd, n_r, row_align, classes):
     for layer in (0, 1):
         launches = [s for s in shapes if s[0] == "layer_cand" and s[1] == layer]
         assert len(launches) == passes, shapes
+        if fwd == "fp32" and n_r > 64 and layer == 1:
+            assert all(one[9] == 0 for one in launches), shapes                                    # no tail there
+            continue
         for one in launches:
             assert one[3] == 8 and one[7] == 1, shapes                                             # eight waves, merged
             assert one[8:10] == (36, 4) and one[10] >= 2, shapes                                   # tail of 4, sliced
@@ -257,7 +265,22 @@ def test_zz_which_instantiations_ran(B):
             for kind in (2, 3):
                 if not any(s[0] == "bf16" and s[1] == second and s[2] in (4, 8) and s[4] == kind and s[5] == mb for s in SEEN):
                     missing.append(("bf16", second, "4|8 waves", "shifted grid", kind, mb))
+    # sliced tails: every kind of row access, with and without the second product, every number of row blocks that
+    # has the instantiation (fp32 with the second product and four row blocks is single-buffered: no tail)
+    for fwd, kinds in (("bf16", (0, 1, 2, 3)), ("fp32", (0, 1))):
+        for second in (0, 1):
+            for kind in kinds:
+                if kind == 0 and fwd == "bf16":
+                    want = [(fwd, 0, 0, 2)]       # plain loads in bf16: ragged K (first layer of the wide-output case)
+                    if second:
+                        continue
+                else:
+                    want = [(fwd, second, kind, mb) for mb in ((1, 2, 4) if fwd == "bf16" else (1, 2))]
+                missing += [("tail",) + t for t in want if t not in TAILS]
+    if ("fp32", 0, 1, 4) not in TAILS:
+        missing.append(("tail", "fp32", 0, 1, 4))
     print("\n  launch shapes seen:", sorted(SEEN))
+    print("  sliced tails seen:", sorted(TAILS))
     assert not missing, missing
 
 
