@@ -278,28 +278,27 @@ __device__ inline void load_tile_edge2(f32x4 (&u)[8], const float* __restrict__ 
 // Staging ring of the shifted column grid (bf16): two staging tiles of the ordinary layout, the first for
 // the columns whose bit 6 is clear, the second for the others.  A tile of the shifted grid starts sigma
 // columns before a multiple of 64, so its first sigma columns go to one half and the rest to the other.
-// ring_w[i]: the lane's byte offset for row 4 i + lane / 16 of an EVEN tile; an odd tile flips the half.
-__device__ inline void ring_offsets(unsigned (&ring_w)[8], int lane, int sigma) {
+// ring_w: the lane's byte offset for row lane / 16 of an EVEN tile; an odd tile flips the half, and the offset for
+// row 4 i + lane / 16 is ring_w exclusive-or a constant: the row bits (i * 512) and the swizzle bits
+// ((2 i mod 8) * 16) of i touch no bit that the lane's part sets differently.  One register instead of eight, in a
+// kernel that has none to spare.
+__device__ inline unsigned ring_offset(int lane, int sigma) {
   const int rsub = lane >> 4, kq = lane & 15;
   const int col = (4 * kq - sigma) & 63;            // column inside its block of 64
   const int kp = col >> 2;
   const unsigned half = 4 * kq < sigma ? 4096u : 0u;   // columns before the tile's own block of 64
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = 4 * i + rsub;
-    ring_w[i] = half + r * 128 + ((((kp >> 1) ^ (r >> 1)) & 7) << 4) + ((kp & 1) << 3);
-  }
+  return half + rsub * 128 + ((((kp >> 1) ^ (rsub >> 1)) & 7) << 4) + ((kp & 1) << 3);
 }
 template <bool ODD>
-__device__ inline void stage_ring(const f32x4 (&u)[8], unsigned char* st, const unsigned (&ring_w)[8]) {
-  // the flip is hidden from the optimiser, which would otherwise keep both sets of eight offsets in
-  // registers (the kernel has none to spare) instead of one set and eight exclusive-ors per tile
-  unsigned flip = ODD ? 4096u : 0u;
-  asm volatile("" : "+s"(flip));
+__device__ inline void stage_ring(const f32x4 (&u)[8], unsigned char* st, unsigned ring_w) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const bf16x4 h = __builtin_convertvector(u[i], bf16x4);
-    *reinterpret_cast<bf16x4*>(st + (ring_w[i] ^ flip)) = h;
+    // the constant is hidden from the optimiser, which would otherwise hoist the eight offsets out of the
+    // K loop and keep them in eight registers again
+    unsigned ci = ((unsigned)(i * 512) | (unsigned)(((2 * i) & 7) << 4)) ^ (ODD ? 4096u : 0u);
+    asm volatile("" : "+s"(ci));
+    *reinterpret_cast<bf16x4*>(st + (ring_w ^ ci)) = h;
   }
 }
 
@@ -503,8 +502,8 @@ __global__ __launch_bounds__(64 * NW * KS) void layer_kernel(const LayerArgs a) 
   // RING: columns between the line a row starts in and the row's first element (the same for all rows of the tile)
   const int sigma = RING ? __builtin_amdgcn_readfirstlane((int)((reinterpret_cast<uintptr_t>(Urow0) & 127) >> 2)) : 0;
   const float* __restrict__ Uring = Urow0 - sigma;   // tile j of the shifted grid starts at Uring + 64 j
-  unsigned ring_w[RING == 1 ? 8 : 1], ring_p[2];
-  if constexpr (RING == 1) ring_offsets(ring_w, lane, sigma);
+  unsigned ring_w = 0, ring_p[2];
+  if constexpr (RING == 1) ring_w = ring_offset(lane, sigma);
   if constexpr (RING == 2) ring_offsets2(ring_p, lane, sigma);
 
   const unsigned char* Ag = reinterpret_cast<const unsigned char*>(J.A_base);
