@@ -206,6 +206,29 @@ class Runner:
             e[2] += r["bytes"]
         return per, per_layer
 
+    def baselines(self):
+        """Mean, Median, Krum (Section 6.1.1, Definitions 4 and 5) and the aggregation that also takes the server's SGD
+        step (Algorithm 1), on the same candidates: one unrecorded warm-up pass, three recorded ones."""
+        B, torch, w = self.B, self.torch, self.w
+        x_step = w.x.clone()
+        for i in range(-1, 3):
+            B.profile_enable(i >= 0)
+            G = self.Gs[i % self.n_buf]
+            B.zeno_mean(G, out=self.out)
+            B.zeno_median(G, out=self.out)
+            B.zeno_aggregate_update(G, self.scores, w.b, w.gamma, x_step, x_next=x_step, want_out=False, selected=self.sel)
+            if 3 <= w.m <= 128 and w.m - w.b - 2 >= 1:
+                B.zeno_krum(G, w.b, out=self.out)
+        torch.cuda.synchronize()
+        per = {}
+        for name, layer, ms, nbytes in B.profile_collect():
+            e = per.setdefault(name, [0, 0.0, 0.0])
+            e[0] += 1
+            e[1] += ms
+            e[2] += nbytes
+        B.profile_enable(False)
+        return {k: {"avg_ms": v[1] / v[0], "algorithmic_GBps": (v[2] / v[0]) / (v[1] / v[0]) / 1e6} for k, v in per.items()}
+
     def summary(self, steps, warmup, graph=False):
         """ms per step, roofline fraction of the step, and the per-launch table of one workload."""
         elapsed = self.time_steps(steps, warmup)
@@ -220,6 +243,8 @@ class Runner:
                "launches": {k: {"per_step": v[0] / n_prof, "avg_ms": v[1] / v[0],
                                 "algorithmic_GBps": (v[2] / v[0]) / (v[1] / v[0]) / 1e6} for k, v in per.items()},
                "layers": layer_table(per_layer)}
+        if w.m * w.d * 4 >= (1 << 30):
+            out["baseline_aggregators"] = self.baselines()
         if graph:
             g_elapsed = self.time_graph(steps, warmup)
             out["graph_replay_ms_per_step"] = 1e3 * g_elapsed / steps
