@@ -70,7 +70,11 @@ __device__ inline void split3(const f32x4& v0, const f32x4& v1, bf16x8& h, bf16x
 }
 
 // CENTER: second pass; runs only if *run_flag != 0 and subtracts row *center from every row.
-template <int RB, bool CENTER>
+// NT: streaming loads, where the rows start on 128-byte lines; the 256-byte row segments of other rows share their
+// outer lines with the wave's next chunk, which streaming loads would fetch from memory again (dense rows of
+// workload 5, m = 64: 3.0 -> 2.8 ms with plain loads; the same switch made the averaging kernel slower, 1.68 -> 1.85 ms,
+// and did nothing for the shared-chunk kernel below, so those always stream).
+template <int RB, bool CENTER, bool NT>
 __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : 2) void krum_gram_kernel(const float* __restrict__ G, long long ldg,
                                                                     int m, long long d, float* __restrict__ partial,
                                                                     const int32_t* __restrict__ center,
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : 2) void krum_gram_ke
         const float* p = G + (long long)rc * ldg + k0;
         f32x4 v;
         if (k_full) {
-          v = load_stream4(p + kq);
+          v = NT ? load_stream4(p + kq) : *reinterpret_cast<const f32x4_a4*>(p + kq);
         } else {
           v = load4_masked(p, kq, (int)(d - k0), true);
         }
@@ -514,9 +518,9 @@ int gram_resident() {
       n_cu = 256;
     constexpr int lds = kGramWaves * RB * 32 * 64 * 4;
     if (lds > 48 * 1024)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB, false>),
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB, false, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&krum_gram_kernel<RB, false>),
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(&krum_gram_kernel<RB, false, true>),
                                                      64 * kGramWaves, lds) != hipSuccess || per_cu < 1)
       per_cu = 1;
     return n_cu * per_cu;
@@ -538,6 +542,8 @@ int compute_units() {
 // workgroups that share a chunk through LDS, one per compute unit)
 int gram_grid(int rb) { return rb == 1 ? gram_resident<1>() : rb == 2 ? gram_resident<2>() : compute_units(); }
 
+inline bool rows_on_lines(const float* G, long long ldg) { return reinterpret_cast<uintptr_t>(G) % 128 == 0 && ldg % 32 == 0; }
+
 template <int RB, bool CENTER>
 hipError_t launch_gram_shared(const float* G, long long ldg, int m, long long d, float* partial, int grid, const int32_t* center,
                               const int32_t* run_flag, hipStream_t stream) {
@@ -550,18 +556,24 @@ hipError_t launch_gram_shared(const float* G, long long ldg, int m, long long d,
   return hipGetLastError();
 }
 
-template <int RB, bool CENTER>
-hipError_t launch_gram(const float* G, long long ldg, int m, long long d, float* partial, int grid, const int32_t* center,
-                       const int32_t* run_flag, hipStream_t stream) {
+template <int RB, bool CENTER, bool NT>
+hipError_t launch_gram_nt(const float* G, long long ldg, int m, long long d, float* partial, int grid, const int32_t* center,
+                          const int32_t* run_flag, hipStream_t stream) {
   constexpr int lds = kGramWaves * RB * 32 * 64 * 4;
   static const hipError_t attr_err =
-      lds > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB, CENTER>),
+      lds > 48 * 1024 ? hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_kernel<RB, CENTER, NT>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds)
                       : hipSuccess;
   if (attr_err != hipSuccess) return attr_err;
-  hipLaunchKernelGGL((krum_gram_kernel<RB, CENTER>), dim3(grid), dim3(64 * kGramWaves), lds, stream, G, ldg, m, d, partial,
+  hipLaunchKernelGGL((krum_gram_kernel<RB, CENTER, NT>), dim3(grid), dim3(64 * kGramWaves), lds, stream, G, ldg, m, d, partial,
                      center, run_flag);
   return hipGetLastError();
+}
+template <int RB, bool CENTER>
+hipError_t launch_gram(const float* G, long long ldg, int m, long long d, float* partial, int grid, const int32_t* center,
+                       const int32_t* run_flag, hipStream_t stream) {
+  if (rows_on_lines(G, ldg)) return launch_gram_nt<RB, CENTER, true>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  return launch_gram_nt<RB, CENTER, false>(G, ldg, m, d, partial, grid, center, run_flag, stream);
 }
 
 template <bool CENTER>
