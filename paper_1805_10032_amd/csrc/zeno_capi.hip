@@ -91,8 +91,8 @@ Plan make_plan(const zeno_model* mdl, int m, int n_r) {
       p.sz_wt[l] = (size_t)p.wt_rows[l] * pad64(D.dims[l]) * p.esize;
       p.off_wt[l] = take(p.sz_wt[l]);
     }
-    // upper bound on the partial-norm slots of this layer: one launch over all candidates, or two launches
-    // (the second with few candidates, whose tiles may then split K more widely) with a range of slots each
+    // upper bound on the partial-norm slots of this layer: the whole tiles of a launch, and a second range for the
+    // (tile, slice) pairs of a sliced tail (at most 8 slices per 256-feature tile, i.e. one per 32 features)
     p.P += norm_slots_bound(N, m, p.MB) + norm_slots_bound(N, 1, p.MB);
   }
   p.n_counters = kMaxSliceGroups;
