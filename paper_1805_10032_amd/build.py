@@ -17,9 +17,12 @@ LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.environ.get("ZENO_BUILD_OUT") or os.path.join(LIB_DIR, "libzeno_hip.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["zeno_capi.hip", "zeno_layer.hip", "zeno_layer_bf16_delta.hip", "zeno_layer_bf16_first.hip",
-           "zeno_layer_f32_delta.hip", "zeno_layer_f32_first.hip", "zeno_loss.hip", "zeno_aggregate.hip",
-           "zeno_median.hip", "zeno_median_select.hip", "zeno_krum.hip", "zeno_conv.hip"]
+# (source, object suffix, extra flags).  The streaming layer kernel's four instantiation files are compiled once per
+# number of row blocks, longest first, so that twelve objects of similar size build in parallel.
+LAYER_UNITS = ["zeno_layer_bf16_delta.hip", "zeno_layer_bf16_first.hip", "zeno_layer_f32_delta.hip", "zeno_layer_f32_first.hip"]
+SOURCES = ([(u, f"_mb{mb}", [f"-DZENO_LAYER_MB={mb}"]) for mb in (4, 2, 1) for u in LAYER_UNITS] +
+           [(s, "", []) for s in ("zeno_median.hip", "zeno_krum.hip", "zeno_capi.hip", "zeno_layer.hip", "zeno_loss.hip",
+                                  "zeno_aggregate.hip", "zeno_median_select.hip", "zeno_conv.hip")])
 
 # Packed-fp32 instruction selection is switched off for all device code.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -52,9 +55,10 @@ def _fresh(obj, src, stamp):
         return False
 
 
-def _compile(src, force=True):
-    obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
-    extra = os.environ.get("ZENO_EXTRA_HIPCC_FLAGS", "").split()
+def _compile(unit, force=True):
+    src, suffix, unit_flags = unit
+    obj = os.path.join(OBJ_DIR, src.replace(".hip", suffix + ".o"))
+    extra = [*unit_flags, *os.environ.get("ZENO_EXTRA_HIPCC_FLAGS", "").split()]
     stamp = " ".join([*HIPCC_FLAGS, *PER_FILE_FLAGS.get(src, []), *extra])
     if not force and _fresh(obj, src, stamp):
         return obj, ""

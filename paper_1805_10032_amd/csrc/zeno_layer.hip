@@ -1,25 +1,40 @@
 // Dispatcher of the streaming layer kernel: launch shapes, the choice between merged
 // and separate launches of the pass at x, and the packing of the batch.  The kernel
-// itself lives in zeno_layer_impl.h and is compiled in four translation units
-// (zeno_layer_{bf16,f32}_{first,delta}.hip).
+// itself lives in zeno_layer_impl.h and is compiled in twelve objects (the four files
+// zeno_layer_{bf16,f32}_{first,delta}.hip, each once per number of row blocks).
 #include <cstring>
 
 #include "zeno_layer_impl.h"
 
 namespace zeno {
 
-hipError_t launch_layer_bf16_delta(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
-hipError_t launch_layer_bf16_first(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
-hipError_t launch_layer_f32_delta(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
-hipError_t launch_layer_f32_first(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape);
-int ks_waves_bf16_delta(int MB);
-int ks_waves_bf16_first(int MB);
-int ks_waves_f32_delta(int MB);
-int ks_waves_f32_first(int MB);
-int wgs_per_cu_bf16_delta(int MB, int NW, int k_waves);
-int wgs_per_cu_bf16_first(int MB, int NW, int k_waves);
-int wgs_per_cu_f32_delta(int MB, int NW, int k_waves);
-int wgs_per_cu_f32_first(int MB, int NW, int k_waves);
+// the entry points of the twelve kernel objects: (operand type, second product) x row blocks
+#define ZENO_DECLARE_LAYER(NAME)                                                                                  \
+  hipError_t launch_layer_##NAME##_mb1(const LayerArgs& a, int NW, hipStream_t stream, LaunchShape* shape);       \
+  hipError_t launch_layer_##NAME##_mb2(const LayerArgs& a, int NW, hipStream_t stream, LaunchShape* shape);       \
+  hipError_t launch_layer_##NAME##_mb4(const LayerArgs& a, int NW, hipStream_t stream, LaunchShape* shape);       \
+  int wgs_per_cu_##NAME##_mb1(int NW, int k_waves);                                                               \
+  int wgs_per_cu_##NAME##_mb2(int NW, int k_waves);                                                               \
+  int wgs_per_cu_##NAME##_mb4(int NW, int k_waves);                                                               \
+  static hipError_t launch_layer_##NAME(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape) { \
+    return MB == 1 ? launch_layer_##NAME##_mb1(a, NW, stream, shape)                                              \
+         : MB == 2 ? launch_layer_##NAME##_mb2(a, NW, stream, shape)                                              \
+                   : launch_layer_##NAME##_mb4(a, NW, stream, shape);                                             \
+  }                                                                                                               \
+  static int wgs_per_cu_##NAME(int MB, int NW, int k_waves) {                                                     \
+    return MB == 1 ? wgs_per_cu_##NAME##_mb1(NW, k_waves) : MB == 2 ? wgs_per_cu_##NAME##_mb2(NW, k_waves)        \
+                                                                     : wgs_per_cu_##NAME##_mb4(NW, k_waves);      \
+  }
+ZENO_DECLARE_LAYER(bf16_delta)
+ZENO_DECLARE_LAYER(bf16_first)
+ZENO_DECLARE_LAYER(f32_delta)
+ZENO_DECLARE_LAYER(f32_first)
+#undef ZENO_DECLARE_LAYER
+
+template <bool BF16, bool DELTA>
+static int ks_waves_for(int MB) {
+  return MB == 1 ? split_k_waves<BF16, DELTA, 1>() : MB == 2 ? split_k_waves<BF16, DELTA, 2>() : split_k_waves<BF16, DELTA, 4>();
+}
 
 static int compute_units() {
   static const int n_cu = [] {
@@ -37,8 +52,8 @@ static int wgs_per_cu(bool bf16, bool delta, int MB, int NW, int k_waves = 1) {
 }
 
 static int ks_waves(bool bf16, bool delta, int MB) {
-  return bf16 ? (delta ? ks_waves_bf16_delta(MB) : ks_waves_bf16_first(MB))
-              : (delta ? ks_waves_f32_delta(MB) : ks_waves_f32_first(MB));
+  return bf16 ? (delta ? ks_waves_for<true, true>(MB) : ks_waves_for<true, false>(MB))
+              : (delta ? ks_waves_for<false, true>(MB) : ks_waves_for<false, false>(MB));
 }
 
 // Waves per workgroup of a launch.  Where eight would be picked, four are taken instead if two

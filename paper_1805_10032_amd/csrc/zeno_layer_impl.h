@@ -1203,13 +1203,6 @@ int wgs_per_cu_nw(int NW, int k_waves) {
   return wgs_per_cu_inst<BF16, DELTA, MB, 1, 1>();
 }
 
-template <bool BF16, bool DELTA>
-int wgs_per_cu_mb(int MB, int NW, int k_waves) {
-  if (MB == 1) return wgs_per_cu_nw<BF16, DELTA, 1>(NW, k_waves);
-  if (MB == 2) return wgs_per_cu_nw<BF16, DELTA, 2>(NW, k_waves);
-  return wgs_per_cu_nw<BF16, DELTA, 4>(NW, k_waves);
-}
-
 // Streaming loads are used when every row segment a load instruction covers
 // starts on a 128-byte line: base pointers, row pitch, block offset and row
 // length of every job in the launch are multiples of 128 bytes.
@@ -1296,13 +1289,6 @@ hipError_t launch_nw(const LayerArgs& a, int NW, hipStream_t stream, LaunchShape
   return launch_nt<BF16, DELTA, MB, 1>(a, stream, shape);
 }
 
-template <bool BF16, bool DELTA>
-hipError_t launch_mb(const LayerArgs& a, int MB, int NW, hipStream_t stream, LaunchShape* shape) {
-  if (MB == 1) return launch_nw<BF16, DELTA, 1>(a, NW, stream, shape);
-  if (MB == 2) return launch_nw<BF16, DELTA, 2>(a, NW, stream, shape);
-  return launch_nw<BF16, DELTA, 4>(a, NW, stream, shape);
-}
-
 // Waves per workgroup (32 output features each): the widest workgroup that still
 // gives every compute unit work, since a wider workgroup re-reads less of the
 // activations per byte of weights; narrow layers fall back to one wave to spread
@@ -1323,22 +1309,25 @@ int launch_nw_for(const LayerArgs& a) {
 
 }  // namespace zeno
 
-// The kernel is compiled in four translation units, one per (operand type, second
-// product) pair, so that the instantiations build in parallel; each defines the two
-// entry points the dispatcher in zeno_layer.hip calls.
-#define ZENO_LAYER_INSTANCE(NAME, BF16, DELTA)                                                    \
-  namespace zeno {                                                                                \
-  hipError_t launch_layer_##NAME(const LayerArgs& a, int MB, int NW, hipStream_t stream,          \
-                                 LaunchShape* shape) {                                            \
-    return launch_mb<BF16, DELTA>(a, MB, NW, stream, shape);                                      \
-  }                                                                                               \
-  int wgs_per_cu_##NAME(int MB, int NW, int k_waves) {                                            \
-    return wgs_per_cu_mb<BF16, DELTA>(MB, NW, k_waves);                                           \
-  }                                                                                               \
-  int ks_waves_##NAME(int MB) {                                                                   \
-    return MB == 1 ? split_k_waves<BF16, DELTA, 1>() : MB == 2 ? split_k_waves<BF16, DELTA, 2>()  \
-                                                               : split_k_waves<BF16, DELTA, 4>(); \
-  }                                                                                               \
+// The kernel is compiled in twelve objects so that the instantiations build in parallel: four source files, one per
+// (operand type, second product) pair, each compiled once per number of row blocks (-DZENO_LAYER_MB=1, 2, 4; without
+// the definition a file holds all three).  Each object defines the two entry points of its (pair, row blocks) that the
+// dispatcher in zeno_layer.hip calls.
+#define ZENO_LAYER_INSTANCE_MB_(NAME, BF16, DELTA, MB)                                                       \
+  namespace zeno {                                                                                           \
+  hipError_t launch_layer_##NAME##_mb##MB(const LayerArgs& a, int NW, hipStream_t stream, LaunchShape* shape) { \
+    return launch_nw<BF16, DELTA, MB>(a, NW, stream, shape);                                                 \
+  }                                                                                                          \
+  int wgs_per_cu_##NAME##_mb##MB(int NW, int k_waves) { return wgs_per_cu_nw<BF16, DELTA, MB>(NW, k_waves); }   \
   }
+#define ZENO_LAYER_INSTANCE_MB(NAME, BF16, DELTA, MB) ZENO_LAYER_INSTANCE_MB_(NAME, BF16, DELTA, MB)
+#ifdef ZENO_LAYER_MB
+#define ZENO_LAYER_INSTANCE(NAME, BF16, DELTA) ZENO_LAYER_INSTANCE_MB(NAME, BF16, DELTA, ZENO_LAYER_MB)
+#else
+#define ZENO_LAYER_INSTANCE(NAME, BF16, DELTA) \
+  ZENO_LAYER_INSTANCE_MB(NAME, BF16, DELTA, 1) \
+  ZENO_LAYER_INSTANCE_MB(NAME, BF16, DELTA, 2) \
+  ZENO_LAYER_INSTANCE_MB(NAME, BF16, DELTA, 4)
+#endif
 
 #endif  // ZENO_LAYER_IMPL_H_

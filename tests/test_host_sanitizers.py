@@ -22,9 +22,9 @@ def test_argument_layer_under_address_and_ub_sanitizers(tmp_path):
         subprocess.run([hipcc, *build.HIPCC_FLAGS, *san, "-c", os.path.join(build.CSRC, src), "-o", obj],
                        check=True, capture_output=True, text=True)
         objs.append(obj)
-    for src in build.SOURCES:
+    for src, suffix, _flags in build.SOURCES:
         if src not in ("zeno_capi.hip", "zeno_layer.hip"):
-            objs.append(os.path.join(build.OBJ_DIR, src.replace(".hip", ".o")))
+            objs.append(os.path.join(build.OBJ_DIR, src.replace(".hip", suffix + ".o")))
     main_obj = str(tmp_path / "host_checks.o")
     subprocess.run([hipcc, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
                     "-fno-sanitize-recover=undefined", "-I", os.path.join(ROOT, "include"),
