@@ -217,38 +217,45 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : 2) void krum_gram_ke
 //  * waves 0..3 stage: wave t takes tile t of the chunk (the coalesced loads of krum_gram_kernel, requested four
 //    chunks ahead), brings it into operand order through its private swizzled tile, splits every float into its
 //    three bf16 pieces and writes the pieces, in operand order, to the chunk's shared buffer
-//    ([tile][piece][16-column step][64 lanes x 16 bytes], double-buffered: one barrier per chunk);
-//  * waves 4..7 multiply: wave 4 + s takes the 16-column step s of the chunk, reads the 3 RB operand fragments of
-//    that step once and issues the six matrix instructions of every block pair.
+//    ([16-row block][piece][32-column step][64 lanes x 16 bytes], double-buffered: one barrier per chunk);
+//  * waves 4..7 multiply, in 16 x 16 blocks (v_mfma_f32_16x16x32_bf16): the m rows are NBL = ceil(m / 16) blocks of
+//    16 rows, and only the NBL (NBL + 1) / 2 block pairs a <= b are formed, so rows beyond m cost at most 15 rows of
+//    padding and the diagonal blocks waste a 16 x 16 triangle, not a 32 x 32 one (m = 100: 28 pairs x 8 cycles per
+//    16 columns and piece product against 10 x 32 with 32-row blocks).  Wave 4 + w takes the 32-column step w & 1 of
+//    the chunk and every second block pair (w >> 1), reads the 3 NBL operand fragments of its step once and issues
+//    the six piece products of each of its pairs.
 // The vector ALU work of the staging wave and the matrix instructions of the multiplying wave of a SIMD run side by
-// side; each fragment crosses LDS once per chunk.  The four multiplying waves add their accumulators through LDS
-// at the end, in the fixed tree (0+2)+(1+3), and write the workgroup's partial Gram in the layout of krum_gram_kernel.
+// side.  The two multiplying waves of a pair set add their accumulators through LDS at the end (step 0 + step 1)
+// and write the workgroup's partial Gram in the 32 x 32 block layout of krum_gram_kernel (16 x 16 quadrants that are
+// not formed, below the diagonal or beyond the last live block, are written as zeros).
 // Two things in the staging waves matter as much as the split of roles: the loaded values are first touched when
 // their tile is staged (zeroing the rows beyond m right behind the load made every wave wait for the load it had
 // just requested), and the steady-state loop has no branch between requesting a tile and staging it four chunks
 // later (where paths with different numbers of loads meet, the compiler waits for all of them).
-// Measured (MI355X, d = 14.7 M): m = 72 / 96 / 100 / 128: 1.28 / 1.43 / 1.75 / 1.97 ms per Krum call, against
-// 1.91 / 1.95 / 2.0 / 2.5 ms with krum_gram_kernel<3 or 4>; staging alone runs at the memory's pace (1.35 ms for
-// m = 128, 5.6 TB/s), the products alone take 1.04 ms, and the barrier per chunk lets them overlap only in part.
+// Measured (MI355X, d = 14.7 M): m = 72 / 96 / 100 / 128: 1.21 / 1.37 / 1.63 / 1.88 ms per Krum call (with 32 x 32
+// blocks in the multiplying waves 1.28 / 1.43 / 1.65 / 1.97 ms; with krum_gram_kernel<3 or 4> 1.91 / 1.95 / 2.0 / 2.5 ms).
+// Staging alone runs at the memory's pace (1.35 ms for m = 128, 5.6 TB/s), the products alone take less, and the
+// barrier per chunk lets the two overlap only in part; a higher issue priority for either role changes nothing.
 constexpr int kSharedWaves = 8;
 
 template <int RB>
 struct SharedGram {
-  static constexpr int PAIRS = RB * (RB + 1) / 2;
+  static constexpr int PAIRS = RB * (RB + 1) / 2;               // 32 x 32 block pairs of the partial Gram
   static constexpr int BUF_BYTES = RB * 3 * 4 * 1024;           // the pieces of one chunk
   static constexpr int STAGE_OFF = 2 * BUF_BYTES;
   static constexpr int TILE_BYTES = 32 * 64 * 4;
   static constexpr int LDS_BYTES = STAGE_OFF + 4 * TILE_BYTES;
-  static_assert(2 * PAIRS * 16 * 64 * 4 <= LDS_BYTES, "the final reduction fits the buffers");
+  static constexpr int MAX_HALF_PAIRS = (2 * RB * (2 * RB + 1) / 2 + 1) / 2;   // 16 x 16 block pairs of one multiplying wave
+  static_assert(2 * MAX_HALF_PAIRS * 4 * 64 * 4 <= LDS_BYTES, "the final reduction fits the buffers");
 };
 
-template <int RB, bool CENTER>
+template <int RB, int NBL, bool CENTER>
 __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(const float* __restrict__ G, long long ldg, int m,
                                                                              long long d, float* __restrict__ partial,
                                                                              const int32_t* __restrict__ center,
                                                                              const int32_t* __restrict__ run_flag) {
   using SG = SharedGram<RB>;
-  constexpr int PAIRS = SG::PAIRS;
+  static_assert(NBL == 2 * RB || NBL == 2 * RB - 1, "live 16-row blocks of RB 32-row tiles");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   if (CENTER && *run_flag == 0) return;   // uniform over the launch
   const int tid = threadIdx.x, lane = tid & 63;
@@ -259,7 +266,7 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
   const long long c_end = (n_chunks - blockIdx.x + gridDim.x - 1) / gridDim.x;
   const int n = lane & 31, h = lane >> 5;
 
-  // Both roles pass the same barriers: one after the first chunk is staged, one per chunk in the loop, five in the
+  // Both roles pass the same barriers: one after the first chunk is staged, one per chunk in the loop, two in the
   // final reduction.
   if (wave < 4) {
     // ---- staging waves
@@ -294,7 +301,9 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
 #pragma unroll
       for (int j = 0; j < 8; ++j) u[j] = (32 * t + 4 * j + rsub < m) ? (CENTER ? u[j] - cv : u[j]) : zero;
       stage_tile<false>(u, st, lane);
-      // per 16-column step s, lane (n, h) reads row n, columns 16 s + 8 h .. + 7 and splits them
+      // per 16-column step s, lane (n, h) reads row n, columns 16 s + 8 h .. + 7 and splits them.  In the operand
+      // fragment of the 16-row block 2 t + n / 16 and the 32-column step s / 2 these eight columns are the share of
+      // fragment lane 16 (2 (s % 2) + h) + n % 16 (row n % 16, columns 8 (lane / 16) .. + 7 of the step).
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         const unsigned char* row = st + n * 256;
@@ -302,10 +311,11 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
         const f32x4 v1 = *reinterpret_cast<const f32x4*>(row + ((((4 * s + 2 * h + 1) ^ n) & 15) << 4));
         bf16x8 fh, fm, fl;
         split3(v0, v1, fh, fm, fl);
-        unsigned char* dst = lds + buf * SG::BUF_BYTES + (t * 3 * 4 + s) * 1024 + lane * 16;
+        const int flane = 16 * (2 * (s & 1) + h) + (n & 15);
+        unsigned char* dst = lds + buf * SG::BUF_BYTES + (((2 * t + (n >> 4)) * 3) * 2 + (s >> 1)) * 1024 + flane * 16;
         *reinterpret_cast<bf16x8*>(dst) = fh;
-        *reinterpret_cast<bf16x8*>(dst + 4 * 1024) = fm;
-        *reinterpret_cast<bf16x8*>(dst + 8 * 1024) = fl;
+        *reinterpret_cast<bf16x8*>(dst + 2 * 1024) = fm;
+        *reinterpret_cast<bf16x8*>(dst + 4 * 1024) = fl;
       }
     };
     // four register sets: chunk c sits in set c % 4 and is requested four chunks ahead (four staging waves per compute
@@ -351,25 +361,26 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
         for (int k = 0; k < 4; ++k) __syncthreads();
     }
     for (; c < c_end; c += 4) quad(Any{}, c);
-    for (int i = 0; i < 5; ++i) __syncthreads();
+    for (int i = 0; i < 2; ++i) __syncthreads();
     return;
   }
 
   // ---- multiplying waves
-  const int ks = wave - 4;   // 16-column step of every chunk
-  f32x16 acc[PAIRS];
+  const int q = (wave - 4) & 1;      // 32-column step of every chunk
+  const int half = (wave - 4) >> 1;  // block pairs p with p % 2 == half
+  constexpr int PAIRS16 = NBL * (NBL + 1) / 2;
+  f32x4 acc[(PAIRS16 + 1) / 2];
 #pragma unroll
-  for (int p = 0; p < PAIRS; ++p)
+  for (int i = 0; i < (PAIRS16 + 1) / 2; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto multiply = [&](auto half_c, int buf) __attribute__((always_inline)) {
+    constexpr int HALF = decltype(half_c)::value;
+    bf16x8 fh[NBL], fm[NBL], fl[NBL];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) acc[p][j] = 0.f;
-  auto multiply = [&](int buf) __attribute__((always_inline)) {
-    bf16x8 fh[RB], fm[RB], fl[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const unsigned char* src = lds + buf * SG::BUF_BYTES + (rb * 3 * 4 + ks) * 1024 + lane * 16;
-      fh[rb] = *reinterpret_cast<const bf16x8*>(src);
-      fm[rb] = *reinterpret_cast<const bf16x8*>(src + 4 * 1024);
-      fl[rb] = *reinterpret_cast<const bf16x8*>(src + 8 * 1024);
+    for (int g = 0; g < NBL; ++g) {
+      const unsigned char* src = lds + buf * SG::BUF_BYTES + ((g * 3) * 2 + q) * 1024 + lane * 16;
+      fh[g] = *reinterpret_cast<const bf16x8*>(src);
+      fm[g] = *reinterpret_cast<const bf16x8*>(src + 2 * 1024);
+      fl[g] = *reinterpret_cast<const bf16x8*>(src + 4 * 1024);
     }
     // The six piece products of a block pair go to its accumulator in the same order as in krum_gram_kernel
     // (smallest first), but product kind by product kind over all pairs: consecutive matrix instructions then
@@ -378,46 +389,76 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
     for (int kind = 0; kind < 6; ++kind) {
       int p = 0;
 #pragma unroll
-      for (int a = 0; a < RB; ++a)
+      for (int a = 0; a < NBL; ++a)
 #pragma unroll
-        for (int b = a; b < RB; ++b, ++p) {
+        for (int b = a; b < NBL; ++b, ++p) {
+          if ((p & 1) != HALF) continue;
           const bf16x8 x = kind == 0 ? fl[a] : (kind == 2 || kind == 3) ? fm[a] : fh[a];
           const bf16x8 y = kind == 1 ? fl[b] : (kind == 2 || kind == 4) ? fm[b] : fh[b];
-          acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[p], 0, 0, 0);
+          acc[p >> 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, acc[p >> 1], 0, 0, 0);
         }
     }
   };
   __syncthreads();
-  for (long long c = 0; c < c_end; ++c) {
-    multiply((int)(c & 1));
-    __syncthreads();
+  if (half == 0) {
+    for (long long c = 0; c < c_end; ++c) {
+      multiply(std::integral_constant<int, 0>{}, (int)(c & 1));
+      __syncthreads();
+    }
+  } else {
+    for (long long c = 0; c < c_end; ++c) {
+      multiply(std::integral_constant<int, 1>{}, (int)(c & 1));
+      __syncthreads();
+    }
   }
-  // sum the four accumulators in a fixed tree, (0+2)+(1+3), through LDS
-  float* red = reinterpret_cast<float*>(lds);
+  // the two column steps of a pair set are added through LDS, step 0 + step 1
+  float* red = reinterpret_cast<float*>(lds) + half * (SG::MAX_HALF_PAIRS * 4 * 64);
   __syncthreads();   // everybody is done with the buffers
-  for (int step = 2; step >= 1; step >>= 1) {
-    if (ks >= step && ks < 2 * step) {
+  if (q == 1) {
 #pragma unroll
-      for (int p = 0; p < PAIRS; ++p)
+    for (int i = 0; i < (PAIRS16 + 1) / 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) red[(((ks - step) * PAIRS + p) * 16 + j) * 64 + lane] = acc[p][j];
-    }
-    __syncthreads();
-    if (ks < step) {
-#pragma unroll
-      for (int p = 0; p < PAIRS; ++p)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[p][j] += red[((ks * PAIRS + p) * 16 + j) * 64 + lane];
-    }
-    __syncthreads();
+      for (int j = 0; j < 4; ++j) red[(i * 4 + j) * 64 + lane] = acc[i][j];
   }
-  if (ks == 0) {
-    // accumulator element j of lane (n, h): row 8 (j/4) + 4 h + j%4 of block a, column n of block b
-    float* out = partial + (long long)blockIdx.x * PAIRS * 1024;
+  __syncthreads();
+  if (q == 1) return;
 #pragma unroll
-    for (int p = 0; p < PAIRS; ++p)
+  for (int i = 0; i < (PAIRS16 + 1) / 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 16; ++j) out[p * 1024 + (8 * (j >> 2) + 4 * h + (j & 3)) * 32 + n] = acc[p][j];
+    for (int j = 0; j < 4; ++j) acc[i][j] += red[(i * 4 + j) * 64 + lane];
+  // accumulator element j of lane l: row 4 (l / 16) + j of block a, row l % 16 of block b; block pair (a, b) is the
+  // quadrant (a % 2, b % 2) of the 32 x 32 block pair (a / 2, b / 2)
+  float* out = partial + (long long)blockIdx.x * SG::PAIRS * 1024;
+  const int oi = 4 * (lane >> 4), oj = lane & 15;
+  auto pair32 = [](int A, int B) { return A * RB - A * (A - 1) / 2 + (B - A); };
+  {
+    int p = 0;
+#pragma unroll
+    for (int a = 0; a < NBL; ++a)
+#pragma unroll
+      for (int b = a; b < NBL; ++b, ++p) {
+        if ((p & 1) != half) continue;   // (uniform over the wave)
+        float* o = out + pair32(a >> 1, b >> 1) * 1024 + ((a & 1) * 16 + oi) * 32 + (b & 1) * 16 + oj;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j * 32] = acc[p >> 1][j];
+      }
+  }
+  if (half == 0) {
+    // the quadrants nobody forms: below the diagonal inside a diagonal 32 x 32 block, and those of a block beyond NBL
+#pragma unroll
+    for (int A = 0; A < RB; ++A)
+#pragma unroll
+      for (int B = A; B < RB; ++B)
+#pragma unroll
+        for (int qa = 0; qa < 2; ++qa)
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb) {
+            const int a = 2 * A + qa, b = 2 * B + qb;
+            if (a <= b && b < NBL) continue;
+            float* o = out + pair32(A, B) * 1024 + (qa * 16 + oi) * 32 + qb * 16 + oj;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j * 32] = 0.f;
+          }
   }
 }
 
@@ -544,14 +585,14 @@ int gram_grid(int rb) { return rb == 1 ? gram_resident<1>() : rb == 2 ? gram_res
 
 inline bool rows_on_lines(const float* G, long long ldg) { return reinterpret_cast<uintptr_t>(G) % 128 == 0 && ldg % 32 == 0; }
 
-template <int RB, bool CENTER>
+template <int RB, int NBL, bool CENTER>
 hipError_t launch_gram_shared(const float* G, long long ldg, int m, long long d, float* partial, int grid, const int32_t* center,
                               const int32_t* run_flag, hipStream_t stream) {
   constexpr int lds = SharedGram<RB>::LDS_BYTES;
-  static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_shared_kernel<RB, CENTER>),
+  static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&krum_gram_shared_kernel<RB, NBL, CENTER>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (attr_err != hipSuccess) return attr_err;
-  hipLaunchKernelGGL((krum_gram_shared_kernel<RB, CENTER>), dim3(grid), dim3(64 * kSharedWaves), lds, stream, G, ldg, m, d,
+  hipLaunchKernelGGL((krum_gram_shared_kernel<RB, NBL, CENTER>), dim3(grid), dim3(64 * kSharedWaves), lds, stream, G, ldg, m, d,
                      partial, center, run_flag);
   return hipGetLastError();
 }
@@ -581,8 +622,11 @@ hipError_t launch_gram_rb(int rb, const float* G, long long ldg, int m, long lon
                           const int32_t* center, const int32_t* run_flag, hipStream_t stream) {
   if (rb == 1) return launch_gram<1, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
   if (rb == 2) return launch_gram<2, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
-  if (rb == 3) return launch_gram_shared<3, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
-  return launch_gram_shared<4, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  const int nbl = (m + 15) / 16;   // live 16-row blocks
+  if (nbl == 5) return launch_gram_shared<3, 5, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  if (nbl == 6) return launch_gram_shared<3, 6, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  if (nbl == 7) return launch_gram_shared<4, 7, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
+  return launch_gram_shared<4, 8, CENTER>(G, ldg, m, d, partial, grid, center, run_flag, stream);
 }
 
 }  // namespace
