@@ -215,36 +215,38 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : 2) void krum_gram_ke
 // one wave fits a SIMD and nothing overlaps its vector work and its matrix instructions.  Here the eight waves of a
 // workgroup work on ONE chunk at a time, in two roles, one wave of each role per SIMD:
 //  * waves 0..3 stage: wave t takes tile t of the chunk (the coalesced loads of krum_gram_kernel, requested four
-//    chunks ahead), brings it into operand order through its private swizzled tile, splits every float into its
-//    three bf16 pieces and writes the pieces, in operand order, to the chunk's shared buffer
-//    ([16-row block][piece][32-column step][64 lanes x 16 bytes], double-buffered: one barrier per chunk);
+//    chunks ahead), zeroes the rows beyond m, subtracts the centre row in the second pass, and writes the floats
+//    into the chunk's shared buffer, a row per 256 bytes with its 16-byte column groups exclusive-or'ed with the
+//    row number (double-buffered: one barrier per chunk);
 //  * waves 4..7 multiply, in 16 x 16 blocks (v_mfma_f32_16x16x32_bf16): the m rows are NBL = ceil(m / 16) blocks of
 //    16 rows, and only the NBL (NBL + 1) / 2 block pairs a <= b are formed, so rows beyond m cost at most 15 rows of
 //    padding and the diagonal blocks waste a 16 x 16 triangle, not a 32 x 32 one (m = 100: 28 pairs x 8 cycles per
 //    16 columns and piece product against 10 x 32 with 32-row blocks).  Wave 4 + w takes the 32-column step w & 1 of
-//    the chunk and every second block pair (w >> 1), reads the 3 NBL operand fragments of its step once and issues
-//    the six piece products of each of its pairs.
-// The vector ALU work of the staging wave and the matrix instructions of the multiplying wave of a SIMD run side by
-// side.  The two multiplying waves of a pair set add their accumulators through LDS at the end (step 0 + step 1)
-// and write the workgroup's partial Gram in the 32 x 32 block layout of krum_gram_kernel (16 x 16 quadrants that are
-// not formed, below the diagonal or beyond the last live block, are written as zeros).
+//    the chunk and every second block pair (w >> 1): it reads the operand fragment of every block in operand order
+//    straight from the staged rows, splits it into the three bf16 pieces and issues the six piece products of each
+//    of its pairs.
+// The two multiplying waves of a pair set add their accumulators through LDS at the end (step 0 + step 1) and write
+// the workgroup's partial Gram in the 32 x 32 block layout of krum_gram_kernel (16 x 16 quadrants that are not
+// formed, below the diagonal or beyond the last live block, are written as zeros).
 // Two things in the staging waves matter as much as the split of roles: the loaded values are first touched when
 // their tile is staged (zeroing the rows beyond m right behind the load made every wave wait for the load it had
 // just requested), and the steady-state loop has no branch between requesting a tile and staging it four chunks
 // later (where paths with different numbers of loads meet, the compiler waits for all of them).
-// Measured (MI355X, d = 14.7 M): m = 72 / 96 / 100 / 128: 1.21 / 1.37 / 1.63 / 1.88 ms per Krum call (with 32 x 32
-// blocks in the multiplying waves 1.28 / 1.43 / 1.65 / 1.97 ms; with krum_gram_kernel<3 or 4> 1.91 / 1.95 / 2.0 / 2.5 ms).
-// Staging alone runs at the memory's pace (1.35 ms for m = 128, 5.6 TB/s), the products alone take less, and the
-// barrier per chunk lets the two overlap only in part; a higher issue priority for either role changes nothing.
+// Measured (MI355X, d = 14.7 M): m = 72 / 96 / 100 / 128: 1.01 / 1.29 / 1.49 / 1.84 ms per Krum call.  Before, the
+// staging waves also brought their tile into operand order through a private tile and split it, and the multiplying
+// waves read finished pieces: 1.21 / 1.37 / 1.63 / 1.88 ms (1.28 / 1.43 / 1.65 / 1.97 ms with 32 x 32 blocks; with
+// krum_gram_kernel<3 or 4> 1.91 / 1.95 / 2.0 / 2.5 ms).  Timing variants of this kernel (wrong results, same
+// accesses): without the splitting instructions it runs at the memory's pace (1.16 / 1.17 / 1.37 ms for
+// m = 96 / 100 / 128, 5.0-5.6 TB/s); the vector instructions of the split add their issue time to the matrix
+// instructions' on the same SIMD, whichever wave they sit in, and here both waves of a column step split every block.
 constexpr int kSharedWaves = 8;
 
 template <int RB>
 struct SharedGram {
   static constexpr int PAIRS = RB * (RB + 1) / 2;               // 32 x 32 block pairs of the partial Gram
-  static constexpr int BUF_BYTES = RB * 3 * 4 * 1024;           // the pieces of one chunk
-  static constexpr int STAGE_OFF = 2 * BUF_BYTES;
   static constexpr int TILE_BYTES = 32 * 64 * 4;
-  static constexpr int LDS_BYTES = STAGE_OFF + 4 * TILE_BYTES;
+  static constexpr int BUF_BYTES = RB * TILE_BYTES;             // one chunk: RB tiles of 32 rows x 64 floats
+  static constexpr int LDS_BYTES = 2 * BUF_BYTES;
   static constexpr int MAX_HALF_PAIRS = (2 * RB * (2 * RB + 1) / 2 + 1) / 2;   // 16 x 16 block pairs of one multiplying wave
   static_assert(2 * MAX_HALF_PAIRS * 4 * 64 * 4 <= LDS_BYTES, "the final reduction fits the buffers");
 };
@@ -264,7 +266,6 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
   // time the chip reads a few contiguous stretches of every row (here c counts the chunks of this workgroup).
   const long long n_chunks = (d + 63) / 64;
   const long long c_end = (n_chunks - blockIdx.x + gridDim.x - 1) / gridDim.x;
-  const int n = lane & 31, h = lane >> 5;
 
   // Both roles pass the same barriers: one after the first chunk is staged, one per chunk in the loop, two in the
   // final reduction.
@@ -273,7 +274,6 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
     const int t = wave;
     const bool active = t < RB && c_end > 0;
     const float* __restrict__ crow = CENTER ? G + (long long)(*center) * ldg : G;
-    unsigned char* st = lds + SG::STAGE_OFF + t * SG::TILE_BYTES;
     const int rsub = lane >> 4, kq = (lane & 15) << 2;
     // FULL: the caller knows that the chunk is complete (no branch on the way to the loads: the compiler counts
     // the loads in flight exactly only along straight-line code, and waits for all of them wherever paths with
@@ -300,23 +300,9 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
       const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int j = 0; j < 8; ++j) u[j] = (32 * t + 4 * j + rsub < m) ? (CENTER ? u[j] - cv : u[j]) : zero;
-      stage_tile<false>(u, st, lane);
-      // per 16-column step s, lane (n, h) reads row n, columns 16 s + 8 h .. + 7 and splits them.  In the operand
-      // fragment of the 16-row block 2 t + n / 16 and the 32-column step s / 2 these eight columns are the share of
-      // fragment lane 16 (2 (s % 2) + h) + n % 16 (row n % 16, columns 8 (lane / 16) .. + 7 of the step).
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const unsigned char* row = st + n * 256;
-        const f32x4 v0 = *reinterpret_cast<const f32x4*>(row + ((((4 * s + 2 * h) ^ n) & 15) << 4));
-        const f32x4 v1 = *reinterpret_cast<const f32x4*>(row + ((((4 * s + 2 * h + 1) ^ n) & 15) << 4));
-        bf16x8 fh, fm, fl;
-        split3(v0, v1, fh, fm, fl);
-        const int flane = 16 * (2 * (s & 1) + h) + (n & 15);
-        unsigned char* dst = lds + buf * SG::BUF_BYTES + (((2 * t + (n >> 4)) * 3) * 2 + (s >> 1)) * 1024 + flane * 16;
-        *reinterpret_cast<bf16x8*>(dst) = fh;
-        *reinterpret_cast<bf16x8*>(dst + 2 * 1024) = fm;
-        *reinterpret_cast<bf16x8*>(dst + 4 * 1024) = fl;
-      }
+      // row r of the tile at r x 256 bytes, its 16-byte column groups exclusive-or'ed with r (the staging tile of
+      // the layer kernel): the multiplying waves read it in operand order without bank conflicts
+      stage_tile<false>(u, lds + buf * SG::BUF_BYTES + t * SG::TILE_BYTES, lane);
     };
     // four register sets: chunk c sits in set c % 4 and is requested four chunks ahead (four staging waves per compute
     // unit, 8 KB per tile: 128 KB in flight, what it takes to keep the memory system busy at its loaded latency)
@@ -372,15 +358,20 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
   f32x4 acc[(PAIRS16 + 1) / 2];
 #pragma unroll
   for (int i = 0; i < (PAIRS16 + 1) / 2; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int frow = lane & 15;
+  const int fcol0 = (((8 * q + 2 * (lane >> 4)) ^ frow) & 15) << 4, fcol1 = (((8 * q + 2 * (lane >> 4) + 1) ^ frow) & 15) << 4;
   auto multiply = [&](auto half_c, int buf) __attribute__((always_inline)) {
     constexpr int HALF = decltype(half_c)::value;
+    // Operand fragment of the 16-row block g and this wave's 32-column step: lane l holds row l % 16, columns
+    // 8 (l / 16) .. + 7 of the step, i.e. two 16-byte groups of the staged row, which it splits into the three bf16
+    // pieces (the two waves of a column step both split every block: cheaper than passing pieces through LDS).
     bf16x8 fh[NBL], fm[NBL], fl[NBL];
 #pragma unroll
     for (int g = 0; g < NBL; ++g) {
-      const unsigned char* src = lds + buf * SG::BUF_BYTES + ((g * 3) * 2 + q) * 1024 + lane * 16;
-      fh[g] = *reinterpret_cast<const bf16x8*>(src);
-      fm[g] = *reinterpret_cast<const bf16x8*>(src + 2 * 1024);
-      fl[g] = *reinterpret_cast<const bf16x8*>(src + 4 * 1024);
+      const unsigned char* row = lds + buf * SG::BUF_BYTES + g * (16 * 256) + frow * 256;
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(row + fcol0);
+      const f32x4 v1 = *reinterpret_cast<const f32x4*>(row + fcol1);
+      split3(v0, v1, fh[g], fm[g], fl[g]);
     }
     // The six piece products of a block pair go to its accumulator in the same order as in krum_gram_kernel
     // (smallest first), but product kind by product kind over all pairs: consecutive matrix instructions then
