@@ -42,27 +42,37 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 // h = bf16(x), m = bf16(x - h), l = bf16(x - h - m), round to nearest even each time;
 // both subtractions are exact.
 __device__ inline void split3(const f32x4& v0, const f32x4& v1, bf16x8& h, bf16x8& m, bf16x8& l) {
-  // Two floats at a time: one packed conversion gives both bf16 pieces in one register, and the pieces' float values
-  // (needed for the exact remainders) are that register shifted and masked, not converted a second time.
+  // Two floats at a time: one packed conversion gives both bf16 pieces in one register, and the exact remainder of
+  // either float is one instruction, the bf16 dot product of that register with (-1, 0) or (0, -1) added to the
+  // float (v_dot2c_f32_bf16: the product with -1 is exact, the product with 0 vanishes, and the sum x - h is
+  // representable, so its single rounding changes nothing).  Seven instructions per two floats; taking the pieces'
+  // float values out of the packed register with a shift or a mask and subtracting took eleven.
   typedef float f32x2 __attribute__((ext_vector_type(2)));
   typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   const float x[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+  // The two constants go through registers: written as immediates, (-1, 0) is emitted as the inline constant -1.0,
+  // which this instruction does not read as the bf16 pair (-1, 0) (measured: the remainders then come out wrong).
+  unsigned first_bits = 0x0000bf80u, second_bits = 0xbf800000u;
+  asm("" : "+s"(first_bits), "+s"(second_bits));
+  const bf16x2 minus_first = __builtin_bit_cast(bf16x2, first_bits), minus_second = __builtin_bit_cast(bf16x2, second_bits);
   u32x4 hu, mu, lu;
   auto pack = [](float a, float b) {
     const f32x2 t = {a, b};
-    return __builtin_bit_cast(unsigned, __builtin_convertvector(t, bf16x2));
+    return __builtin_convertvector(t, bf16x2);
   };
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const float a = x[2 * i], b = x[2 * i + 1];
-    const unsigned hp = pack(a, b);
-    const float ra = a - __uint_as_float(hp << 16), rb = b - __uint_as_float(hp & 0xffff0000u);
-    const unsigned mp = pack(ra, rb);
-    const float sa = ra - __uint_as_float(mp << 16), sb = rb - __uint_as_float(mp & 0xffff0000u);
-    hu[i] = hp;
-    mu[i] = mp;
-    lu[i] = pack(sa, sb);
+    const bf16x2 hp = pack(a, b);
+    const float ra = __builtin_amdgcn_fdot2_f32_bf16(hp, minus_first, a, false);
+    const float rb = __builtin_amdgcn_fdot2_f32_bf16(hp, minus_second, b, false);
+    const bf16x2 mp = pack(ra, rb);
+    const float sa = __builtin_amdgcn_fdot2_f32_bf16(mp, minus_first, ra, false);
+    const float sb = __builtin_amdgcn_fdot2_f32_bf16(mp, minus_second, rb, false);
+    hu[i] = __builtin_bit_cast(unsigned, hp);
+    mu[i] = __builtin_bit_cast(unsigned, mp);
+    lu[i] = __builtin_bit_cast(unsigned, pack(sa, sb));
   }
   h = __builtin_bit_cast(bf16x8, hu);
   m = __builtin_bit_cast(bf16x8, mu);
@@ -232,13 +242,14 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : 2) void krum_gram_ke
 // their tile is staged (zeroing the rows beyond m right behind the load made every wave wait for the load it had
 // just requested), and the steady-state loop has no branch between requesting a tile and staging it four chunks
 // later (where paths with different numbers of loads meet, the compiler waits for all of them).
-// Measured (MI355X, d = 14.7 M): m = 72 / 96 / 100 / 128: 1.01 / 1.29 / 1.49 / 1.84 ms per Krum call.  Before, the
-// staging waves also brought their tile into operand order through a private tile and split it, and the multiplying
-// waves read finished pieces: 1.21 / 1.37 / 1.63 / 1.88 ms (1.28 / 1.43 / 1.65 / 1.97 ms with 32 x 32 blocks; with
-// krum_gram_kernel<3 or 4> 1.91 / 1.95 / 2.0 / 2.5 ms).  Timing variants of this kernel (wrong results, same
-// accesses): without the splitting instructions it runs at the memory's pace (1.16 / 1.17 / 1.37 ms for
-// m = 96 / 100 / 128, 5.0-5.6 TB/s); the vector instructions of the split add their issue time to the matrix
-// instructions' on the same SIMD, whichever wave they sit in, and here both waves of a column step split every block.
+// Measured (MI355X, d = 14.7 M): m = 72 / 96 / 100 / 128: 0.95 / 1.18 / 1.40 / 1.75 ms per Krum call (1.01 / 1.29 /
+// 1.49 / 1.84 ms with the eleven-instruction split).  Before, the staging waves also brought their tile into operand
+// order through a private tile and split it, and the multiplying waves read finished pieces: 1.21 / 1.37 / 1.63 /
+// 1.88 ms (1.28 / 1.43 / 1.65 / 1.97 ms with 32 x 32 blocks; with krum_gram_kernel<3 or 4> 1.91 / 1.95 / 2.0 / 2.5 ms).
+// Timing variants of this kernel (wrong results, same accesses): without the splitting instructions it runs at the
+// memory's pace (1.16 / 1.17 / 1.37 ms for m = 96 / 100 / 128, 5.0-5.6 TB/s); the vector instructions of the split
+// add their issue time to the matrix instructions' on the same SIMD, whichever wave they sit in, and here both waves
+// of a column step split every block.
 constexpr int kSharedWaves = 8;
 
 template <int RB>
