@@ -231,25 +231,29 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : 2) void krum_gram_ke
 //  * waves 4..7 multiply, in 16 x 16 blocks (v_mfma_f32_16x16x32_bf16): the m rows are NBL = ceil(m / 16) blocks of
 //    16 rows, and only the NBL (NBL + 1) / 2 block pairs a <= b are formed, so rows beyond m cost at most 15 rows of
 //    padding and the diagonal blocks waste a 16 x 16 triangle, not a 32 x 32 one (m = 100: 28 pairs x 8 cycles per
-//    16 columns and piece product against 10 x 32 with 32-row blocks).  Wave 4 + w takes the 32-column step w & 1 of
-//    the chunk and every second block pair (w >> 1): it reads the operand fragment of every block in operand order
-//    straight from the staged rows, splits it into the three bf16 pieces and issues the six piece products of each
-//    of its pairs.
-// The two multiplying waves of a pair set add their accumulators through LDS at the end (step 0 + step 1) and write
+//    16 columns and piece product against 10 x 32 with 32-row blocks).  A multiplying wave reads the operand fragment
+//    of every block in operand order straight from the staged rows, splits it into the three bf16 pieces and issues
+//    the six piece products of its block pairs.  Up to seven blocks (m <= 112) a wave holds all pairs: wave 4 + w
+//    takes the 32-column step w & 1 of every second chunk and spreads its products over two barrier intervals, so
+//    no block is split twice.  With eight blocks (36 pairs, 144 accumulator registers) that does not fit: there
+//    wave 4 + w takes the step w & 1 of every chunk and every second block pair (w >> 1), and both waves of a step
+//    split every block.
+// The multiplying waves add their accumulators through LDS at the end in a fixed order and write
 // the workgroup's partial Gram in the 32 x 32 block layout of krum_gram_kernel (16 x 16 quadrants that are not
 // formed, below the diagonal or beyond the last live block, are written as zeros).
 // Two things in the staging waves matter as much as the split of roles: the loaded values are first touched when
 // their tile is staged (zeroing the rows beyond m right behind the load made every wave wait for the load it had
 // just requested), and the steady-state loop has no branch between requesting a tile and staging it four chunks
 // later (where paths with different numbers of loads meet, the compiler waits for all of them).
-// Measured (MI355X, d = 14.7 M): m = 72 / 96 / 100 / 128: 0.95 / 1.18 / 1.40 / 1.75 ms per Krum call (1.01 / 1.29 /
-// 1.49 / 1.84 ms with the eleven-instruction split).  Before, the staging waves also brought their tile into operand
+// Measured (MI355X, d = 14.7 M): m = 72 / 96 / 100 / 112 / 128: 0.86 / 1.10 / 1.30 / 1.38 / 1.70-1.75 ms per Krum call
+// (m = 72: 5.1 TB/s).  With every block split by both waves of a column step also for m <= 112, same box:
+// 0.94 / 1.15 / 1.33 / 1.41 ms (over boxes 0.95 / 1.18 / 1.33-1.40); with the
+// eleven-instruction split 1.01 / 1.29 / 1.49 / 1.84 ms.  Before, the staging waves also brought their tile into operand
 // order through a private tile and split it, and the multiplying waves read finished pieces: 1.21 / 1.37 / 1.63 /
 // 1.88 ms (1.28 / 1.43 / 1.65 / 1.97 ms with 32 x 32 blocks; with krum_gram_kernel<3 or 4> 1.91 / 1.95 / 2.0 / 2.5 ms).
-// Timing variants of this kernel (wrong results, same accesses): without the splitting instructions it runs at the
-// memory's pace (1.16 / 1.17 / 1.37 ms for m = 96 / 100 / 128, 5.0-5.6 TB/s); the vector instructions of the split
-// add their issue time to the matrix instructions' on the same SIMD, whichever wave they sit in, and here both waves
-// of a column step split every block.
+// Timing variants (wrong results, same accesses) without the splitting instructions run at the memory's pace
+// (1.16 / 1.17 / 1.37 ms for m = 96 / 100 / 128): the vector instructions of the split add their issue time to the
+// matrix instructions' on the same SIMD, whichever wave they sit in.
 constexpr int kSharedWaves = 8;
 
 template <int RB>
@@ -278,8 +282,10 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
   const long long n_chunks = (d + 63) / 64;
   const long long c_end = (n_chunks - blockIdx.x + gridDim.x - 1) / gridDim.x;
 
-  // Both roles pass the same barriers: one after the first chunk is staged, one per chunk in the loop, two in the
-  // final reduction.
+  // Both roles pass the same barriers: one after the first chunk is staged, one per chunk in the loop, and those of
+  // the final reduction (five where four waves hold partial sums of every block pair, two where two do).
+  constexpr bool ALTERNATE = NBL <= 7;
+  constexpr int kFinalBarriers = ALTERNATE ? 5 : 2;
   if (wave < 4) {
     // ---- staging waves
     const int t = wave;
@@ -358,14 +364,112 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
         for (int k = 0; k < 4; ++k) __syncthreads();
     }
     for (; c < c_end; c += 4) quad(Any{}, c);
-    for (int i = 0; i < 2; ++i) __syncthreads();
+    for (int i = 0; i < kFinalBarriers; ++i) __syncthreads();
     return;
   }
 
   // ---- multiplying waves
+  constexpr int PAIRS16 = NBL * (NBL + 1) / 2;
+  if constexpr (ALTERNATE) {
+    // Up to seven live row blocks: all block pairs (at most 28 x 4 accumulator registers) and all fragments fit one
+    // wave, so no block is split twice.  Wave 4 + w takes the 32-column step w & 1 of every second chunk (w >> 1 its
+    // parity) and has two barrier intervals for it: in the chunk's own interval it reads and splits the fragments and
+    // issues the first two kinds of piece products, in the next one (from registers, while the other two waves read
+    // the next chunk) the remaining four kinds.  The split is the larger half of a multiplying wave's vector work, and
+    // vector and matrix instructions of a SIMD do not overlap here; the two intervals then cost about the same.
+    const int q = (wave - 4) & 1, parity = (wave - 4) >> 1;
+    f32x4 acc[PAIRS16];
+#pragma unroll
+    for (int i = 0; i < PAIRS16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int frow = lane & 15;
+    const int fcol0 = (((8 * q + 2 * (lane >> 4)) ^ frow) & 15) << 4, fcol1 = (((8 * q + 2 * (lane >> 4) + 1) ^ frow) & 15) << 4;
+    bf16x8 fh[NBL], fm[NBL], fl[NBL];
+    auto fetch = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+      for (int g = 0; g < NBL; ++g) {
+        const unsigned char* row = lds + buf * SG::BUF_BYTES + g * (16 * 256) + frow * 256;
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(row + fcol0);
+        const f32x4 v1 = *reinterpret_cast<const f32x4*>(row + fcol1);
+        split3(v0, v1, fh[g], fm[g], fl[g]);
+      }
+    };
+    // piece products of the kinds [first, last) over all block pairs, kind by kind (the order within a pair's
+    // accumulator is that of krum_gram_kernel, smallest first)
+    auto products = [&](auto first_c, auto last_c) __attribute__((always_inline)) {
+#pragma unroll
+      for (int kind = decltype(first_c)::value; kind < decltype(last_c)::value; ++kind) {
+        int p = 0;
+#pragma unroll
+        for (int a = 0; a < NBL; ++a)
+#pragma unroll
+          for (int b = a; b < NBL; ++b, ++p) {
+            const bf16x8 x = kind == 0 ? fl[a] : (kind == 2 || kind == 3) ? fm[a] : fh[a];
+            const bf16x8 y = kind == 1 ? fl[b] : (kind == 2 || kind == 4) ? fm[b] : fh[b];
+            acc[p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, acc[p], 0, 0, 0);
+          }
+      }
+    };
+    using K0 = std::integral_constant<int, 0>;
+    using K2 = std::integral_constant<int, 2>;
+    using K6 = std::integral_constant<int, 6>;
+    // Barriers: the one after the first staged chunk; then one per chunk c = 0 .. c_end - 1 at the end of its
+    // interval.  A wave of parity 1 sits out interval 0; every wave passes the barrier that ends its chunk's interval
+    // and, if that interval is not the last one, the barrier that ends the next.
+    __syncthreads();
+    if (parity == 1 && c_end > 0) __syncthreads();
+    for (long long c = parity; c < c_end; c += 2) {
+      fetch((int)(c & 1));
+      products(K0{}, K2{});
+      __syncthreads();
+      products(K2{}, K6{});
+      if (c + 1 < c_end) __syncthreads();
+    }
+    // the four partial sums are added through LDS in the fixed tree (0+2)+(1+3)
+    const int w = wave - 4;
+    float* red = reinterpret_cast<float*>(lds);
+    static_assert(2 * PAIRS16 * 4 * 64 * 4 <= SG::LDS_BYTES, "the final reduction fits the buffers");
+    __syncthreads();   // everybody is done with the buffers
+    for (int step = 2; step >= 1; step >>= 1) {
+      if (w >= step && w < 2 * step) {
+#pragma unroll
+        for (int p = 0; p < PAIRS16; ++p)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) red[(((w - step) * PAIRS16 + p) * 4 + j) * 64 + lane] = acc[p][j];
+      }
+      __syncthreads();
+      if (w < step) {
+#pragma unroll
+        for (int p = 0; p < PAIRS16; ++p)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[p][j] += red[((w * PAIRS16 + p) * 4 + j) * 64 + lane];
+      }
+      __syncthreads();
+    }
+    if (w != 0) return;
+    // accumulator element j of lane l: row 4 (l / 16) + j of block a, row l % 16 of block b; block pair (a, b) is the
+    // quadrant (a % 2, b % 2) of the 32 x 32 block pair (a / 2, b / 2); quadrants nobody forms are written as zeros
+    float* out = partial + (long long)blockIdx.x * SG::PAIRS * 1024;
+    const int oi = 4 * (lane >> 4), oj = lane & 15;
+    auto pair32 = [](int A, int B) { return A * RB - A * (A - 1) / 2 + (B - A); };
+#pragma unroll
+    for (int A = 0; A < RB; ++A)
+#pragma unroll
+      for (int B = A; B < RB; ++B)
+#pragma unroll
+        for (int qa = 0; qa < 2; ++qa)
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb) {
+            const int a = 2 * A + qa, b = 2 * B + qb;
+            const bool formed = a <= b && b < NBL;
+            const int p = formed ? a * NBL - a * (a - 1) / 2 + (b - a) : 0;
+            float* o = out + pair32(A, B) * 1024 + (qa * 16 + oi) * 32 + qb * 16 + oj;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j * 32] = formed ? acc[p][j] : 0.f;
+          }
+    return;
+  }
   const int q = (wave - 4) & 1;      // 32-column step of every chunk
   const int half = (wave - 4) >> 1;  // block pairs p with p % 2 == half
-  constexpr int PAIRS16 = NBL * (NBL + 1) / 2;
   f32x4 acc[(PAIRS16 + 1) / 2];
 #pragma unroll
   for (int i = 0; i < (PAIRS16 + 1) / 2; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
