@@ -235,9 +235,9 @@ __global__ __launch_bounds__(64 * kGramWaves, RB == 1 ? 3 : 2) void krum_gram_ke
 //    of every block in operand order straight from the staged rows, splits it into the three bf16 pieces and issues
 //    the six piece products of its block pairs.  Up to seven blocks (m <= 112) a wave holds all pairs: wave 4 + w
 //    takes the 32-column step w & 1 of every second chunk and spreads its products over two barrier intervals, so
-//    no block is split twice.  With eight blocks (36 pairs, 144 accumulator registers) that does not fit: there
-//    wave 4 + w takes the step w & 1 of every chunk and every second block pair (w >> 1), and both waves of a step
-//    split every block.
+//    no block is split twice.  With eight blocks (36 pairs, 144 accumulator registers; it compiles to 252 registers
+//    without spills) the same scheme measured no gain (m = 128: 1.69 -> 1.72 ms): there wave 4 + w takes the step
+//    w & 1 of every chunk and every second block pair (w >> 1), and both waves of a step split every block.
 // The multiplying waves add their accumulators through LDS at the end in a fixed order and write
 // the workgroup's partial Gram in the 32 x 32 block layout of krum_gram_kernel (16 x 16 quadrants that are not
 // formed, below the diagonal or beyond the last live block, are written as zeros).
@@ -371,8 +371,8 @@ __global__ __launch_bounds__(64 * kSharedWaves) void krum_gram_shared_kernel(con
   // ---- multiplying waves
   constexpr int PAIRS16 = NBL * (NBL + 1) / 2;
   if constexpr (ALTERNATE) {
-    // Up to seven live row blocks: all block pairs (at most 28 x 4 accumulator registers) and all fragments fit one
-    // wave, so no block is split twice.  Wave 4 + w takes the 32-column step w & 1 of every second chunk (w >> 1 its
+    // Up to seven live row blocks: a wave holds all block pairs (at most 28 x 4 accumulator registers) and all
+    // fragments, so no block is split twice.  Wave 4 + w takes the 32-column step w & 1 of every second chunk (w >> 1 its
     // parity) and has two barrier intervals for it: in the chunk's own interval it reads and splits the fragments and
     // issues the first two kinds of piece products, in the next one (from registers, while the other two waves read
     // the next chunk) the remaining four kinds.  The split is the larger half of a multiplying wave's vector work, and
